@@ -1,0 +1,127 @@
+/*
+ * tova.h -- C ABI of the TOVA bounded-KV-cache decode step for AMD MI355X (gfx950).
+ *
+ * The library implements the hot path of the TOVA policy ("Token Omission Via
+ * Attention", arXiv 2401.06104): a decoder layer seen as a bounded multi-state
+ * RNN whose state is a KV cache of at most k rows (Sec. 3.1-3.3).  One decode
+ * step of one (layer, sequence) unit
+ *   1. appends the incoming token's k_t, v_t to the multi-state and lets the
+ *      query q_t attend over all of it, Softmax(q K^T / sqrt(d)) V per head
+ *      (Sec. 3.2, Sec. 2.2) -- the output still sees the row dropped below;
+ *   2. if the multi-state now exceeds k rows, averages the attention weights
+ *      of q_t over the query heads of the layer, takes the argmin and drops
+ *      that row from K and V (Sec. 4; App. B, Alg. 1).  All heads of a layer
+ *      share the victim (the "layer" variant that App. A finds best).
+ * Rows live in k fixed slots: the victim's slot is overwritten in place by the
+ * new token (attention does not depend on row order); if the new token itself
+ * scores lowest it is not stored.  Ties go to the lowest candidate index, the
+ * new token having the highest (k).
+ *
+ * Conventions
+ *   - every function returns TOVA_OK (0) or a negative tova_status; nothing
+ *     throws, aborts or prints.  tova_strerror() describes a code; after
+ *     TOVA_EHIP it also carries the HIP runtime's message (thread-local).
+ *   - "DEVICE" pointers are HIP device memory on the current device, owned by
+ *     the caller, 256-byte aligned, and must outlive every use enqueued on the
+ *     stream.  "HOST" pointers are ordinary host memory.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default
+ *     stream).  Calls enqueue work and return; they never synchronise.
+ *   - one cache may be used from one host thread at a time.
+ *   - inputs must be finite; with NaN scores the victim is unspecified
+ *     (but always in range).
+ */
+#ifndef TOVA_H
+#define TOVA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TOVA_OK = 0,
+  TOVA_EINVAL = -1, /* null / misaligned pointer, non-positive size, H % H_kv != 0, bad dtype ... */
+  TOVA_ENOSUP = -2, /* valid problem, but a shape the kernels do not cover                       */
+  TOVA_EHIP = -3,   /* a HIP call (launch) failed                                                  */
+  TOVA_ENOMEM = -4  /* host allocation of the descriptor failed                                     */
+} tova_status;
+
+enum { TOVA_F32 = 0, TOVA_BF16 = 1 };
+
+typedef struct tova_cache tova_cache_t; /* opaque host-side descriptor */
+
+/* Problem statement, in the paper's terms (App. B: attn_heads, hidden_dim,
+ * cache_max_size; batch and layers are independent units). */
+typedef struct {
+  int32_t n_layers;     /* L                                                          */
+  int32_t batch;        /* B independent sequences                                     */
+  int32_t capacity_k;   /* k = cache_max_size, the multi-state size (Sec. 3.3)         */
+  int32_t n_q_heads;    /* H query heads                                               */
+  int32_t n_kv_heads;   /* H_kv, divides H; query head h reads KV head h / (H / H_kv)  */
+  int32_t head_dim;     /* d in {32, 64, 128}                                          */
+  int32_t dtype;        /* TOVA_F32 or TOVA_BF16: type of q, k, v, K, V and out        */
+  float softmax_scale;  /* <= 0 selects 1 / sqrt(d)                                    */
+  int32_t n_splits;     /* 0 = automatic; S >= 1 asks for S slot chunks per KV head    */
+} tova_config_t;
+
+/* Where things live inside the caller's buffers (byte offsets). */
+typedef struct {
+  size_t k_offset;          /* kv_mem:    K  [L][B][H_kv][k][d]                 */
+  size_t v_offset;          /* kv_mem:    V  [L][B][H_kv][k][d]                 */
+  size_t occupancy_offset;  /* state_mem: int32 [L][B]    rows in use, min(t,k) */
+  size_t slot_token_offset; /* state_mem: int32 [L][B][k] token index held by a slot, -1 = empty */
+  int32_t n_splits;         /* resolved split count S                            */
+  int32_t rows_per_split;   /* slots per chunk                                   */
+  int32_t block_threads;    /* workgroup size the step kernel is launched with   */
+  int32_t grid_blocks;      /* workgroups per step                               */
+  int32_t lds_bytes;        /* dynamic LDS per workgroup                         */
+} tova_layout_t;
+
+/* Sizes of the three caller-owned DEVICE buffers.  kv_bytes is exactly
+ * 2*L*B*H_kv*k*d*sizeof(elem) (the paper's cache-memory row, Sec. 7.1 table).
+ * HOST pointers; any of the three outputs may be NULL. */
+int tova_cache_bytes(const tova_config_t* cfg, size_t* kv_bytes, size_t* state_bytes,
+                     size_t* scratch_bytes);
+
+/* Offsets and launch plan for a configuration (host only, no GPU needed). */
+int tova_cache_layout(const tova_config_t* cfg, tova_layout_t* layout);
+
+/* Creates a descriptor over caller-owned DEVICE buffers of at least the sizes
+ * tova_cache_bytes reports and enqueues a kernel that empties the cache
+ * (occupancy 0, slot_token -1, scratch counters 0).  K/V contents are not
+ * touched: empty slots are never read. */
+int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, void* state_mem,
+                    void* scratch_mem, void* hip_stream);
+
+/* One decode step for every (layer, sequence) unit (Sec. 3.2 + Sec. 4).
+ *   q      DEVICE [L][B][H][d]      queries of the incoming tokens
+ *   k_new  DEVICE [L][B][H_kv][d]   their keys   (post positional encoding)
+ *   v_new  DEVICE [L][B][H_kv][d]   their values
+ *   out    DEVICE [L][B][H][d]      attention outputs over cached rows + the new row
+ *   evicted DEVICE int32 [L][B] or NULL: -1 while the cache is filling,
+ *          0..k-1 = slot whose row was dropped and now holds the new token,
+ *          k = the new token itself was dropped.
+ * Below capacity the new row goes to slot `occupancy` (App. B: no-op branch). */
+int tova_decode_step(tova_cache_t* cache, const void* q, const void* k_new, const void* v_new,
+                     void* out, int32_t* evicted, void* hip_stream);
+
+/* n_steps consecutive decode steps with inputs resident in device memory:
+ * the arrays of tova_decode_step with a leading [n_steps] dimension
+ * (evicted: [n_steps][L][B], may be NULL).  Equivalent to n_steps calls. */
+int tova_decode_steps(tova_cache_t* cache, int32_t n_steps, const void* q, const void* k_new,
+                      const void* v_new, void* out, int32_t* evicted, void* hip_stream);
+
+/* Number of tokens the cache has seen since tova_cache_init (HOST out pointer). */
+int tova_cache_tokens_seen(const tova_cache_t* cache, int64_t* t);
+
+/* Frees the host descriptor only; device buffers stay with the caller. */
+int tova_cache_destroy(tova_cache_t* cache);
+
+const char* tova_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOVA_H */

@@ -64,14 +64,15 @@ class TovaOracle:
         n = self.n
         out = np.empty((self.H, self.d), dtype=np.float64)
         p = np.empty((self.H, n + 1), dtype=np.float64)
-        for h in range(self.H):
-            g = h // self.G                                       # KV head serving query head h
+        for g in range(self.H_kv):
+            # the multi-state of KV head g with the incoming row appended
             Kc = np.concatenate([self.K[g, :n], k_new[g][None, :]], axis=0)   # [n+1, d]
             Vc = np.concatenate([self.V[g, :n], v_new[g][None, :]], axis=0)
-            l = self.scale * (Kc @ q[h])                          # logits over the n+1 candidates
-            w = np.exp(l - np.max(l))
-            p[h] = w / np.sum(w)                                  # softmax
-            out[h] = p[h] @ Vc
+            for h in range(g * self.G, (g + 1) * self.G):             # query heads it serves: h // G == g
+                l = self.scale * (Kc @ q[h])                          # logits over the n+1 candidates
+                w = np.exp(l - np.max(l))
+                p[h] = w / np.sum(w)                                  # softmax
+                out[h] = p[h] @ Vc
         return out, p
 
     # -- step 3a: head-averaged score of the last (only) query -----------------

@@ -1,0 +1,212 @@
+"""ctypes binding of include/tova.h: argument marshalling only.
+
+Function names follow the C ABI (tova_cache_bytes, tova_cache_layout, and the
+TovaCache methods init / decode_step / decode_steps / destroy map one-to-one to
+tova_cache_init / tova_decode_step / tova_decode_steps / tova_cache_destroy).
+There is no fallback: if libtova.so is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, byref, c_char_p, c_float, c_int, c_int32, c_int64, c_size_t, c_void_p
+from typing import Optional
+
+TOVA_OK, TOVA_EINVAL, TOVA_ENOSUP, TOVA_EHIP, TOVA_ENOMEM = 0, -1, -2, -3, -4
+TOVA_F32, TOVA_BF16 = 0, 1
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+_LIB: Optional[ctypes.CDLL] = None
+
+
+class TovaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {tova_strerror(status)} (status {status})")
+
+
+class TovaConfig(ctypes.Structure):
+    _fields_ = [("n_layers", c_int32), ("batch", c_int32), ("capacity_k", c_int32),
+                ("n_q_heads", c_int32), ("n_kv_heads", c_int32), ("head_dim", c_int32),
+                ("dtype", c_int32), ("softmax_scale", c_float), ("n_splits", c_int32)]
+
+
+class TovaLayout(ctypes.Structure):
+    _fields_ = [("k_offset", c_size_t), ("v_offset", c_size_t), ("occupancy_offset", c_size_t),
+                ("slot_token_offset", c_size_t), ("n_splits", c_int32), ("rows_per_split", c_int32),
+                ("block_threads", c_int32), ("grid_blocks", c_int32), ("lds_bytes", c_int32)]
+
+
+def library_path() -> str:
+    return os.path.join(_PKG_DIR, "libtova.so")
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the in-tree libtova.so.  Raises if it has not been built."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} not found: build it with `python -m paper_2401_06104_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = ctypes.CDLL(path)
+    cfgp = POINTER(TovaConfig)
+    lib.tova_cache_bytes.argtypes = [cfgp, POINTER(c_size_t), POINTER(c_size_t), POINTER(c_size_t)]
+    lib.tova_cache_layout.argtypes = [cfgp, POINTER(TovaLayout)]
+    lib.tova_cache_init.argtypes = [POINTER(c_void_p), cfgp, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.tova_decode_step.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.tova_decode_steps.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+                                      c_void_p, c_void_p]
+    lib.tova_cache_tokens_seen.argtypes = [c_void_p, POINTER(c_int64)]
+    lib.tova_cache_destroy.argtypes = [c_void_p]
+    lib.tova_strerror.argtypes = [c_int]
+    lib.tova_strerror.restype = c_char_p
+    for name in ("tova_cache_bytes", "tova_cache_layout", "tova_cache_init", "tova_decode_step",
+                 "tova_decode_steps", "tova_cache_tokens_seen", "tova_cache_destroy"):
+        getattr(lib, name).restype = c_int
+    _LIB = lib
+    return lib
+
+
+def tova_strerror(status: int) -> str:
+    return load_library().tova_strerror(int(status)).decode()
+
+
+def tova_cache_bytes(cfg: TovaConfig):
+    """(kv_bytes, state_bytes, scratch_bytes) of the caller-owned device buffers."""
+    kv, st, sc = c_size_t(), c_size_t(), c_size_t()
+    rc = load_library().tova_cache_bytes(byref(cfg), byref(kv), byref(st), byref(sc))
+    if rc != TOVA_OK:
+        raise TovaError(rc, "tova_cache_bytes")
+    return kv.value, st.value, sc.value
+
+
+def tova_cache_layout(cfg: TovaConfig) -> TovaLayout:
+    lay = TovaLayout()
+    rc = load_library().tova_cache_layout(byref(cfg), byref(lay))
+    if rc != TOVA_OK:
+        raise TovaError(rc, "tova_cache_layout")
+    return lay
+
+
+def _stream_handle(stream) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+class TovaCache:
+    """Owns the three device buffers (torch tensors) and the library's descriptor."""
+
+    def __init__(self, n_layers: int, batch: int, capacity_k: int, n_q_heads: int, n_kv_heads: int,
+                 head_dim: int, dtype="bf16", softmax_scale: float = 0.0, n_splits: int = 0,
+                 device="cuda:0", stream=None):
+        import torch
+        self._torch = torch
+        self.lib = load_library()
+        code = {"f32": TOVA_F32, "fp32": TOVA_F32, "float32": TOVA_F32, torch.float32: TOVA_F32,
+                "bf16": TOVA_BF16, "bfloat16": TOVA_BF16, torch.bfloat16: TOVA_BF16}[dtype]
+        self.cfg = TovaConfig(n_layers, batch, capacity_k, n_q_heads, n_kv_heads, head_dim, code,
+                              float(softmax_scale), int(n_splits))
+        self.torch_dtype = torch.float32 if code == TOVA_F32 else torch.bfloat16
+        self.device = torch.device(device)
+        self.layout = tova_cache_layout(self.cfg)
+        kvb, stb, scb = tova_cache_bytes(self.cfg)
+        self.kv_mem = torch.empty(kvb, dtype=torch.uint8, device=self.device)
+        self.state_mem = torch.empty(stb, dtype=torch.uint8, device=self.device)
+        self.scratch_mem = torch.empty(scb, dtype=torch.uint8, device=self.device)
+        self._h = c_void_p()
+        with torch.cuda.device(self.device):
+            rc = self.lib.tova_cache_init(byref(self._h), byref(self.cfg), self.kv_mem.data_ptr(),
+                                          self.state_mem.data_ptr(), self.scratch_mem.data_ptr(),
+                                          _stream_handle(stream))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_cache_init")
+
+    # ---- views into the caller-owned buffers (no copies) -----------------
+    def _shape_kv(self):
+        c = self.cfg
+        return (c.n_layers, c.batch, c.n_kv_heads, c.capacity_k, c.head_dim)
+
+    @property
+    def K(self):
+        n = self.kv_mem.numel() // 2
+        return self.kv_mem[self.layout.k_offset:self.layout.k_offset + n].view(self.torch_dtype).view(self._shape_kv())
+
+    @property
+    def V(self):
+        n = self.kv_mem.numel() // 2
+        return self.kv_mem[self.layout.v_offset:self.layout.v_offset + n].view(self.torch_dtype).view(self._shape_kv())
+
+    @property
+    def occupancy(self):
+        c = self.cfg
+        o = self.layout.occupancy_offset
+        return self.state_mem[o:o + 4 * c.n_layers * c.batch].view(self._torch.int32).view(c.n_layers, c.batch)
+
+    @property
+    def slot_token(self):
+        c = self.cfg
+        o = self.layout.slot_token_offset
+        n = c.n_layers * c.batch * c.capacity_k
+        return self.state_mem[o:o + 4 * n].view(self._torch.int32).view(c.n_layers, c.batch, c.capacity_k)
+
+    @property
+    def tokens_seen(self) -> int:
+        t = c_int64()
+        rc = self.lib.tova_cache_tokens_seen(self._h, byref(t))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_cache_tokens_seen")
+        return t.value
+
+    # ---- the calls ----------------------------------------------------------
+    def _check(self, name, x, shape):
+        if x.dtype != self.torch_dtype or x.device != self.kv_mem.device or not x.is_contiguous() \
+                or tuple(x.shape) != tuple(shape):
+            raise ValueError(f"{name}: expected contiguous {self.torch_dtype} {tuple(shape)} on "
+                             f"{self.kv_mem.device}, got {x.dtype} {tuple(x.shape)} on {x.device}")
+
+    def decode_step(self, q, k_new, v_new, out, evicted=None, stream=None):
+        c = self.cfg
+        self._check("q", q, (c.n_layers, c.batch, c.n_q_heads, c.head_dim))
+        self._check("k_new", k_new, (c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        self._check("v_new", v_new, (c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        self._check("out", out, (c.n_layers, c.batch, c.n_q_heads, c.head_dim))
+        ev = self._evicted_ptr(evicted, (c.n_layers, c.batch))
+        rc = self.lib.tova_decode_step(self._h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
+                                       out.data_ptr(), ev, _stream_handle(stream))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_decode_step")
+
+    def decode_steps(self, q, k_new, v_new, out, evicted=None, stream=None):
+        c = self.cfg
+        T = q.shape[0]
+        self._check("q", q, (T, c.n_layers, c.batch, c.n_q_heads, c.head_dim))
+        self._check("k_new", k_new, (T, c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        self._check("v_new", v_new, (T, c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        self._check("out", out, (T, c.n_layers, c.batch, c.n_q_heads, c.head_dim))
+        ev = self._evicted_ptr(evicted, (T, c.n_layers, c.batch))
+        rc = self.lib.tova_decode_steps(self._h, T, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
+                                        out.data_ptr(), ev, _stream_handle(stream))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_decode_steps")
+
+    def _evicted_ptr(self, evicted, shape):
+        if evicted is None:
+            return None
+        if evicted.dtype != self._torch.int32 or not evicted.is_contiguous() \
+                or tuple(evicted.shape) != tuple(shape) or evicted.device != self.kv_mem.device:
+            raise ValueError(f"evicted: expected contiguous int32 {tuple(shape)} on {self.kv_mem.device}")
+        return evicted.data_ptr()
+
+    def destroy(self):
+        if self._h:
+            self.lib.tova_cache_destroy(self._h)
+            self._h = c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

@@ -1,0 +1,269 @@
+// Host side of the C ABI declared in include/tova.h: argument validation, buffer layout,
+// launch planning and the per-step launch loop.  No device code lives here.
+#include <hip/hip_runtime_api.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "tova.h"
+#include "tova_internal.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int kTargetBlocks = 512;     // two workgroups per CU on 256 CUs
+constexpr int kMinRowsPerSplit = 32;   // below this a chunk is all launch overhead
+constexpr int kSmallFloats = 512;      // must match the kernel's fixed LDS area
+constexpr int kMaxLdsBytes = 64 * 1024;
+
+thread_local char g_hip_msg[256] = {0};
+
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Resolved {
+  int L, B, k, H, H_kv, G, D, esize, bf16;
+  int units, pairs, S, R, kp, NT, grid, lds;
+  float scale;
+  size_t kv_bytes, state_bytes, scratch_bytes;
+  size_t v_off;                                   // in kv_mem
+  size_t occ_off, slot_off;                       // in state_mem
+  size_t cnt_pair_off, cnt_unit_off, cnt_bytes;   // in scratch_mem
+  size_t sg_off, escr_off, stats_off, accp_off;
+};
+
+int resolve(const tova_config_t* c, Resolved* r) {
+  if (!c || !r) return TOVA_EINVAL;
+  if (c->n_layers <= 0 || c->batch <= 0 || c->capacity_k <= 0 || c->n_q_heads <= 0 ||
+      c->n_kv_heads <= 0 || c->head_dim <= 0 || c->n_splits < 0)
+    return TOVA_EINVAL;
+  if (c->n_q_heads % c->n_kv_heads != 0) return TOVA_EINVAL;
+  if (c->dtype != TOVA_F32 && c->dtype != TOVA_BF16) return TOVA_EINVAL;
+  if (!(c->softmax_scale == c->softmax_scale)) return TOVA_EINVAL;  // NaN
+  const int G = c->n_q_heads / c->n_kv_heads;
+  if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return TOVA_ENOSUP;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return TOVA_ENOSUP;
+  // index ranges the kernel keeps in 32 bits
+  const long long units = (long long)c->n_layers * c->batch;
+  const long long pairs = units * c->n_kv_heads;
+  if (pairs > (1LL << 28) || c->capacity_k > (1 << 24) || units * c->n_q_heads > (1LL << 30))
+    return TOVA_ENOSUP;
+
+  r->L = c->n_layers; r->B = c->batch; r->k = c->capacity_k; r->H = c->n_q_heads;
+  r->H_kv = c->n_kv_heads; r->G = G; r->D = c->head_dim;
+  r->bf16 = (c->dtype == TOVA_BF16); r->esize = r->bf16 ? 2 : 4;
+  r->units = (int)units; r->pairs = (int)pairs;
+  r->scale = c->softmax_scale > 0.f ? c->softmax_scale : (float)(1.0 / std::sqrt((double)r->D));
+
+  // ---- split count: enough workgroups to fill 256 CUs, chunks that fit LDS ----
+  const int k = r->k;
+  int S = c->n_splits;
+  if (S <= 0) {
+    S = (r->pairs >= kTargetBlocks) ? 1 : (kTargetBlocks + r->pairs - 1) / r->pairs;
+    int smax = k / kMinRowsPerSplit;
+    if (smax < 1) smax = 1;
+    if (S > smax) S = smax;
+  }
+  const int big_cap = kMaxLdsBytes / 4 - kSmallFloats;  // floats available for the big LDS area
+  const int r_cap = big_cap / G - 1;                    // logits of R slots + the new token
+  const int s_lds = (k + r_cap - 1) / r_cap;
+  if (S < s_lds) S = s_lds;
+  if (S > k) S = k;
+  int R = (k + S - 1) / S;
+  S = (k + R - 1) / R;
+  r->S = S; r->R = R;
+  r->kp = (int)round_up((size_t)k + 1, 64);
+
+  int NT = (R >= 256) ? 512 : 256;
+  if (const char* e = std::getenv("TOVA_BLOCK_THREADS")) {  // tuning aid: 64..512, multiple of 64
+    int v = std::atoi(e);
+    if (v >= 64 && v <= 512 && v % 64 == 0) NT = v;
+  }
+  r->NT = NT;
+  long long big = (long long)(R + 1) * G;
+  const long long red = (long long)(NT / 64) * G * r->D;
+  if (red > big) big = red;
+  if ((long long)S * G + G > big) big = (long long)S * G + G;
+  if (big > big_cap) return TOVA_ENOSUP;
+  r->lds = (int)((kSmallFloats + big) * 4);
+  r->grid = (r->pairs + 7) / 8 * 8 * S;
+
+  // ---- caller-owned buffers ----
+  const size_t kv_one = (size_t)r->pairs * k * r->D * r->esize;
+  r->v_off = kv_one;
+  r->kv_bytes = 2 * kv_one;
+  r->occ_off = 0;
+  r->slot_off = round_up((size_t)r->units * 4, kAlign);
+  r->state_bytes = r->slot_off + round_up((size_t)r->units * k * 4, kAlign);
+
+  size_t off = 0;
+  r->cnt_pair_off = off; off += round_up((size_t)r->pairs * 4, kAlign);
+  r->cnt_unit_off = off; off += round_up((size_t)r->units * 4, kAlign);
+  r->cnt_bytes = off;
+  r->sg_off = off; off += round_up((size_t)r->pairs * r->kp * 4, kAlign);
+  r->escr_off = r->stats_off = r->accp_off = off;
+  if (S > 1) {
+    r->escr_off = off; off += round_up((size_t)r->pairs * r->kp * G * 4, kAlign);
+    r->stats_off = off; off += round_up((size_t)r->pairs * S * G * 2 * 4, kAlign);
+    r->accp_off = off; off += round_up((size_t)r->pairs * S * G * r->D * 4, kAlign);
+  }
+  r->scratch_bytes = off;
+  return TOVA_OK;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+  std::snprintf(g_hip_msg, sizeof g_hip_msg, "%s: %s", what, hipGetErrorString(e));
+  return TOVA_EHIP;
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+}  // namespace
+
+struct tova_cache {
+  Resolved r;
+  char* kv;
+  char* state;
+  char* scratch;
+  int64_t t;  // tokens seen
+};
+
+extern "C" {
+
+int tova_cache_bytes(const tova_config_t* cfg, size_t* kv_bytes, size_t* state_bytes,
+                     size_t* scratch_bytes) {
+  Resolved r;
+  int rc = resolve(cfg, &r);
+  if (rc != TOVA_OK) return rc;
+  if (kv_bytes) *kv_bytes = r.kv_bytes;
+  if (state_bytes) *state_bytes = r.state_bytes;
+  if (scratch_bytes) *scratch_bytes = r.scratch_bytes;
+  return TOVA_OK;
+}
+
+int tova_cache_layout(const tova_config_t* cfg, tova_layout_t* layout) {
+  if (!layout) return TOVA_EINVAL;
+  Resolved r;
+  int rc = resolve(cfg, &r);
+  if (rc != TOVA_OK) return rc;
+  layout->k_offset = 0;
+  layout->v_offset = r.v_off;
+  layout->occupancy_offset = r.occ_off;
+  layout->slot_token_offset = r.slot_off;
+  layout->n_splits = r.S;
+  layout->rows_per_split = r.R;
+  layout->block_threads = r.NT;
+  layout->grid_blocks = r.grid;
+  layout->lds_bytes = r.lds;
+  return TOVA_OK;
+}
+
+int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, void* state_mem,
+                    void* scratch_mem, void* hip_stream) {
+  if (!out) return TOVA_EINVAL;
+  *out = nullptr;
+  Resolved r;
+  int rc = resolve(cfg, &r);
+  if (rc != TOVA_OK) return rc;
+  if (!kv_mem || !state_mem || !scratch_mem) return TOVA_EINVAL;
+  if (!aligned(kv_mem, kAlign) || !aligned(state_mem, kAlign) || !aligned(scratch_mem, kAlign))
+    return TOVA_EINVAL;
+  tova_cache* c = new (std::nothrow) tova_cache;
+  if (!c) return TOVA_ENOMEM;
+  c->r = r;
+  c->kv = static_cast<char*>(kv_mem);
+  c->state = static_cast<char*>(state_mem);
+  c->scratch = static_cast<char*>(scratch_mem);
+  c->t = 0;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  // fill kernels, not memsets, so that the call can be recorded into a HIP graph
+  hipError_t e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->state + r.occ_off), 0,
+                                       (size_t)r.units, s);
+  if (e == hipSuccess)
+    e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->state + r.slot_off), -1,
+                              (size_t)r.units * r.k, s);
+  if (e == hipSuccess)
+    e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->scratch), 0, r.cnt_bytes / 4, s);
+  if (e != hipSuccess) {
+    delete c;
+    return hip_fail(e, "tova_cache_init");
+  }
+  *out = c;
+  return TOVA_OK;
+}
+
+int tova_decode_steps(tova_cache_t* c, int32_t n_steps, const void* q, const void* k_new,
+                      const void* v_new, void* out, int32_t* evicted, void* hip_stream) {
+  if (!c || n_steps < 0) return TOVA_EINVAL;
+  if (n_steps == 0) return TOVA_OK;
+  if (!q || !k_new || !v_new || !out) return TOVA_EINVAL;
+  if (!aligned(q, 16) || !aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(out, 16) ||
+      !aligned(evicted, 4))
+    return TOVA_EINVAL;
+  const Resolved& r = c->r;
+  if (c->t + n_steps > 0x7fffffffLL) return TOVA_ENOSUP;  // token index is kept in 32 bits
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  const size_t q_step = (size_t)r.units * r.H * r.D * r.esize;
+  const size_t kv_step = (size_t)r.pairs * r.D * r.esize;
+  tova::StepParams p;
+  p.K = c->kv;
+  p.V = c->kv + r.v_off;
+  p.occupancy = reinterpret_cast<int32_t*>(c->state + r.occ_off);
+  p.slot_token = reinterpret_cast<int32_t*>(c->state + r.slot_off);
+  p.cnt_pair = reinterpret_cast<int32_t*>(c->scratch + r.cnt_pair_off);
+  p.cnt_unit = reinterpret_cast<int32_t*>(c->scratch + r.cnt_unit_off);
+  p.sg = reinterpret_cast<float*>(c->scratch + r.sg_off);
+  p.escr = reinterpret_cast<float*>(c->scratch + r.escr_off);
+  p.stats = reinterpret_cast<float*>(c->scratch + r.stats_off);
+  p.accp = reinterpret_cast<float*>(c->scratch + r.accp_off);
+  p.pairs = r.pairs; p.H = r.H; p.H_kv = r.H_kv; p.k = r.k;
+  p.S = r.S; p.R = r.R; p.kp = r.kp; p.scale = r.scale;
+  const tova::LaunchPlan lp{r.grid, r.NT, r.lds};
+
+  for (int32_t i = 0; i < n_steps; ++i) {
+    p.q = static_cast<const char*>(q) + (size_t)i * q_step;
+    p.k_new = static_cast<const char*>(k_new) + (size_t)i * kv_step;
+    p.v_new = static_cast<const char*>(v_new) + (size_t)i * kv_step;
+    p.out = static_cast<char*>(out) + (size_t)i * q_step;
+    p.evicted = evicted ? evicted + (size_t)i * r.units : nullptr;
+    p.n = (int32_t)(c->t < r.k ? c->t : r.k);
+    p.t = (int32_t)c->t;
+    hipError_t e = tova::launch_step(r.bf16, r.D, r.G, p, lp, s);
+    if (e != hipSuccess) return hip_fail(e, "tova_decode_step launch");
+    c->t += 1;
+  }
+  return TOVA_OK;
+}
+
+int tova_decode_step(tova_cache_t* c, const void* q, const void* k_new, const void* v_new, void* out,
+                     int32_t* evicted, void* hip_stream) {
+  return tova_decode_steps(c, 1, q, k_new, v_new, out, evicted, hip_stream);
+}
+
+int tova_cache_tokens_seen(const tova_cache_t* c, int64_t* t) {
+  if (!c || !t) return TOVA_EINVAL;
+  *t = c->t;
+  return TOVA_OK;
+}
+
+int tova_cache_destroy(tova_cache_t* c) {
+  if (!c) return TOVA_EINVAL;
+  delete c;
+  return TOVA_OK;
+}
+
+const char* tova_strerror(int status) {
+  switch (status) {
+    case TOVA_OK: return "ok";
+    case TOVA_EINVAL: return "invalid argument";
+    case TOVA_ENOSUP: return "shape not supported by the gfx950 kernels";
+    case TOVA_EHIP: return g_hip_msg[0] ? g_hip_msg : "HIP runtime error";
+    case TOVA_ENOMEM: return "out of host memory";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,48 @@
+// Shared between the host API (tova_api.cpp) and the device code (tova_kernels.hip).
+#ifndef TOVA_INTERNAL_H
+#define TOVA_INTERNAL_H
+
+#include <hip/hip_runtime_api.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace tova {
+
+constexpr int kUnroll = 4;  // 16-byte loads in flight per lane in the K and V streams
+
+// Arguments of one step launch (one token for every unit).
+struct StepParams {
+  const void* q;       // [units][H][d]
+  const void* k_new;   // [units][H_kv][d]
+  const void* v_new;   // [units][H_kv][d]
+  void* out;           // [units][H][d]
+  int32_t* evicted;    // [units] or null
+  void* K;             // [units][H_kv][k][d]
+  void* V;
+  int32_t* occupancy;  // [units]
+  int32_t* slot_token; // [units][k]
+  float* sg;           // [pairs][kp]        per-KV-head partial of the score vector
+  float* escr;         // [pairs][kp][G]     chunk-local exp values   (S > 1 only)
+  float* stats;        // [pairs][S][G][2]   chunk-local (max, sum)   (S > 1 only)
+  float* accp;         // [pairs][S][G][d]   chunk-local PV partials  (S > 1 only)
+  int32_t* cnt_pair;   // [pairs] arrival counters, zero between launches
+  int32_t* cnt_unit;   // [units]
+  int32_t pairs;       // units * H_kv
+  int32_t H, H_kv, k;
+  int32_t n;           // rows cached before this step, min(t, k)
+  int32_t S, R;        // chunks per KV head, slots per chunk
+  int32_t kp;          // k + 1 rounded up to 64: stride of sg / escr
+  int32_t t;           // index of the incoming token
+  float scale;
+};
+
+struct LaunchPlan {
+  int32_t grid, block, lds_bytes;
+};
+
+hipError_t launch_step(int dtype_is_bf16, int D, int G, const StepParams& p, const LaunchPlan& lp,
+                       hipStream_t stream);
+hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_t stream);
+
+}  // namespace tova
+#endif

@@ -1,0 +1,554 @@
+// TOVA bounded-KV-cache decode step for gfx950 (MI355X): device code and launchers.
+//
+// One kernel launch advances every (layer, sequence) unit by one token
+// (Sec. 3.2: append the new row, attend; Sec. 4 / App. B Alg. 1: average the
+// attention weights over heads, argmin, drop that row).
+//
+// Work decomposition.  A workgroup owns one (unit, KV head, slot chunk): it
+// streams its chunk of K once and its chunk of V once, 16 bytes per lane,
+// rows laid across LPR = d / (16 / sizeof(elem)) adjacent lanes so that every
+// wave-level load covers whole, contiguous rows.  The G = H / H_kv query
+// heads that share the KV head are all served from the same streamed row
+// (grouped-query attention reads K/V once, not G times).
+//
+//   phase 1  logits   l[i][g] = scale * q_g . K[i]      -> LDS
+//   phase 2  softmax  m_g, e[i][g] = exp(l - m_g), Z_g  (chunk-local)
+//   phase 3  PV       acc_g = sum_i e[i][g] * V[i]
+//   phase 4  combine  (a) per (unit, KV head): merge the chunks' (m, Z, acc)
+//                         -> out; head-group partial of the score vector
+//                     (b) per unit: sum the partials over KV heads in fixed
+//                         order, argmin with lowest-index tie break, overwrite
+//                         the victim's slot with the new row, log `evicted`.
+//            Both levels use the "last workgroup to arrive does the merge"
+//            pattern: results are written to scratch, made visible with an
+//            agent-scope fence, and an atomic counter elects the finisher.
+//            Nothing ever waits on another workgroup, so every wave reaches
+//            its exit whatever the scheduling order.
+//
+// The score needs every head's *global* softmax normaliser, so when the slots
+// of a KV head are split over several workgroups the chunk-local e values go
+// to scratch (fp32, G per candidate) and are rescaled by the finisher.
+// With a single chunk (S == 1) they never leave LDS.
+//
+// The path is bound by HBM bandwidth (2*k*d*sizeof(elem) bytes per KV head
+// and step against 4*G*k*d flops): no matrix cores are used.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tova_internal.h"
+
+namespace tova {
+namespace {
+
+// ---------------------------------------------------------------- elements
+struct alignas(16) V16 {
+  uint32_t w[4];
+};
+
+struct bf16_t {
+  uint16_t x;
+};
+
+template <typename T>
+struct Elem;
+
+template <>
+struct Elem<float> {
+  static constexpr int VEC = 4;
+  static __device__ __forceinline__ void unpack(const V16& p, float (&f)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(p.w[i]);
+  }
+  static __device__ __forceinline__ float round_trip(float v) { return v; }
+  static __device__ __forceinline__ void store(float* dst, float v) { *dst = v; }
+};
+
+template <>
+struct Elem<bf16_t> {
+  static constexpr int VEC = 8;
+  static __device__ __forceinline__ void unpack(const V16& p, float (&f)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(p.w[i] << 16);
+      f[2 * i + 1] = __uint_as_float(p.w[i] & 0xffff0000u);
+    }
+  }
+  // round to nearest even, NaN kept quiet
+  static __device__ __forceinline__ void store(bf16_t* dst, float v) {
+    uint32_t u = __float_as_uint(v);
+    uint16_t r;
+    if ((u & 0x7fffffffu) > 0x7f800000u) {
+      r = 0x7fc0;
+    } else {
+      u += 0x7fffu + ((u >> 16) & 1u);
+      r = (uint16_t)(u >> 16);
+    }
+    dst->x = r;
+  }
+};
+
+// ------------------------------------------------------- cross-lane helpers
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over each group of LPR adjacent lanes; every lane of the group gets the total.
+// quad_perm[1,0,3,2], quad_perm[2,3,0,1], row_half_mirror, row_mirror, then LDS-crossbar
+// shuffles for groups wider than a DPP row of 16.
+template <int LPR>
+__device__ __forceinline__ float group_sum(float x) {
+  if (LPR >= 2) x += dpp_mov<0xB1>(x);
+  if (LPR >= 4) x += dpp_mov<0x4E>(x);
+  if (LPR >= 8) x += dpp_mov<0x141>(x);
+  if (LPR >= 16) x += dpp_mov<0x140>(x);
+  if (LPR >= 32) x += __shfl_xor(x, 16);
+  if (LPR >= 64) x += __shfl_xor(x, 32);
+  return x;
+}
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+  return x;
+}
+
+// Small fixed LDS area in front of the big dynamic one (floats).
+constexpr int kSmallFloats = 512;
+constexpr int kMaxWaves = 16;
+
+// Block-wide max / sum of G per-thread values.  `red` holds kMaxWaves * G floats.
+// Waves are combined in wave order, so the result does not depend on timing.
+template <int G, bool IS_MAX>
+__device__ __forceinline__ void block_reduce(float (&v)[G], float* red, int lane, int wave, int nw) {
+#pragma unroll
+  for (int g = 0; g < G; ++g) v[g] = IS_MAX ? wave_max(v[g]) : wave_sum(v[g]);
+  __syncthreads();  // previous users of `red` are done
+  if (lane == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) red[wave * G + g] = v[g];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float a = red[g];
+    for (int w = 1; w < nw; ++w) a = IS_MAX ? fmaxf(a, red[w * G + g]) : a + red[w * G + g];
+    v[g] = a;
+  }
+}
+
+// Elects the last of `expected` arrivals on `counter`.  All threads of the block call it
+// after writing their results; it returns true in every thread of exactly one block, which
+// may then read what the others wrote.  The finisher resets the counter for the next step.
+__device__ __forceinline__ bool last_arrival(int32_t* counter, int expected, int* flag_lds, int tid) {
+  __threadfence();  // release: this thread's global writes are visible device-wide
+  __syncthreads();
+  if (tid == 0) {
+    __threadfence();
+    int prev = atomicAdd(counter, 1);
+    int last = (prev == expected - 1);
+    if (last) *counter = 0;  // nobody else touches it before the next launch
+    *flag_lds = last;
+  }
+  __syncthreads();
+  bool last = (*flag_lds != 0);
+  if (last) __threadfence();  // acquire: drop stale cached lines before reading peers' results
+  return last;
+}
+
+// ------------------------------------------------------------------ kernel
+template <typename T, int D, int G, int U>
+__global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
+  using E = Elem<T>;
+  constexpr int VEC = E::VEC;
+  constexpr int LPR = D / VEC;   // lanes per row
+  constexpr int RPW = 64 / LPR;  // rows per wave-level load
+  static_assert(D % VEC == 0 && LPR >= 1 && LPR <= 64 && (LPR & (LPR - 1)) == 0, "row geometry");
+
+  extern __shared__ float4 smem4[];
+  float* small = reinterpret_cast<float*>(smem4);  // kSmallFloats
+  float* big = small + kSmallFloats;
+  int* flag_lds = reinterpret_cast<int*>(small + 480);
+
+  const int tid = threadIdx.x;
+  const int nt = blockDim.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int nw = nt >> 6;
+  const int li = lane % LPR;  // position inside the row
+  const int rg = lane / LPR;  // which of the RPW rows of a wave-level load
+
+  // blockIdx -> (pair = (unit, KV head), chunk).  Consecutive block ids go to
+  // consecutive XCDs, so the S chunks of one pair are placed on the same XCD
+  // (their partial results then meet in one L2).
+  const int S = p.S, R = p.R, k = p.k, n = p.n;
+  const int xcd = blockIdx.x & 7;
+  const int wq = blockIdx.x >> 3;
+  const int pair = (wq / S) * 8 + xcd;
+  const int chunk = wq % S;
+  const int c_new = min(n / R, S - 1);  // the chunk that also takes the incoming token
+  if (pair >= p.pairs || chunk > c_new) return;
+  const int unit = pair / p.H_kv;
+  const int kvh = pair - unit * p.H_kv;
+  const int r0 = chunk * R;
+  const int r1 = min(r0 + R, n);
+  const int ncached = r1 - r0;
+  const int nloc = ncached + (chunk == c_new ? 1 : 0);  // local candidates, >= 1
+  const bool full = (n == k);
+
+  const T* Kb = reinterpret_cast<const T*>(p.K) + ((size_t)pair * k + r0) * D;
+  const T* Vb = reinterpret_cast<const T*>(p.V) + ((size_t)pair * k + r0) * D;
+  const T* knew = reinterpret_cast<const T*>(p.k_new) + (size_t)pair * D;
+  const T* vnew = reinterpret_cast<const T*>(p.v_new) + (size_t)pair * D;
+  const T* qb = reinterpret_cast<const T*>(p.q) + ((size_t)unit * p.H + (size_t)kvh * G) * D;
+
+  float* e_lds = big;  // [nloc][G]
+
+  // ---------------- phase 1: logits ----------------
+  {
+    float qf[G][VEC];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      V16 pk = *reinterpret_cast<const V16*>(qb + g * D + li * VEC);
+      E::unpack(pk, qf[g]);
+    }
+    for (int base = wave * (RPW * U); base < nloc; base += nw * (RPW * U)) {
+      V16 kv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = base + u * RPW + rg;
+        kv[u] = V16{{0u, 0u, 0u, 0u}};
+        if (i < nloc) {
+          const T* row = (i < ncached) ? (Kb + (size_t)i * D) : knew;
+          kv[u] = *reinterpret_cast<const V16*>(row + li * VEC);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = base + u * RPW + rg;
+        float kf[VEC];
+        E::unpack(kv[u], kf);
+        float dot[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float a = 0.f;
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) a = fmaf(qf[g][v], kf[v], a);
+          dot[g] = group_sum<LPR>(a) * p.scale;
+        }
+        if (li == 0 && i < nloc) {
+#pragma unroll
+          for (int g = 0; g < G; ++g) e_lds[i * G + g] = dot[g];
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---------------- phase 2: chunk-local softmax ----------------
+  float m[G], Z[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) m[g] = -INFINITY;
+  for (int i = tid; i < nloc; i += nt) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) m[g] = fmaxf(m[g], e_lds[i * G + g]);
+  }
+  block_reduce<G, true>(m, small, lane, wave, nw);
+#pragma unroll
+  for (int g = 0; g < G; ++g) Z[g] = 0.f;
+  for (int i = tid; i < nloc; i += nt) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float e = expf(e_lds[i * G + g] - m[g]);
+      e_lds[i * G + g] = e;
+      Z[g] += e;
+    }
+  }
+  block_reduce<G, false>(Z, small + kMaxWaves * G, lane, wave, nw);
+
+  // Score contributions leave LDS now (each thread re-reads only what it wrote itself).
+  if (full) {
+    if (S == 1) {
+      float* sg = p.sg + (size_t)pair * p.kp;
+      for (int i = tid; i < nloc; i += nt) {
+        float a = 0.f;
+#pragma unroll
+        for (int g = 0; g < G; ++g) a += e_lds[i * G + g] / Z[g];
+        sg[i] = a;
+      }
+    } else {
+      float* es = p.escr + ((size_t)pair * p.kp + r0) * G;
+      for (int i = tid; i < nloc; i += nt) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) es[i * G + g] = e_lds[i * G + g];
+      }
+    }
+  }
+  __syncthreads();  // e_lds complete for everyone
+
+  // ---------------- phase 3: PV ----------------
+  float acc[G][VEC];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[g][v] = 0.f;
+  for (int base = wave * (RPW * U); base < nloc; base += nw * (RPW * U)) {
+    V16 vv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = base + u * RPW + rg;
+      vv[u] = V16{{0u, 0u, 0u, 0u}};
+      if (i < nloc) {
+        const T* row = (i < ncached) ? (Vb + (size_t)i * D) : vnew;
+        vv[u] = *reinterpret_cast<const V16*>(row + li * VEC);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = base + u * RPW + rg;
+      float vf[VEC];
+      E::unpack(vv[u], vf);
+      float w[G];
+#pragma unroll
+      for (int g = 0; g < G; ++g) w[g] = (i < nloc) ? e_lds[i * G + g] : 0.f;
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[g][v] = fmaf(w[g], vf[v], acc[g][v]);
+    }
+  }
+  // combine the RPW row groups of the wave, then the waves (in wave order)
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+      float a = acc[g][v];
+#pragma unroll
+      for (int o = LPR; o < 64; o <<= 1) a += __shfl_xor(a, o);
+      acc[g][v] = a;
+    }
+  __syncthreads();  // everyone is done reading e_lds; reuse the area
+  float* red = big;  // [nw][G*D]
+  if (rg == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) red[(wave * G + g) * D + li * VEC + v] = acc[g][v];
+  }
+  __syncthreads();
+
+  T* outb = reinterpret_cast<T*>(p.out) + ((size_t)unit * p.H + (size_t)kvh * G) * D;
+  if (S == 1) {
+    for (int x = tid; x < G * D; x += nt) {
+      float a = red[x];
+      for (int w = 1; w < nw; ++w) a += red[w * G * D + x];
+      // Z of head x / D; G is a compile-time constant so this is a select chain
+      float zg = Z[0];
+#pragma unroll
+      for (int g = 1; g < G; ++g) zg = (x / D == g) ? Z[g] : zg;
+      E::store(outb + x, a / zg);
+    }
+  } else {
+    float* ap = p.accp + ((size_t)pair * S + chunk) * (G * D);
+    for (int x = tid; x < G * D; x += nt) {
+      float a = red[x];
+      for (int w = 1; w < nw; ++w) a += red[w * G * D + x];
+      ap[x] = a;
+    }
+    if (tid < G) {
+      float mg = m[0], zg = Z[0];
+#pragma unroll
+      for (int g = 1; g < G; ++g) {
+        mg = (tid == g) ? m[g] : mg;
+        zg = (tid == g) ? Z[g] : zg;
+      }
+      float* st = p.stats + (((size_t)pair * S + chunk) * G + tid) * 2;
+      st[0] = mg;
+      st[1] = zg;
+    }
+  }
+
+  // ---------------- phase 4a: merge the chunks of this (unit, KV head) ----------------
+  if (S > 1) {
+    const int nact = c_new + 1;  // chunks that ran this step
+    if (nact > 1) {
+      if (!last_arrival(p.cnt_pair + pair, nact, flag_lds, tid)) return;
+    } else {
+      __syncthreads();
+    }
+    // global normalisers: m_g = max_c m_c, Z_g = sum_c Z_c exp(m_c - m_g)
+    float* wl = big;                  // [nact][G]  exp(m_c - m_g)
+    float* zl = big + nact * G;       // [G]
+    __syncthreads();
+    if (tid < G) {
+      const float* st = p.stats + ((size_t)pair * S * G + tid) * 2;
+      float mg = -INFINITY;
+      for (int c = 0; c < nact; ++c) mg = fmaxf(mg, st[(size_t)c * G * 2]);
+      float zg = 0.f;
+      for (int c = 0; c < nact; ++c) {
+        float w = expf(st[(size_t)c * G * 2] - mg);
+        wl[c * G + tid] = w;
+        zg += st[(size_t)c * G * 2 + 1] * w;
+      }
+      zl[tid] = zg;
+    }
+    __syncthreads();
+    const float* ap = p.accp + (size_t)pair * S * (G * D);
+    for (int x = tid; x < G * D; x += nt) {
+      const int g = x / D;
+      float a = 0.f;
+      for (int c = 0; c < nact; ++c) a = fmaf(ap[(size_t)c * G * D + x], wl[c * G + g], a);
+      E::store(outb + x, a / zl[g]);
+    }
+    if (full) {
+      const float* es = p.escr + (size_t)pair * p.kp * G;
+      float* sg = p.sg + (size_t)pair * p.kp;
+      for (int j = tid; j <= n; j += nt) {
+        const int c = min(j / R, c_new);
+        float a = 0.f;
+#pragma unroll
+        for (int g = 0; g < G; ++g) a += es[(size_t)j * G + g] * wl[c * G + g] / zl[g];
+        sg[j] = a;
+      }
+    }
+  }
+
+  // ---------------- phase 4b: state update ----------------
+  constexpr int ROW16 = D * (int)sizeof(T) / 16;  // 16-byte pieces per row
+  if (!full) {
+    // below capacity (App. B: num_kv <= cache_max_size): the new row takes slot n
+    if (tid < ROW16) {
+      reinterpret_cast<V16*>(const_cast<T*>(Kb) - (size_t)r0 * D + (size_t)n * D)[tid] =
+          reinterpret_cast<const V16*>(knew)[tid];
+      reinterpret_cast<V16*>(const_cast<T*>(Vb) - (size_t)r0 * D + (size_t)n * D)[tid] =
+          reinterpret_cast<const V16*>(vnew)[tid];
+    }
+    if (kvh == 0 && tid == 0) {
+      if (p.evicted) p.evicted[unit] = -1;
+      p.slot_token[(size_t)unit * k + n] = p.t;
+      p.occupancy[unit] = n + 1;
+    }
+    return;
+  }
+
+  if (p.H_kv > 1) {
+    if (!last_arrival(p.cnt_unit + unit, p.H_kv, flag_lds, tid)) return;
+  } else {
+    __threadfence();
+    __syncthreads();
+  }
+  // head-mean score (as a sum: the factor 1/H does not move the argmin) over the k+1
+  // candidates, KV-head partials added in head order; lowest index wins ties.
+  const float* sgu = p.sg + (size_t)unit * p.H_kv * p.kp;
+  float best = INFINITY;
+  int bj = 0x7fffffff;
+  for (int j = tid; j <= k; j += nt) {
+    float s = sgu[j];
+    for (int h = 1; h < p.H_kv; ++h) s += sgu[(size_t)h * p.kp + j];
+    if (s < best) {
+      best = s;
+      bj = j;
+    }
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    float ob = __shfl_xor(best, o);
+    int oj = __shfl_xor(bj, o);
+    if (ob < best || (ob == best && oj < bj)) {
+      best = ob;
+      bj = oj;
+    }
+  }
+  float* bv = small + 256;
+  int* bi = reinterpret_cast<int*>(small + 256 + kMaxWaves);
+  __syncthreads();
+  if (lane == 0) {
+    bv[wave] = best;
+    bi[wave] = bj;
+  }
+  __syncthreads();
+  best = bv[0];
+  bj = bi[0];
+  for (int w = 1; w < nw; ++w) {
+    float ob = bv[w];
+    int oj = bi[w];
+    if (ob < best || (ob == best && oj < bj)) {
+      best = ob;
+      bj = oj;
+    }
+  }
+  if (bj > k) bj = k;  // only reachable with non-finite scores
+  if (bj < k) {
+    T* Ku = reinterpret_cast<T*>(p.K) + ((size_t)unit * p.H_kv * k + bj) * D;
+    T* Vu = reinterpret_cast<T*>(p.V) + ((size_t)unit * p.H_kv * k + bj) * D;
+    const T* kn = reinterpret_cast<const T*>(p.k_new) + (size_t)unit * p.H_kv * D;
+    const T* vn = reinterpret_cast<const T*>(p.v_new) + (size_t)unit * p.H_kv * D;
+    for (int x = tid; x < p.H_kv * ROW16; x += nt) {
+      const int h = x / ROW16, c = x - h * ROW16;
+      reinterpret_cast<V16*>(Ku + (size_t)h * k * D)[c] = reinterpret_cast<const V16*>(kn + (size_t)h * D)[c];
+      reinterpret_cast<V16*>(Vu + (size_t)h * k * D)[c] = reinterpret_cast<const V16*>(vn + (size_t)h * D)[c];
+    }
+  }
+  if (tid == 0) {
+    if (p.evicted) p.evicted[unit] = bj;
+    if (bj < k) p.slot_token[(size_t)unit * k + bj] = p.t;
+    p.occupancy[unit] = k;
+  }
+}
+
+__global__ void tova_fill_i32_kernel(int32_t* dst, int32_t value, size_t count) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < count; i += stride) dst[i] = value;
+}
+
+template <typename T, int D, int G>
+hipError_t launch_one(const StepParams& p, const LaunchPlan& lp, hipStream_t stream) {
+  hipLaunchKernelGGL((tova_step_kernel<T, D, G, kUnroll>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes,
+                     stream, p);
+  return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t launch_g(int G, const StepParams& p, const LaunchPlan& lp, hipStream_t s) {
+  switch (G) {
+    case 1: return launch_one<T, D, 1>(p, lp, s);
+    case 2: return launch_one<T, D, 2>(p, lp, s);
+    case 4: return launch_one<T, D, 4>(p, lp, s);
+    case 8: return launch_one<T, D, 8>(p, lp, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+template <typename T>
+hipError_t launch_d(int D, int G, const StepParams& p, const LaunchPlan& lp, hipStream_t s) {
+  switch (D) {
+    case 32: return launch_g<T, 32>(G, p, lp, s);
+    case 64: return launch_g<T, 64>(G, p, lp, s);
+    case 128: return launch_g<T, 128>(G, p, lp, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_step(int dtype_is_bf16, int D, int G, const StepParams& p, const LaunchPlan& lp,
+                       hipStream_t stream) {
+  return dtype_is_bf16 ? launch_d<bf16_t>(D, G, p, lp, stream) : launch_d<float>(D, G, p, lp, stream);
+}
+
+hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_t stream) {
+  if (count == 0) return hipSuccess;
+  size_t blocks = (count + 255) / 256;
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(tova_fill_i32_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, dst, value, count);
+  return hipGetLastError();
+}
+
+}  // namespace tova

@@ -1,0 +1,172 @@
+"""GPU-vs-oracle parity harness.
+
+run_gpu() drives the HIP library over a whole synthetic stream (inputs generated on the
+device, chunk by chunk) and keeps the `evicted` log of every unit plus the outputs of the
+sampled units.  check_unit() then re-creates one sampled (layer, sequence) unit on the CPU
+from the same generator, steps the fp64 oracle through it and compares element by element.
+
+Bars (written here, used by every parity test):
+  * outputs: per output vector (one head of one step) max|gpu - ref| / max|ref| <= OUT_TOL
+    (2e-2 for bf16, 1e-5 for fp32);
+  * victims: identical at every step, except steps where the oracle's two lowest head-mean
+    scores are closer than GAP_EXEMPT = 1e-6 *and* the GPU's choice is within that distance
+    of the minimum; those are counted, reported, and the oracle then follows the GPU's
+    choice so that both keep the same state;
+  * final slot -> token map: identical; cached K/V rows: bit-identical to the stream rows.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from workloads import Stream, StreamSpec
+
+OUT_TOL = {"bf16": 2e-2, "f32": 1e-5}
+GAP_EXEMPT = 1e-6
+
+
+def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: int = 256,
+            single_step_calls: bool = False, device="cuda:0"):
+    """units: list of (layer, seq) whose outputs are kept.  Returns a dict of CPU arrays."""
+    from paper_2401_06104_amd import TovaCache
+
+    dev = torch.device(device)
+    cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype,
+                      n_splits=n_splits, device=dev)
+    stream = Stream(spec, seed, device=dev)
+    evicted = torch.empty(spec.T, spec.L, spec.B, dtype=torch.int32, device=dev)
+    ul = torch.tensor([u[0] for u in units], device=dev)
+    ub = torch.tensor([u[1] for u in units], device=dev)
+    outs = []
+    for t0 in range(0, spec.T, chunk_steps):
+        t1 = min(spec.T, t0 + chunk_steps)
+        c = stream.chunk(t0, t1)
+        out = torch.empty_like(c["q"])
+        if single_step_calls:
+            for i in range(t1 - t0):
+                cache.decode_step(c["q"][i], c["k"][i], c["v"][i], out[i], evicted[t0 + i])
+        else:
+            cache.decode_steps(c["q"], c["k"], c["v"], out, evicted[t0:t1])
+        outs.append(out[:, ul, ub].float().cpu())
+    torch.cuda.synchronize(dev)
+    res = {
+        "out": torch.cat(outs).numpy(),                       # [T, n_units, H, d] float32
+        "evicted": evicted.cpu().numpy(),                     # [T, L, B]
+        "slot_token": cache.slot_token.cpu().numpy(),         # [L, B, k]
+        "occupancy": cache.occupancy.cpu().numpy(),
+        "K": cache.K[ul, ub].float().cpu().numpy(),           # [n_units, H_kv, k, d]
+        "V": cache.V[ul, ub].float().cpu().numpy(),
+        "layout": (cache.layout.n_splits, cache.layout.rows_per_split, cache.layout.block_threads,
+                   cache.layout.grid_blocks),
+        "tokens_seen": cache.tokens_seen,
+    }
+    cache.destroy()
+    return res
+
+
+def check_unit(spec: StreamSpec, seed: int, unit, gpu_out, gpu_evicted, gpu_slot_token, gpu_K, gpu_V,
+               t_stop=None):
+    """Steps the oracle over unit=(layer, seq) and compares with the GPU's log.
+    gpu_out [T, H, d], gpu_evicted [T], gpu_slot_token [k], gpu_K / gpu_V [H_kv, k, d].
+    Returns a dict of statistics; raises AssertionError on any violation."""
+    from oracle.tova_oracle import TovaOracle
+
+    l, b = unit
+    T = spec.T if t_stop is None else t_stop
+    tol = OUT_TOL[spec.dtype]
+    st = Stream(spec, seed, device="cpu", layers=[l], seqs=[b])
+    orc = TovaOracle(spec.k, spec.H, spec.H_kv, spec.d)
+    stats = dict(unit=unit, steps=T, evict_steps=0, near_tie_steps=0, mismatches=0, max_rel_err=0.0,
+                 max_gap_at_mismatch=0.0, min_gap=float("inf"))
+    kk_all, vv_all = [], []
+    for t0 in range(0, T, 512):
+        t1 = min(T, t0 + 512)
+        c = st.chunk(t0, t1)
+        q = c["q"][:, 0, 0].double().numpy()
+        kk = c["k"][:, 0, 0].double().numpy()
+        vv = c["v"][:, 0, 0].double().numpy()
+        kk_all.append(kk); vv_all.append(vv)
+        for i in range(t1 - t0):
+            t = t0 + i
+            out, p = orc.attend(q[i], kk[i], vv[i])
+            g = gpu_out[t].astype(np.float64)
+            err = np.abs(g - out).max(axis=1) / np.maximum(np.abs(out).max(axis=1), 1e-30)
+            worst = float(err.max())
+            assert worst <= tol, f"unit {unit} step {t}: output rel err {worst:.3e} > {tol}"
+            stats["max_rel_err"] = max(stats["max_rel_err"], worst)
+            ge = int(gpu_evicted[t])
+            if orc.n + 1 <= spec.k:
+                assert ge == -1, f"unit {unit} step {t}: GPU evicted {ge} while filling"
+                orc.update(-1, kk[i], vv[i])
+                continue
+            s = orc.scores(p)
+            j, gap = orc.select(s)
+            stats["evict_steps"] += 1
+            stats["min_gap"] = min(stats["min_gap"], gap)
+            if gap < GAP_EXEMPT:
+                stats["near_tie_steps"] += 1
+            assert 0 <= ge <= spec.k, f"unit {unit} step {t}: GPU victim {ge} out of range"
+            if ge != j:
+                ok = gap < GAP_EXEMPT and (s[ge] - s[j]) < GAP_EXEMPT
+                assert ok, (f"unit {unit} step {t}: GPU victim {ge} != oracle {j}, "
+                            f"gap {gap:.3e}, s[gpu]-min {s[ge] - s[j]:.3e}")
+                stats["mismatches"] += 1
+                stats["max_gap_at_mismatch"] = max(stats["max_gap_at_mismatch"], float(s[ge] - s[j]))
+            orc.update(ge, kk[i], vv[i])     # == j unless a counted near-tie
+    if t_stop is None:
+        assert np.array_equal(orc.slot_token, gpu_slot_token.astype(np.int64)), f"unit {unit}: slot_token differs"
+        n = orc.n
+        assert np.array_equal(orc.K[:, :n], gpu_K[:, :n].astype(np.float64)), f"unit {unit}: cached K differs"
+        assert np.array_equal(orc.V[:, :n], gpu_V[:, :n].astype(np.float64)), f"unit {unit}: cached V differs"
+        # and the cached rows are the raw stream rows of the tokens the map names
+        kk_all, vv_all = np.concatenate(kk_all), np.concatenate(vv_all)
+        for slot in range(n):
+            tk = int(gpu_slot_token[slot])
+            assert np.array_equal(gpu_K[:, slot].astype(np.float64), kk_all[tk])
+            assert np.array_equal(gpu_V[:, slot].astype(np.float64), vv_all[tk])
+    return stats
+
+
+def _check_unit_star(args):
+    return check_unit(*args)
+
+
+def check_units(spec, seed, units, res, workers: int = 1, t_stop=None):
+    """Checks every sampled unit; with workers > 1 in spawned CPU-only processes."""
+    jobs = []
+    for ui, (l, b) in enumerate(units):
+        jobs.append((spec, seed, (l, b), res["out"][:, ui], res["evicted"][:, l, b],
+                     res["slot_token"][l, b], res["K"][ui], res["V"][ui], t_stop))
+    if workers <= 1 or len(jobs) == 1:
+        return [check_unit(*j) for j in jobs]
+    import multiprocessing as mp
+    with mp.get_context("spawn").Pool(min(workers, len(jobs))) as pool:
+        return pool.map(_check_unit_star, jobs)
+
+
+def check_global_invariants(spec, res):
+    """Properties of the whole run that hold at any size (every unit, every step)."""
+    ev = res["evicted"]
+    k = spec.k
+    fill = min(k, spec.T)
+    assert (ev[:fill] == -1).all(), "a unit evicted before its cache was full"
+    if spec.T > k:
+        assert ((ev[k:] >= 0) & (ev[k:] <= k)).all(), "victim out of range after capacity"
+    assert (res["occupancy"] == min(spec.T, k)).all()
+    assert res["tokens_seen"] == spec.T
+    # replay the evicted log on integers alone: it must reproduce the final slot -> token map
+    st = np.full((spec.L, spec.B, k), -1, dtype=np.int64)
+    li, bi = np.meshgrid(np.arange(spec.L), np.arange(spec.B), indexing="ij")
+    for t in range(spec.T):
+        if t < k:
+            st[:, :, t] = t
+        else:
+            e = ev[t]
+            m = e < k
+            st[li[m], bi[m], e[m]] = t
+    assert np.array_equal(st, res["slot_token"].astype(np.int64)), "slot_token inconsistent with the evicted log"
+    # retained tokens are distinct
+    for l in range(spec.L):
+        for b in range(spec.B):
+            row = st[l, b][st[l, b] >= 0]
+            assert len(set(row.tolist())) == len(row)

@@ -1,0 +1,109 @@
+"""CPU tests of the C-ABI library: it loads, exports what include/tova.h declares, and its
+host-side logic (validation, sizes, launch plan) behaves.  No GPU call is made."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2401_06104_amd import (TovaConfig, TovaLayout, TovaError, load_library, tova_cache_bytes,
+                                  tova_cache_layout, tova_strerror, TOVA_BF16, TOVA_F32, TOVA_EINVAL,
+                                  TOVA_ENOSUP, TOVA_OK)
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def cfg(L=1, B=1, k=16, H=4, Hkv=4, d=32, dt=TOVA_F32, scale=0.0, S=0):
+    return TovaConfig(L, B, k, H, Hkv, d, dt, scale, S)
+
+
+def test_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "tova.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(tova_[a-z_]+)\s*\(", text))
+    assert {"tova_cache_init", "tova_decode_step", "tova_decode_steps", "tova_cache_bytes"} <= names
+    lib = load_library()
+    for n in sorted(names):
+        assert hasattr(lib, n), f"libtova.so does not export {n}"
+
+
+def test_strerror():
+    assert tova_strerror(TOVA_OK) == "ok"
+    assert "invalid" in tova_strerror(TOVA_EINVAL)
+    assert "unknown" in tova_strerror(-99)
+
+
+# Sec. 7.1 efficiency table, first row: memory of the LLaMA-2-7B cache at batch 1.
+def test_cache_bytes_reproduces_paper_memory_row():
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "cache_memory_row.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 5
+    for size, printed in rows:
+        k, printed = int(size), float(printed)
+        kv, _, _ = tova_cache_bytes(cfg(L=32, B=1, k=k, H=32, Hkv=32, d=128, dt=TOVA_BF16))
+        assert kv == 2 * 32 * k * 32 * 128 * 2                 # K and V, 32 layers, bf16
+        # the printed figures are a few % above the raw cache (allocator / framework overhead,
+        # rounding to two digits); they must scale with k exactly like the raw size
+        assert 0.85 * printed < kv / 1e9 < 1.0 * printed + 0.005
+
+
+def test_validation_errors():
+    lib = load_library()
+    bad = [cfg(L=0), cfg(B=-1), cfg(k=0), cfg(H=0), cfg(Hkv=0), cfg(d=0), cfg(H=6, Hkv=4),
+           cfg(dt=7), cfg(S=-1), cfg(scale=float("nan"))]
+    for c in bad:
+        with pytest.raises(TovaError) as e:
+            tova_cache_bytes(c)
+        assert e.value.status == TOVA_EINVAL
+    for c in [cfg(d=48), cfg(d=256), cfg(H=32, Hkv=2), cfg(H=3, Hkv=1)]:
+        with pytest.raises(TovaError) as e:
+            tova_cache_layout(c)
+        assert e.value.status == TOVA_ENOSUP
+    assert lib.tova_cache_bytes(None, None, None, None) == TOVA_EINVAL
+    assert lib.tova_cache_layout(ctypes.byref(cfg()), None) == TOVA_EINVAL
+    # init: null / misaligned buffers are rejected before any HIP call
+    h = ctypes.c_void_p()
+    c = cfg()
+    assert lib.tova_cache_init(ctypes.byref(h), ctypes.byref(c), None, None, None, None) == TOVA_EINVAL
+    assert lib.tova_cache_init(ctypes.byref(h), ctypes.byref(c), 256 + 8, 512, 768, None) == TOVA_EINVAL
+    assert lib.tova_cache_init(None, ctypes.byref(c), 256, 512, 768, None) == TOVA_EINVAL
+    assert not h.value
+    assert lib.tova_decode_step(None, None, None, None, None, None, None) == TOVA_EINVAL
+    assert lib.tova_decode_steps(None, 3, None, None, None, None, None, None) == TOVA_EINVAL
+    assert lib.tova_cache_destroy(None) == TOVA_EINVAL
+    assert lib.tova_cache_tokens_seen(None, None) == TOVA_EINVAL
+
+
+@pytest.mark.parametrize("c,expect_S", [
+    (cfg(), 1),                                                        # tiny: one chunk
+    (cfg(B=64, k=1024, H=32, Hkv=8, d=128, dt=TOVA_BF16), 1),          # 512 (seq, KV head) pairs
+    (cfg(k=512, H=32, Hkv=32, d=128, dt=TOVA_BF16), 16),               # 32 pairs -> split
+    (cfg(L=32, k=4096, H=32, Hkv=4, d=128, dt=TOVA_BF16), 4),          # 128 pairs -> split
+    (cfg(L=32, B=64, k=4096, H=32, Hkv=32, d=128, dt=TOVA_BF16), 1),
+])
+def test_launch_plan(c, expect_S):
+    lay = tova_cache_layout(c)
+    assert lay.n_splits == expect_S
+    R, S, k = lay.rows_per_split, lay.n_splits, c.capacity_k
+    assert R * S >= k and R * (S - 1) < k                   # chunks cover the slots, none is dead
+    pairs = c.n_layers * c.batch * c.n_kv_heads
+    assert lay.grid_blocks == (pairs + 7) // 8 * 8 * S
+    assert lay.block_threads in (256, 512)
+    G = c.n_q_heads // c.n_kv_heads
+    assert lay.lds_bytes >= 4 * (R + 1) * G and lay.lds_bytes <= 64 * 1024
+    kv, st, sc = tova_cache_bytes(c)
+    esize = 2 if c.dtype == TOVA_BF16 else 4
+    assert kv == 2 * pairs * k * c.head_dim * esize and lay.v_offset == kv // 2 and lay.k_offset == 0
+    assert st >= lay.slot_token_offset + 4 * c.n_layers * c.batch * k
+    assert lay.slot_token_offset >= 4 * c.n_layers * c.batch
+
+
+def test_forced_splits_are_normalised():
+    c = cfg(k=100, S=7, d=128, dt=TOVA_BF16)
+    lay = tova_cache_layout(c)
+    assert lay.rows_per_split == 15 and lay.n_splits == 7
+    lay = tova_cache_layout(cfg(k=5, S=64))
+    assert lay.n_splits == 5 and lay.rows_per_split == 1
+    # a chunk that would not fit LDS is split further, whatever was asked
+    lay = tova_cache_layout(cfg(k=1 << 16, H=8, Hkv=1, d=128, dt=TOVA_BF16, S=1))
+    assert lay.n_splits > 1 and lay.lds_bytes <= 64 * 1024
