@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the TOVA decode step on one MI355X.
+
+Workload (the configuration the headline metric is quoted on): Mistral-7B-shaped GQA layer,
+32 query heads / 8 KV heads, head_dim 128, bf16, batch 64, cache capacity k = 1024.  The cache
+is first filled through the same API (1024 untimed steps), then `--steps` decode steps at full
+occupancy are timed in one tova_decode_steps call with all inputs already resident in HBM.
+One "step" = one token for each of the 64 sequences = one launch of the fused kernel.
+
+Prints ONE JSON line (see README / DESIGN for the fields).  `roofline` is the fused step
+kernel against the HBM roofline: algorithmic bytes per launch / average launch duration measured
+with HIP events on the launch stream over the timed region.  `cpu_baseline` is the fp64 oracle
+timed on host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes_per_step(spec) -> int:
+    """What the method itself must move per decode step at full occupancy, all units:
+    K and V read once, q read, out written, the new k/v read, the victim slot written,
+    evicted + slot_token written."""
+    e = 2 if spec.dtype == "bf16" else 4
+    per_unit = (2 * spec.k * spec.H_kv * spec.d * e      # K + V stream
+                + 2 * spec.H * spec.d * e                # q in, out out
+                + 2 * spec.H_kv * spec.d * e             # k_new, v_new in
+                + 2 * spec.H_kv * spec.d * e             # slot overwrite
+                + 8)                                     # evicted, slot_token
+    return per_unit * spec.L * spec.B
+
+
+def gpu_leg(spec, seed, steps, warmup, device, chunk=256):
+    import torch
+    from paper_2401_06104_amd import TovaCache
+    from workloads import Stream
+
+    dev = torch.device(device)
+    cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype, device=dev)
+    stream = Stream(spec, seed, device=dev)
+    need = spec.k + warmup + steps
+    assert need <= spec.T, f"stream too short: need {need} tokens, spec has {spec.T}"
+
+    def run(t0, t1, keep=False):
+        outs = []
+        for a in range(t0, t1, chunk):
+            b = min(t1, a + chunk)
+            c = stream.chunk(a, b)
+            out = torch.empty_like(c["q"])
+            ev = torch.empty(b - a, spec.L, spec.B, dtype=torch.int32, device=dev)
+            cache.decode_steps(c["q"], c["k"], c["v"], out, ev)
+            if keep:
+                outs.append(ev)
+        return outs
+
+    run(0, spec.k)                                   # fill: untimed, same entry point
+    if warmup:
+        run(spec.k, spec.k + warmup)                 # untimed full-occupancy steps
+    # stage every timed input in HBM first
+    t0 = spec.k + warmup
+    qs, ks, vs = [], [], []
+    for a in range(t0, t0 + steps, chunk):
+        c = stream.chunk(a, min(t0 + steps, a + chunk))
+        qs.append(c["q"]); ks.append(c["k"]); vs.append(c["v"])
+    q, k_new, v_new = torch.cat(qs), torch.cat(ks), torch.cat(vs)
+    del qs, ks, vs
+    out = torch.empty_like(q)
+    evicted = torch.empty(steps, spec.L, spec.B, dtype=torch.int32, device=dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize(dev)
+    w0 = time.perf_counter()
+    e0.record()
+    cache.decode_steps(q, k_new, v_new, out, evicted)
+    e1.record()
+    torch.cuda.synchronize(dev)
+    wall = time.perf_counter() - w0
+    ev_ms = e0.elapsed_time(e1)
+    ev_host = evicted.cpu()
+    ok = bool(((ev_host >= 0) & (ev_host <= spec.k)).all()) and cache.tokens_seen == need
+    lay = cache.layout
+    plan = dict(n_splits=lay.n_splits, rows_per_split=lay.rows_per_split, block_threads=lay.block_threads,
+                grid_blocks=lay.grid_blocks, lds_bytes=lay.lds_bytes)
+    cache.destroy()
+    return dict(wall_s=wall, event_ms=ev_ms, plan=plan, sane=ok,
+                new_token_dropped_frac=float((ev_host == spec.k).float().mean()))
+
+
+def _oracle_worker(args):
+    """One sequence of the workload through the fp64 oracle: fill, then timed steps."""
+    spec, seed, b, n_timed = args
+    import numpy as np  # noqa: F401
+    from oracle.tova_oracle import TovaOracle
+    from workloads import Stream
+    try:
+        from threadpoolctl import threadpool_limits
+        limiter = threadpool_limits(limits=1)       # one thread per worker: cores = workers
+    except Exception:                                # pragma: no cover
+        limiter = None
+    st = Stream(spec, seed, device="cpu", layers=[0], seqs=[b])
+    orc = TovaOracle(spec.k, spec.H, spec.H_kv, spec.d)
+    c = st.chunk(0, spec.k + n_timed)
+    q, kk, vv = (c[n][:, 0, 0].double().numpy() for n in "qkv")
+    for t in range(spec.k):
+        orc.step(q[t], kk[t], vv[t])
+    t0 = time.perf_counter()
+    for t in range(spec.k, spec.k + n_timed):
+        orc.step(q[t], kk[t], vv[t])
+    dt = time.perf_counter() - t0
+    del limiter
+    return dt
+
+
+def cpu_leg(spec, seed, n_timed=768):
+    import multiprocessing as mp
+    cores = max(1, min(16, os.cpu_count() or 1, spec.B))
+    jobs = [(spec, seed, b, n_timed) for b in range(cores)]
+    t0 = time.perf_counter()
+    with mp.get_context("spawn").Pool(cores) as pool:
+        times = pool.map(_oracle_worker, jobs)
+    wall_total = time.perf_counter() - t0
+    timed_wall = max(times)                          # workers run concurrently
+    unit_steps_per_s = cores * n_timed / timed_wall
+    return dict(value=unit_steps_per_s / (spec.L * spec.B), unit="decode steps/s", cores=cores, kind="oracle",
+                sample=(f"{cores} of {spec.B} sequences, one per core, {n_timed} full-occupancy steps each after "
+                        f"an untimed {spec.k}-step fill; unit-steps/s scaled by 1/{spec.L * spec.B} units per step"),
+                unit_steps_per_s=unit_steps_per_s, wall_s_including_fill=wall_total)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2048)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--seed", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=1, help="stack this many independent layers (1 = the named config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-hbm-variant", action="store_true",
+                    help="skip the extra 32-layer run whose 8 GiB cache cannot sit in the last-level cache")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the path shards by batch/layer "
+              "without communication, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    from workloads import spec_for
+
+    spec = spec_for("c3_mistral_gqa", L=args.layers, T=1024 + args.warmup + args.steps)
+    g = gpu_leg(spec, args.seed, args.steps, args.warmup, "cuda:0")
+    ms_per_step = g["event_ms"] / args.steps
+    abytes = algorithmic_bytes_per_step(spec)
+    achieved = abytes / (ms_per_step * 1e-3) / 1e9
+    result = {
+        "metric": "TOVA decode steps/sec and achieved HBM GB/s (% of peak), 1 MI355X",
+        "value": 1e3 / ms_per_step,
+        "unit": "decode steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 storage, f32 arithmetic", "data": "synthetic",
+        "config": {"workload": "c3_mistral_gqa: Mistral-7B-shaped GQA layer, 32 q heads / 8 KV heads, d=128, bf16, "
+                               f"batch 64, k=1024, L={spec.L}; 1024 untimed fill steps then timed decode steps "
+                               "at full occupancy", "seed": args.seed, "plan": g["plan"],
+                   "sequence_steps_per_s": 1e3 / ms_per_step * spec.L * spec.B},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "tova_step_kernel<bf16, d=128, G=4>", "algorithmic_bytes_per_launch": abytes,
+                     "avg_launch_us": ms_per_step * 1e3},
+        "sane": g["sane"], "new_token_dropped_frac": g["new_token_dropped_frac"],
+        "wall_s_timed_region": g["wall_s"],
+    }
+    if not args.no_hbm_variant and args.layers == 1:
+        # same kernel, 32 independent layers: 8 GiB of cache per step cannot be served from the
+        # 256 MB last-level cache, so this is the DRAM-bound figure
+        s32 = spec_for("c3_mistral_gqa", L=32, T=1024 + 8 + 192)
+        g32 = gpu_leg(s32, args.seed, 192, 8, "cuda:0", chunk=32)
+        ms32 = g32["event_ms"] / 192
+        ab32 = algorithmic_bytes_per_step(s32)
+        result["hbm_resident_variant"] = {"workload": "same layer shape x 32 layers (8 GiB cache)", "steps": 192,
+                                          "ms_per_step": ms32, "achieved_GBps": ab32 / (ms32 * 1e-3) / 1e9,
+                                          "frac": ab32 / (ms32 * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                          "sequence_steps_per_s": 1e3 / ms32 * 32 * 64, "sane": g32["sane"]}
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_leg(spec_for("c3_mistral_gqa"), args.seed)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -20,8 +20,8 @@
 //                         order, argmin with lowest-index tie break, overwrite
 //                         the victim's slot with the new row, log `evicted`.
 //            Both levels use the "last workgroup to arrive does the merge"
-//            pattern: results are written to scratch, made visible with an
-//            agent-scope fence, and an atomic counter elects the finisher.
+//            pattern: results are written to scratch with agent-scope
+//            (write-through) stores and an atomic counter elects the finisher.
 //            Nothing ever waits on another workgroup, so every wave reaches
 //            its exit whatever the scheduling order.
 //
@@ -143,23 +143,35 @@ __device__ __forceinline__ void block_reduce(float (&v)[G], float* red, int lane
   }
 }
 
+// Cross-workgroup hand-off.  A full agent-scope release fence writes back the whole L2 of
+// the XCD and an acquire fence invalidates it; issued by every wave of every workgroup that
+// costs far more than the step's entire K/V stream.  Instead, everything one workgroup hands
+// to another is written with agent-scope (write-through) stores and read with agent-scope
+// (cache-bypassing) loads, so no cache maintenance is needed at all: the producer only has
+// to wait until its stores have completed before it bumps the arrival counter.
+__device__ __forceinline__ void st_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Elects the last of `expected` arrivals on `counter`.  All threads of the block call it
-// after writing their results; it returns true in every thread of exactly one block, which
-// may then read what the others wrote.  The finisher resets the counter for the next step.
+// after writing their results with st_agent; it returns true in every thread of exactly one
+// block, which may then read what the others wrote with ld_agent.  The finisher resets the
+// counter for the next step.  Nobody waits for anybody: every block leaves at once.
 __device__ __forceinline__ bool last_arrival(int32_t* counter, int expected, int* flag_lds, int tid) {
-  __threadfence();  // release: this thread's global writes are visible device-wide
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // keep the stores above this point
+  __builtin_amdgcn_s_waitcnt(0);                          // ... and wait until they have completed
   __syncthreads();
   if (tid == 0) {
-    __threadfence();
-    int prev = atomicAdd(counter, 1);
+    int prev = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     int last = (prev == expected - 1);
-    if (last) *counter = 0;  // nobody else touches it before the next launch
+    if (last) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     *flag_lds = last;
   }
   __syncthreads();
-  bool last = (*flag_lds != 0);
-  if (last) __threadfence();  // acquire: drop stale cached lines before reading peers' results
-  return last;
+  return *flag_lds != 0;
 }
 
 // ------------------------------------------------------------------ kernel
@@ -280,13 +292,13 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
         float a = 0.f;
 #pragma unroll
         for (int g = 0; g < G; ++g) a += e_lds[i * G + g] / Z[g];
-        sg[i] = a;
+        st_agent(sg + i, a);
       }
     } else {
       float* es = p.escr + ((size_t)pair * p.kp + r0) * G;
       for (int i = tid; i < nloc; i += nt) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) es[i * G + g] = e_lds[i * G + g];
+        for (int g = 0; g < G; ++g) st_agent(es + i * G + g, e_lds[i * G + g]);
       }
     }
   }
@@ -359,7 +371,7 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
     for (int x = tid; x < G * D; x += nt) {
       float a = red[x];
       for (int w = 1; w < nw; ++w) a += red[w * G * D + x];
-      ap[x] = a;
+      st_agent(ap + x, a);
     }
     if (tid < G) {
       float mg = m[0], zg = Z[0];
@@ -369,8 +381,8 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
         zg = (tid == g) ? Z[g] : zg;
       }
       float* st = p.stats + (((size_t)pair * S + chunk) * G + tid) * 2;
-      st[0] = mg;
-      st[1] = zg;
+      st_agent(st, mg);
+      st_agent(st + 1, zg);
     }
   }
 
@@ -389,12 +401,12 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
     if (tid < G) {
       const float* st = p.stats + ((size_t)pair * S * G + tid) * 2;
       float mg = -INFINITY;
-      for (int c = 0; c < nact; ++c) mg = fmaxf(mg, st[(size_t)c * G * 2]);
+      for (int c = 0; c < nact; ++c) mg = fmaxf(mg, ld_agent(st + (size_t)c * G * 2));
       float zg = 0.f;
       for (int c = 0; c < nact; ++c) {
-        float w = expf(st[(size_t)c * G * 2] - mg);
+        float w = expf(ld_agent(st + (size_t)c * G * 2) - mg);
         wl[c * G + tid] = w;
-        zg += st[(size_t)c * G * 2 + 1] * w;
+        zg += ld_agent(st + (size_t)c * G * 2 + 1) * w;
       }
       zl[tid] = zg;
     }
@@ -403,7 +415,7 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
     for (int x = tid; x < G * D; x += nt) {
       const int g = x / D;
       float a = 0.f;
-      for (int c = 0; c < nact; ++c) a = fmaf(ap[(size_t)c * G * D + x], wl[c * G + g], a);
+      for (int c = 0; c < nact; ++c) a = fmaf(ld_agent(ap + (size_t)c * G * D + x), wl[c * G + g], a);
       E::store(outb + x, a / zl[g]);
     }
     if (full) {
@@ -413,8 +425,8 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
         const int c = min(j / R, c_new);
         float a = 0.f;
 #pragma unroll
-        for (int g = 0; g < G; ++g) a += es[(size_t)j * G + g] * wl[c * G + g] / zl[g];
-        sg[j] = a;
+        for (int g = 0; g < G; ++g) a += ld_agent(es + (size_t)j * G + g) * wl[c * G + g] / zl[g];
+        st_agent(sg + j, a);
       }
     }
   }
@@ -440,7 +452,8 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
   if (p.H_kv > 1) {
     if (!last_arrival(p.cnt_unit + unit, p.H_kv, flag_lds, tid)) return;
   } else {
-    __threadfence();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
   }
   // head-mean score (as a sum: the factor 1/H does not move the argmin) over the k+1
@@ -449,8 +462,8 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
   float best = INFINITY;
   int bj = 0x7fffffff;
   for (int j = tid; j <= k; j += nt) {
-    float s = sgu[j];
-    for (int h = 1; h < p.H_kv; ++h) s += sgu[(size_t)h * p.kp + j];
+    float s = ld_agent(sgu + j);
+    for (int h = 1; h < p.H_kv; ++h) s += ld_agent(sgu + (size_t)h * p.kp + j);
     if (s < best) {
       best = s;
       bj = j;
