@@ -146,6 +146,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hbm-variant", action="store_true",
                     help="skip the extra 32-layer run whose 8 GiB cache cannot sit in the last-level cache")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain elementwise copy kernel of known size (1 GiB in, 1 GiB out) five "
+                         "times, so that hardware byte counters collected over this run can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the path shards by batch/layer "
@@ -193,6 +196,15 @@ def main():
                                           "ms_per_step": ms32, "achieved_GBps": ab32 / (ms32 * 1e-3) / 1e9,
                                           "frac": ab32 / (ms32 * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                           "sequence_steps_per_s": 1e3 / ms32 * 32 * 64, "sane": g32["sane"]}
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")       # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)                                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        result["calibration_copy"] = {"kernel": "torch elementwise mul(src, 1.0, out=dst)", "bytes_read": 1 << 30,
+                                      "bytes_written": 1 << 30, "launches": 5}
+        del src, dst
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_leg(spec_for("c3_mistral_gqa"), args.seed)
     print(json.dumps(result))

@@ -8,7 +8,7 @@
 
 namespace tova {
 
-constexpr int kUnroll = 4;  // 16-byte loads in flight per lane in the K and V streams
+
 
 // Arguments of one step launch (one token for every unit).
 struct StepParams {

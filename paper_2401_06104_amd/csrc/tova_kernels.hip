@@ -48,6 +48,7 @@ struct alignas(16) V16 {
 struct bf16_t {
   uint16_t x;
 };
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 template <typename T>
 struct Elem;
@@ -59,7 +60,12 @@ struct Elem<float> {
 #pragma unroll
     for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(p.w[i]);
   }
-  static __device__ __forceinline__ float round_trip(float v) { return v; }
+  // acc + sum of the 4 products of two 16-byte chunks
+  static __device__ __forceinline__ float dot(const V16& a, const V16& b, float acc) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc = fmaf(__uint_as_float(a.w[i]), __uint_as_float(b.w[i]), acc);
+    return acc;
+  }
   static __device__ __forceinline__ void store(float* dst, float v) { *dst = v; }
 };
 
@@ -72,6 +78,15 @@ struct Elem<bf16_t> {
       f[2 * i] = __uint_as_float(p.w[i] << 16);
       f[2 * i + 1] = __uint_as_float(p.w[i] & 0xffff0000u);
     }
+  }
+  // acc + sum of the 8 products of two 16-byte chunks: v_dot2_f32_bf16 takes the packed
+  // pairs as they are (bf16 products are exact in fp32, the accumulation is fp32)
+  static __device__ __forceinline__ float dot(const V16& a, const V16& b, float acc) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w[i]),
+                                            __builtin_bit_cast(bf16x2_t, b.w[i]), acc, false);
+    return acc;
   }
   // round to nearest even, NaN kept quiet
   static __device__ __forceinline__ void store(bf16_t* dst, float v) {
@@ -94,28 +109,63 @@ __device__ __forceinline__ float dpp_mov(float x) {
       float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
 }
 
-// Sum over each group of LPR adjacent lanes; every lane of the group gets the total.
-// quad_perm[1,0,3,2], quad_perm[2,3,0,1], row_half_mirror, row_mirror, then LDS-crossbar
-// shuffles for groups wider than a DPP row of 16.
-template <int LPR>
-__device__ __forceinline__ float group_sum(float x) {
-  if (LPR >= 2) x += dpp_mov<0xB1>(x);
-  if (LPR >= 4) x += dpp_mov<0x4E>(x);
-  if (LPR >= 8) x += dpp_mov<0x141>(x);
-  if (LPR >= 16) x += dpp_mov<0x140>(x);
-  if (LPR >= 32) x += __shfl_xor(x, 16);
-  if (LPR >= 64) x += __shfl_xor(x, 32);
-  return x;
+// Lane l <-> lane l ^ 16 and l ^ 32 exchanges without the LDS crossbar.  The gfx950 permlane
+// swaps exchange, between two registers a and b, the odd rows of 16 lanes of a with the even
+// rows of b (a' = [a0 b0 a2 b2], b' = [a1 b1 a3 b3]), resp. the upper half of a with the lower
+// half of b; swapping a value with a copy of itself therefore leaves both partners of every
+// lane in a' and b'.  Written as inline asm with both registers as in/out operands: the
+// two-result builtin form returned its first result twice with the ROCm 7.2 compiler.  The
+// s_nop pads cover the VALU -> permlane read/write wait states the compiler cannot see.
+__device__ __forceinline__ void swap_rows16(unsigned& a, unsigned& b) {
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ void swap_rows32(unsigned& a, unsigned& b) {
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+template <bool IS_MAX>
+__device__ __forceinline__ float combine(float a, float b) {
+  return IS_MAX ? fmaxf(a, b) : a + b;
+}
+template <bool IS_MAX>
+__device__ __forceinline__ float fold_rows16(float x) {  // x[l] op x[l ^ 16]
+  unsigned a = __builtin_bit_cast(unsigned, x), b = a;
+  swap_rows16(a, b);
+  return combine<IS_MAX>(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
+}
+template <bool IS_MAX>
+__device__ __forceinline__ float fold_rows32(float x) {  // x[l] op x[l ^ 32]
+  unsigned a = __builtin_bit_cast(unsigned, x), b = a;
+  swap_rows32(a, b);
+  return combine<IS_MAX>(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
 }
 
-__device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+// Reduction over each group of LPR adjacent lanes whose lanes hold partials of the SAME
+// quantity; every lane of the group gets the total.  quad_perm[1,0,3,2], quad_perm[2,3,0,1],
+// row_half_mirror, row_mirror (the mirrors are valid because after the first two steps all
+// lanes of a quad agree), then the row swaps.
+template <int LPR, bool IS_MAX = false>
+__device__ __forceinline__ float group_reduce(float x) {
+  if (LPR >= 2) x = combine<IS_MAX>(x, dpp_mov<0xB1>(x));
+  if (LPR >= 4) x = combine<IS_MAX>(x, dpp_mov<0x4E>(x));
+  if (LPR >= 8) x = combine<IS_MAX>(x, dpp_mov<0x141>(x));
+  if (LPR >= 16) x = combine<IS_MAX>(x, dpp_mov<0x140>(x));
+  if (LPR >= 32) x = fold_rows16<IS_MAX>(x);
+  if (LPR >= 64) x = fold_rows32<IS_MAX>(x);
   return x;
 }
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+template <int LPR>
+__device__ __forceinline__ float group_sum(float x) {
+  return group_reduce<LPR, false>(x);
+}
+
+// Sum over the 64 / LV lanes that hold the same column chunk (lanes l, l + LV, l + 2 LV, ...),
+// for lanes that hold DIFFERENT columns: row rotations inside a row of 16, then the row swaps.
+template <int LV>
+__device__ __forceinline__ float column_sum(float x) {
+  if (LV <= 8) x += dpp_mov<0x128>(x);   // row_ror:8
+  if (LV <= 4) x += dpp_mov<0x124>(x);   // row_ror:4
+  if (LV <= 16) x = fold_rows16<false>(x);
+  if (LV <= 32) x = fold_rows32<false>(x);
   return x;
 }
 
@@ -123,13 +173,14 @@ __device__ __forceinline__ float wave_sum(float x) {
 constexpr int kSmallFloats = 512;
 constexpr int kMaxWaves = 16;
 
-// Block-wide max / sum of G per-thread values.  `red` holds kMaxWaves * G floats.
-// Waves are combined in wave order, so the result does not depend on timing.
+// Block-wide max / sum of G per-thread values with ONE barrier: every wave reduces its lanes
+// (DPP + row swaps), lane 0 posts the wave's result, and after the barrier every thread
+// combines the nw posted values in wave order (so the result does not depend on timing).
+// `red` holds kMaxWaves * G floats and must not be in use by a previous reduction.
 template <int G, bool IS_MAX>
 __device__ __forceinline__ void block_reduce(float (&v)[G], float* red, int lane, int wave, int nw) {
 #pragma unroll
-  for (int g = 0; g < G; ++g) v[g] = IS_MAX ? wave_max(v[g]) : wave_sum(v[g]);
-  __syncthreads();  // previous users of `red` are done
+  for (int g = 0; g < G; ++g) v[g] = group_reduce<64, IS_MAX>(v[g]);
   if (lane == 0) {
 #pragma unroll
     for (int g = 0; g < G; ++g) red[wave * G + g] = v[g];
@@ -138,7 +189,7 @@ __device__ __forceinline__ void block_reduce(float (&v)[G], float* red, int lane
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     float a = red[g];
-    for (int w = 1; w < nw; ++w) a = IS_MAX ? fmaxf(a, red[w * G + g]) : a + red[w * G + g];
+    for (int w = 1; w < nw; ++w) a = combine<IS_MAX>(a, red[w * G + g]);
     v[g] = a;
   }
 }
@@ -154,6 +205,11 @@ __device__ __forceinline__ void st_agent(float* p, float v) {
 }
 __device__ __forceinline__ float ld_agent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_agent2(const float* p) {  // p is 8-byte aligned
+  unsigned long long r = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((uint32_t)r), __uint_as_float((uint32_t)(r >> 32)));
 }
 
 // Elects the last of `expected` arrivals on `counter`.  All threads of the block call it
@@ -175,13 +231,34 @@ __device__ __forceinline__ bool last_arrival(int32_t* counter, int expected, int
 }
 
 // ------------------------------------------------------------------ kernel
-template <typename T, int D, int G, int U>
+// Row geometry.  A row of d elements is CH = d / VEC 16-byte chunks.
+//  * logit pass: LK = CH / CK adjacent lanes share a row, each holding CK chunks
+//    (chunk c * LK + lane), so a wave-level load still covers whole contiguous
+//    rows while the cross-lane sum per (row, head) needs only log2(LK) DPP steps;
+//  * PV pass: one chunk per lane (LV = CH lanes per row), no cross-lane work in
+//    the loop, G * VEC accumulators per lane.
+template <typename T, int D>
+struct Geo {
+  static constexpr int VEC = Elem<T>::VEC;
+  static constexpr int CH = D / VEC;
+  static constexpr int CK = (CH >= 8) ? 2 : 1;
+  static constexpr int LK = CH / CK;
+  static constexpr int RK = 64 / LK;  // rows per wave pass, logit pass
+  static constexpr int UK = 2;        // passes per register buffer (two buffers in flight)
+  static constexpr int LV = CH;
+  static constexpr int RV = 64 / LV;  // rows per wave pass, PV pass
+  static constexpr int UV = 4;
+  static_assert(D % VEC == 0 && CH <= 64 && (CH & (CH - 1)) == 0, "row geometry");
+};
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <typename T, int D, int G>
 __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
   using E = Elem<T>;
-  constexpr int VEC = E::VEC;
-  constexpr int LPR = D / VEC;   // lanes per row
-  constexpr int RPW = 64 / LPR;  // rows per wave-level load
-  static_assert(D % VEC == 0 && LPR >= 1 && LPR <= 64 && (LPR & (LPR - 1)) == 0, "row geometry");
+  using Ge = Geo<T, D>;
+  constexpr int VEC = Ge::VEC, CK = Ge::CK, LK = Ge::LK, RK = Ge::RK, UK = Ge::UK;
+  constexpr int LV = Ge::LV, RV = Ge::RV, UV = Ge::UV;
 
   extern __shared__ float4 smem4[];
   float* small = reinterpret_cast<float*>(smem4);  // kSmallFloats
@@ -193,8 +270,6 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int nw = nt >> 6;
-  const int li = lane % LPR;  // position inside the row
-  const int rg = lane / LPR;  // which of the RPW rows of a wave-level load
 
   // blockIdx -> (pair = (unit, KV head), chunk).  Consecutive block ids go to
   // consecutive XCDs, so the S chunks of one pair are placed on the same XCD
@@ -210,8 +285,9 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
   const int kvh = pair - unit * p.H_kv;
   const int r0 = chunk * R;
   const int r1 = min(r0 + R, n);
-  const int ncached = r1 - r0;
-  const int nloc = ncached + (chunk == c_new ? 1 : 0);  // local candidates, >= 1
+  const int ncached = r1 - r0;                 // cached rows of this chunk
+  const bool has_new = (chunk == c_new);       // local candidate `ncached` is the incoming token
+  const int nloc = ncached + (has_new ? 1 : 0);  // local candidates, >= 1
   const bool full = (n == k);
 
   const T* Kb = reinterpret_cast<const T*>(p.K) + ((size_t)pair * k + r0) * D;
@@ -220,78 +296,139 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
   const T* vnew = reinterpret_cast<const T*>(p.v_new) + (size_t)pair * D;
   const T* qb = reinterpret_cast<const T*>(p.q) + ((size_t)unit * p.H + (size_t)kvh * G) * D;
 
-  float* e_lds = big;  // [nloc][G]
+  float* e_lds = big;  // [nloc][G]: logits (log2 domain), then exp values
+  const float scale2 = p.scale * kLog2e;  // softmax is evaluated as 2^(l2 - max l2)
 
   // ---------------- phase 1: logits ----------------
-  {
-    float qf[G][VEC];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      V16 pk = *reinterpret_cast<const V16*>(qb + g * D + li * VEC);
-      E::unpack(pk, qf[g]);
-    }
-    for (int base = wave * (RPW * U); base < nloc; base += nw * (RPW * U)) {
-      V16 kv[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int i = base + u * RPW + rg;
-        kv[u] = V16{{0u, 0u, 0u, 0u}};
-        if (i < nloc) {
-          const T* row = (i < ncached) ? (Kb + (size_t)i * D) : knew;
-          kv[u] = *reinterpret_cast<const V16*>(row + li * VEC);
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int i = base + u * RPW + rg;
-        float kf[VEC];
-        E::unpack(kv[u], kf);
-        float dot[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-          float a = 0.f;
-#pragma unroll
-          for (int v = 0; v < VEC; ++v) a = fmaf(qf[g][v], kf[v], a);
-          dot[g] = group_sum<LPR>(a) * p.scale;
-        }
-        if (li == 0 && i < nloc) {
-#pragma unroll
-          for (int g = 0; g < G; ++g) e_lds[i * G + g] = dot[g];
-        }
-      }
-    }
-  }
-  __syncthreads();
-
-  // ---------------- phase 2: chunk-local softmax ----------------
-  float m[G], Z[G];
+  float m[G], Z[G];  // chunk-local softmax statistics (log2 domain)
 #pragma unroll
   for (int g = 0; g < G; ++g) m[g] = -INFINITY;
-  for (int i = tid; i < nloc; i += nt) {
+  {
+    const int lk = lane % LK;  // position inside the row
+    const int rk = lane / LK;  // which of the RK rows of a wave pass
+    V16 qf[G][CK];
 #pragma unroll
-    for (int g = 0; g < G; ++g) m[g] = fmaxf(m[g], e_lds[i * G + g]);
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int c = 0; c < CK; ++c)
+        qf[g][c] = *reinterpret_cast<const V16*>(qb + g * D + (c * LK + lk) * VEC);
+
+    auto load_tile = [&](V16(&dst)[UK][CK], int base) {
+#pragma unroll
+      for (int u = 0; u < UK; ++u) {
+        const int i = base + u * RK + rk;
+#pragma unroll
+        for (int c = 0; c < CK; ++c) dst[u][c] = V16{{0u, 0u, 0u, 0u}};
+        if (i < ncached) {
+          const T* row = Kb + (size_t)i * D;
+#pragma unroll
+          for (int c = 0; c < CK; ++c) dst[u][c] = *reinterpret_cast<const V16*>(row + (c * LK + lk) * VEC);
+        }
+      }
+    };
+    auto logits_of = [&](const V16(&row)[CK], float(&l2)[G]) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float a = 0.f;
+#pragma unroll
+        for (int c = 0; c < CK; ++c) a = E::dot(row[c], qf[g][c], a);
+        l2[g] = group_sum<LK>(a) * scale2;
+      }
+    };
+    auto compute_tile = [&](const V16(&src)[UK][CK], int base) {
+#pragma unroll
+      for (int u = 0; u < UK; ++u) {
+        const int i = base + u * RK + rk;
+        float l2[G];
+        logits_of(src[u], l2);
+        if (i < ncached) {
+#pragma unroll
+          for (int g = 0; g < G; ++g) m[g] = fmaxf(m[g], l2[g]);  // running max, per lane
+          if (lk == 0) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) e_lds[i * G + g] = l2[g];
+          }
+        }
+      }
+    };
+
+    constexpr int TILE = RK * UK;  // rows per wave per buffer
+    const int stride = nw * TILE;
+    int base = wave * TILE;
+    V16 bufA[UK][CK], bufB[UK][CK];
+    V16 kn[CK];
+    const bool new_here = has_new && (wave == nw - 1);  // wave-uniform
+    if (new_here) {
+#pragma unroll
+      for (int c = 0; c < CK; ++c) kn[c] = *reinterpret_cast<const V16*>(knew + (c * LK + lk) * VEC);
+    }
+    load_tile(bufA, base);
+    if (new_here) {  // the incoming token is candidate `ncached` (App. B: the last column)
+      float l2[G];
+      logits_of(kn, l2);
+#pragma unroll
+      for (int g = 0; g < G; ++g) m[g] = fmaxf(m[g], l2[g]);
+      if (lane == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) e_lds[ncached * G + g] = l2[g];
+      }
+    }
+    while (base < ncached) {  // two register buffers: the next tile is in flight while this one is used
+      load_tile(bufB, base + stride);
+      compute_tile(bufA, base);
+      base += stride;
+      if (base >= ncached) break;
+      load_tile(bufA, base + stride);
+      compute_tile(bufB, base);
+      base += stride;
+    }
   }
+
+  // The first PV tile is requested now, so that the V stream is already in flight while the
+  // block goes through the softmax barriers.
+  const int lv = lane % LV;
+  const int rv = lane / LV;
+  constexpr int TILEV = RV * UV;
+  const int stridev = nw * TILEV;
+  auto load_vtile = [&](V16(&dst)[UV], int base) {
+#pragma unroll
+    for (int u = 0; u < UV; ++u) {
+      const int i = base + u * RV + rv;
+      dst[u] = V16{{0u, 0u, 0u, 0u}};
+      if (i < ncached) dst[u] = *reinterpret_cast<const V16*>(Vb + (size_t)i * D + lv * VEC);
+    }
+  };
+  V16 vA[UV], vB[UV];
+  int basev = wave * TILEV;
+  load_vtile(vA, basev);
+
+  // ---------------- phase 2: chunk-local softmax ----------------
+  // The barrier inside this reduction is also the one that makes the logits visible.
   block_reduce<G, true>(m, small, lane, wave, nw);
 #pragma unroll
   for (int g = 0; g < G; ++g) Z[g] = 0.f;
   for (int i = tid; i < nloc; i += nt) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      float e = expf(e_lds[i * G + g] - m[g]);
+      float e = __builtin_amdgcn_exp2f(e_lds[i * G + g] - m[g]);
       e_lds[i * G + g] = e;
       Z[g] += e;
     }
   }
+  // ... and the barrier inside this one completes e_lds for the PV pass.
   block_reduce<G, false>(Z, small + kMaxWaves * G, lane, wave, nw);
 
   // Score contributions leave LDS now (each thread re-reads only what it wrote itself).
   if (full) {
     if (S == 1) {
+      float rz[G];
+#pragma unroll
+      for (int g = 0; g < G; ++g) rz[g] = 1.0f / Z[g];
       float* sg = p.sg + (size_t)pair * p.kp;
       for (int i = tid; i < nloc; i += nt) {
         float a = 0.f;
 #pragma unroll
-        for (int g = 0; g < G; ++g) a += e_lds[i * G + g] / Z[g];
+        for (int g = 0; g < G; ++g) a = fmaf(e_lds[i * G + g], rz[g], a);
         st_agent(sg + i, a);
       }
     } else {
@@ -302,7 +439,6 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
       }
     }
   }
-  __syncthreads();  // e_lds complete for everyone
 
   // ---------------- phase 3: PV ----------------
   float acc[G][VEC];
@@ -310,48 +446,54 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
   for (int g = 0; g < G; ++g)
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[g][v] = 0.f;
-  for (int base = wave * (RPW * U); base < nloc; base += nw * (RPW * U)) {
-    V16 vv[U];
+  auto accumulate = [&](const V16& row, const float(&w)[G]) {
+    float vf[VEC];
+    E::unpack(row, vf);
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int i = base + u * RPW + rg;
-      vv[u] = V16{{0u, 0u, 0u, 0u}};
-      if (i < nloc) {
-        const T* row = (i < ncached) ? (Vb + (size_t)i * D) : vnew;
-        vv[u] = *reinterpret_cast<const V16*>(row + li * VEC);
-      }
-    }
+    for (int g = 0; g < G; ++g)
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int i = base + u * RPW + rg;
-      float vf[VEC];
-      E::unpack(vv[u], vf);
+      for (int v = 0; v < VEC; ++v) acc[g][v] = fmaf(w[g], vf[v], acc[g][v]);
+  };
+  auto compute_vtile = [&](const V16(&src)[UV], int base) {
+#pragma unroll
+    for (int u = 0; u < UV; ++u) {
+      const int i = base + u * RV + rv;
       float w[G];
 #pragma unroll
-      for (int g = 0; g < G; ++g) w[g] = (i < nloc) ? e_lds[i * G + g] : 0.f;
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) acc[g][v] = fmaf(w[g], vf[v], acc[g][v]);
+      for (int g = 0; g < G; ++g) w[g] = (i < ncached) ? e_lds[i * G + g] : 0.f;
+      accumulate(src[u], w);
     }
+  };
+  if (has_new && wave == nw - 1) {  // the incoming token's own value row
+    V16 vn = *reinterpret_cast<const V16*>(vnew + lv * VEC);
+    float w[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) w[g] = (rv == 0) ? e_lds[ncached * G + g] : 0.f;
+    accumulate(vn, w);
   }
-  // combine the RPW row groups of the wave, then the waves (in wave order)
+  while (basev < ncached) {
+    load_vtile(vB, basev + stridev);
+    compute_vtile(vA, basev);
+    basev += stridev;
+    if (basev >= ncached) break;
+    load_vtile(vA, basev + stridev);
+    compute_vtile(vB, basev);
+    basev += stridev;
+  }
+  // combine the RV row groups of the wave, then the waves (in wave order)
 #pragma unroll
   for (int g = 0; g < G; ++g)
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
-      float a = acc[g][v];
-#pragma unroll
-      for (int o = LPR; o < 64; o <<= 1) a += __shfl_xor(a, o);
-      acc[g][v] = a;
+      acc[g][v] = column_sum<LV>(acc[g][v]);
     }
   __syncthreads();  // everyone is done reading e_lds; reuse the area
   float* red = big;  // [nw][G*D]
-  if (rg == 0) {
+  if (rv == 0) {
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) red[(wave * G + g) * D + li * VEC + v] = acc[g][v];
+      for (int v = 0; v < VEC; ++v) red[(wave * G + g) * D + lv * VEC + v] = acc[g][v];
   }
   __syncthreads();
 
@@ -394,8 +536,8 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
     } else {
       __syncthreads();
     }
-    // global normalisers: m_g = max_c m_c, Z_g = sum_c Z_c exp(m_c - m_g)
-    float* wl = big;                  // [nact][G]  exp(m_c - m_g)
+    // global normalisers (log2 domain): m_g = max_c m_c, Z_g = sum_c Z_c 2^(m_c - m_g)
+    float* wl = big;                  // [nact][G]  2^(m_c - m_g)
     float* zl = big + nact * G;       // [G]
     __syncthreads();
     if (tid < G) {
@@ -404,7 +546,7 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
       for (int c = 0; c < nact; ++c) mg = fmaxf(mg, ld_agent(st + (size_t)c * G * 2));
       float zg = 0.f;
       for (int c = 0; c < nact; ++c) {
-        float w = expf(ld_agent(st + (size_t)c * G * 2) - mg);
+        float w = __builtin_amdgcn_exp2f(ld_agent(st + (size_t)c * G * 2) - mg);
         wl[c * G + tid] = w;
         zg += ld_agent(st + (size_t)c * G * 2 + 1) * w;
       }
@@ -456,17 +598,49 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
   }
-  // head-mean score (as a sum: the factor 1/H does not move the argmin) over the k+1
-  // candidates, KV-head partials added in head order; lowest index wins ties.
+  // Head-mean score over the k+1 candidates (as a sum: the factor 1/H does not move the
+  // argmin), KV-head partials added in head order; lowest index wins ties.  Candidates are
+  // read two at a time and all of a thread's loads are issued before the first is used: the
+  // loads bypass the caches, so their latency must be overlapped, not serialised.
   const float* sgu = p.sg + (size_t)unit * p.H_kv * p.kp;
+  const int npair2 = (k + 2) / 2;  // candidate pairs (2m, 2m+1) covering 0..k
   float best = INFINITY;
   int bj = 0x7fffffff;
-  for (int j = tid; j <= k; j += nt) {
-    float s = ld_agent(sgu + j);
-    for (int h = 1; h < p.H_kv; ++h) s += ld_agent(sgu + (size_t)h * p.kp + j);
-    if (s < best) {
-      best = s;
-      bj = j;
+  constexpr int JB = 2, HB = 8;
+  for (int m0 = tid; m0 < npair2; m0 += nt * JB) {
+    float s0[JB], s1[JB];
+#pragma unroll
+    for (int b = 0; b < JB; ++b) s0[b] = s1[b] = 0.f;
+    for (int h0 = 0; h0 < p.H_kv; h0 += HB) {
+      float2 raw[JB][HB];
+#pragma unroll
+      for (int b = 0; b < JB; ++b) {
+        const int mm = m0 + b * nt;
+#pragma unroll
+        for (int u = 0; u < HB; ++u) {
+          raw[b][u] = make_float2(0.f, 0.f);
+          if (mm < npair2 && h0 + u < p.H_kv) raw[b][u] = ld_agent2(sgu + (size_t)(h0 + u) * p.kp + 2 * mm);
+        }
+      }
+#pragma unroll
+      for (int b = 0; b < JB; ++b)
+#pragma unroll
+        for (int u = 0; u < HB; ++u) {
+          s0[b] += raw[b][u].x;
+          s1[b] += raw[b][u].y;
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < JB; ++b) {
+      const int j0 = 2 * (m0 + b * nt);
+      if (j0 <= k && s0[b] < best) {
+        best = s0[b];
+        bj = j0;
+      }
+      if (j0 + 1 <= k && s1[b] < best) {
+        best = s1[b];
+        bj = j0 + 1;
+      }
     }
   }
 #pragma unroll
@@ -523,7 +697,7 @@ __global__ void tova_fill_i32_kernel(int32_t* dst, int32_t value, size_t count) 
 
 template <typename T, int D, int G>
 hipError_t launch_one(const StepParams& p, const LaunchPlan& lp, hipStream_t stream) {
-  hipLaunchKernelGGL((tova_step_kernel<T, D, G, kUnroll>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes,
+  hipLaunchKernelGGL((tova_step_kernel<T, D, G>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes,
                      stream, p);
   return hipGetLastError();
 }
