@@ -116,6 +116,13 @@ int tova_decode_steps(tova_cache_t* cache, int32_t n_steps, const void* q, const
 /* Number of tokens the cache has seen since tova_cache_init (HOST out pointer). */
 int tova_cache_tokens_seen(const tova_cache_t* cache, int64_t* t);
 
+/* Checkpoint / resume.  The whole state of a cache is the caller's kv_mem and state_mem plus
+ * this token count: a caller that has copied those buffers back (e.g. from a snapshot taken
+ * after t tokens) tells the library so with this call; the next step then treats the cache as
+ * holding min(t, k) rows and numbers the incoming token t.  The occupancy array in state_mem
+ * must agree (it does if it was restored together with the rest).  t >= 0. */
+int tova_cache_set_tokens_seen(tova_cache_t* cache, int64_t t);
+
 /* Frees the host descriptor only; device buffers stay with the caller. */
 int tova_cache_destroy(tova_cache_t* cache);
 

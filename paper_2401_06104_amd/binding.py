@@ -59,11 +59,13 @@ def load_library() -> ctypes.CDLL:
     lib.tova_decode_steps.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                       c_void_p, c_void_p]
     lib.tova_cache_tokens_seen.argtypes = [c_void_p, POINTER(c_int64)]
+    lib.tova_cache_set_tokens_seen.argtypes = [c_void_p, c_int64]
     lib.tova_cache_destroy.argtypes = [c_void_p]
     lib.tova_strerror.argtypes = [c_int]
     lib.tova_strerror.restype = c_char_p
     for name in ("tova_cache_bytes", "tova_cache_layout", "tova_cache_init", "tova_decode_step",
-                 "tova_decode_steps", "tova_cache_tokens_seen", "tova_cache_destroy"):
+                 "tova_decode_steps", "tova_cache_tokens_seen", "tova_cache_set_tokens_seen",
+                 "tova_cache_destroy"):
         getattr(lib, name).restype = c_int
     _LIB = lib
     return lib
@@ -159,6 +161,11 @@ class TovaCache:
         if rc != TOVA_OK:
             raise TovaError(rc, "tova_cache_tokens_seen")
         return t.value
+
+    def set_tokens_seen(self, t: int):
+        rc = self.lib.tova_cache_set_tokens_seen(self._h, int(t))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_cache_set_tokens_seen")
 
     # ---- the calls ----------------------------------------------------------
     def _check(self, name, x, shape):

@@ -249,6 +249,13 @@ int tova_cache_tokens_seen(const tova_cache_t* c, int64_t* t) {
   return TOVA_OK;
 }
 
+int tova_cache_set_tokens_seen(tova_cache_t* c, int64_t t) {
+  if (!c || t < 0) return TOVA_EINVAL;
+  if (t > 0x7fffffffLL) return TOVA_ENOSUP;
+  c->t = t;
+  return TOVA_OK;
+}
+
 int tova_cache_destroy(tova_cache_t* c) {
   if (!c) return TOVA_EINVAL;
   delete c;

@@ -26,19 +26,39 @@ GAP_EXEMPT = 1e-6
 
 
 def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: int = 256,
-            single_step_calls: bool = False, device="cuda:0"):
-    """units: list of (layer, seq) whose outputs are kept.  Returns a dict of CPU arrays."""
+            single_step_calls: bool = False, device="cuda:0", prefill: bool = False, keep=None,
+            progress: bool = False):
+    """units: list of (layer, seq) whose outputs are kept.  Returns a dict of CPU arrays.
+
+    prefill=True skips the fill phase: the first k tokens are laid down directly (slot j holds
+    token j, which is exactly what k fill steps produce -- App. B's no-op branch) and stepping
+    starts at token k through tova_cache_set_tokens_seen.
+    keep: list of (t0, t1) step ranges whose outputs are kept (default: all steps)."""
     from paper_2401_06104_amd import TovaCache
 
     dev = torch.device(device)
     cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype,
                       n_splits=n_splits, device=dev)
     stream = Stream(spec, seed, device=dev)
-    evicted = torch.empty(spec.T, spec.L, spec.B, dtype=torch.int32, device=dev)
+    evicted = torch.full((spec.T, spec.L, spec.B), -1, dtype=torch.int32, device=dev)
     ul = torch.tensor([u[0] for u in units], device=dev)
     ub = torch.tensor([u[1] for u in units], device=dev)
-    outs = []
-    for t0 in range(0, spec.T, chunk_steps):
+    t_begin = spec.k if prefill else 0
+    default_keep = keep is None
+    keep = [(t_begin, spec.T)] if keep is None else keep
+    outs = {r: [] for r in keep}
+    if prefill:
+        assert spec.T > spec.k
+        K, V = cache.K, cache.V
+        for t0 in range(0, spec.k, chunk_steps):
+            t1 = min(spec.k, t0 + chunk_steps)
+            c = stream.chunk(t0, t1, need_q=False)
+            K[:, :, :, t0:t1, :] = c["k"].permute(1, 2, 3, 0, 4)
+            V[:, :, :, t0:t1, :] = c["v"].permute(1, 2, 3, 0, 4)
+        cache.occupancy.fill_(spec.k)
+        cache.slot_token.copy_(torch.arange(spec.k, dtype=torch.int32, device=dev).expand_as(cache.slot_token))
+        cache.set_tokens_seen(spec.k)
+    for t0 in range(t_begin, spec.T, chunk_steps):
         t1 = min(spec.T, t0 + chunk_steps)
         c = stream.chunk(t0, t1)
         out = torch.empty_like(c["q"])
@@ -47,10 +67,16 @@ def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: 
                 cache.decode_step(c["q"][i], c["k"][i], c["v"][i], out[i], evicted[t0 + i])
         else:
             cache.decode_steps(c["q"], c["k"], c["v"], out, evicted[t0:t1])
-        outs.append(out[:, ul, ub].float().cpu())
+        for (a, b) in keep:
+            lo, hi = max(a, t0), min(b, t1)
+            if lo < hi:
+                outs[(a, b)].append(out[lo - t0:hi - t0][:, ul, ub].float().cpu())
+        if progress and (t0 // chunk_steps) % 16 == 0:
+            torch.cuda.synchronize(dev)
+            print(f"[parity]   gpu at step {t1}/{spec.T}", flush=True)
     torch.cuda.synchronize(dev)
     res = {
-        "out": torch.cat(outs).numpy(),                       # [T, n_units, H, d] float32
+        "out": {r: (torch.cat(v).numpy() if v else None) for r, v in outs.items()},   # [t, n_units, H, d] f32
         "evicted": evicted.cpu().numpy(),                     # [T, L, B]
         "slot_token": cache.slot_token.cpu().numpy(),         # [L, B, k]
         "occupancy": cache.occupancy.cpu().numpy(),
@@ -59,15 +85,56 @@ def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: 
         "layout": (cache.layout.n_splits, cache.layout.rows_per_split, cache.layout.block_threads,
                    cache.layout.grid_blocks),
         "tokens_seen": cache.tokens_seen,
+        "prefill": prefill,
     }
+    if default_keep:
+        res["out"] = res["out"][(t_begin, spec.T)]
+        res["out_t0"] = t_begin
     cache.destroy()
     return res
 
 
+def _compare_step(spec, unit, t, orc, q, kk, vv, gpu_out_t, ge, stats, tol):
+    """One oracle step against the GPU's output / victim of the same step (bars in the header)."""
+    out, p = orc.attend(q, kk, vv)
+    if gpu_out_t is not None:
+        g = gpu_out_t.astype(np.float64)
+        err = np.abs(g - out).max(axis=1) / np.maximum(np.abs(out).max(axis=1), 1e-30)
+        worst = float(err.max())
+        assert worst <= tol, f"unit {unit} step {t}: output rel err {worst:.3e} > {tol}"
+        stats["max_rel_err"] = max(stats["max_rel_err"], worst)
+    ge = int(ge)
+    if orc.n + 1 <= spec.k:
+        assert ge == -1, f"unit {unit} step {t}: GPU evicted {ge} while filling"
+        orc.update(-1, kk, vv)
+        return
+    s = orc.scores(p)
+    j, gap = orc.select(s)
+    stats["evict_steps"] += 1
+    stats["min_gap"] = min(stats["min_gap"], gap)
+    if gap < GAP_EXEMPT:
+        stats["near_tie_steps"] += 1
+    assert 0 <= ge <= spec.k, f"unit {unit} step {t}: GPU victim {ge} out of range"
+    if ge != j:
+        ok = gap < GAP_EXEMPT and (s[ge] - s[j]) < GAP_EXEMPT
+        assert ok, (f"unit {unit} step {t}: GPU victim {ge} != oracle {j}, "
+                    f"gap {gap:.3e}, s[gpu]-min {s[ge] - s[j]:.3e}")
+        stats["mismatches"] += 1
+        stats["max_gap_at_mismatch"] = max(stats["max_gap_at_mismatch"], float(s[ge] - s[j]))
+    orc.update(ge, kk, vv)     # == j unless a counted near-tie
+
+
+def _new_stats(unit, steps):
+    return dict(unit=unit, steps=steps, evict_steps=0, near_tie_steps=0, mismatches=0, max_rel_err=0.0,
+                max_gap_at_mismatch=0.0, min_gap=float("inf"))
+
+
 def check_unit(spec: StreamSpec, seed: int, unit, gpu_out, gpu_evicted, gpu_slot_token, gpu_K, gpu_V,
-               t_stop=None):
-    """Steps the oracle over unit=(layer, seq) and compares with the GPU's log.
-    gpu_out [T, H, d], gpu_evicted [T], gpu_slot_token [k], gpu_K / gpu_V [H_kv, k, d].
+               t_stop=None, prefill=False, out_t0=0):
+    """Steps the oracle over unit=(layer, seq) from the start of the stream (or, with prefill,
+    from the state "slot j holds token j") and compares with the GPU's log.
+    gpu_out [t, H, d] holds steps out_t0.. ; gpu_evicted [T]; gpu_slot_token [k]; gpu_K / gpu_V
+    [H_kv, k, d] are the final cache (compared only when the whole stream is checked).
     Returns a dict of statistics; raises AssertionError on any violation."""
     from oracle.tova_oracle import TovaOracle
 
@@ -76,43 +143,24 @@ def check_unit(spec: StreamSpec, seed: int, unit, gpu_out, gpu_evicted, gpu_slot
     tol = OUT_TOL[spec.dtype]
     st = Stream(spec, seed, device="cpu", layers=[l], seqs=[b])
     orc = TovaOracle(spec.k, spec.H, spec.H_kv, spec.d)
-    stats = dict(unit=unit, steps=T, evict_steps=0, near_tie_steps=0, mismatches=0, max_rel_err=0.0,
-                 max_gap_at_mismatch=0.0, min_gap=float("inf"))
+    stats = _new_stats(unit, T)
     kk_all, vv_all = [], []
     for t0 in range(0, T, 512):
         t1 = min(T, t0 + 512)
-        c = st.chunk(t0, t1)
-        q = c["q"][:, 0, 0].double().numpy()
+        filling = prefill and t1 <= spec.k
+        c = st.chunk(t0, t1, need_q=not filling)
         kk = c["k"][:, 0, 0].double().numpy()
         vv = c["v"][:, 0, 0].double().numpy()
-        kk_all.append(kk); vv_all.append(vv)
+        if t_stop is None:
+            kk_all.append(kk); vv_all.append(vv)
+        q = None if filling else c["q"][:, 0, 0].double().numpy()
         for i in range(t1 - t0):
             t = t0 + i
-            out, p = orc.attend(q[i], kk[i], vv[i])
-            g = gpu_out[t].astype(np.float64)
-            err = np.abs(g - out).max(axis=1) / np.maximum(np.abs(out).max(axis=1), 1e-30)
-            worst = float(err.max())
-            assert worst <= tol, f"unit {unit} step {t}: output rel err {worst:.3e} > {tol}"
-            stats["max_rel_err"] = max(stats["max_rel_err"], worst)
-            ge = int(gpu_evicted[t])
-            if orc.n + 1 <= spec.k:
-                assert ge == -1, f"unit {unit} step {t}: GPU evicted {ge} while filling"
-                orc.update(-1, kk[i], vv[i])
+            if prefill and t < spec.k:
+                orc.update(-1, kk[i], vv[i])         # the no-op branch: the row takes slot t
                 continue
-            s = orc.scores(p)
-            j, gap = orc.select(s)
-            stats["evict_steps"] += 1
-            stats["min_gap"] = min(stats["min_gap"], gap)
-            if gap < GAP_EXEMPT:
-                stats["near_tie_steps"] += 1
-            assert 0 <= ge <= spec.k, f"unit {unit} step {t}: GPU victim {ge} out of range"
-            if ge != j:
-                ok = gap < GAP_EXEMPT and (s[ge] - s[j]) < GAP_EXEMPT
-                assert ok, (f"unit {unit} step {t}: GPU victim {ge} != oracle {j}, "
-                            f"gap {gap:.3e}, s[gpu]-min {s[ge] - s[j]:.3e}")
-                stats["mismatches"] += 1
-                stats["max_gap_at_mismatch"] = max(stats["max_gap_at_mismatch"], float(s[ge] - s[j]))
-            orc.update(ge, kk[i], vv[i])     # == j unless a counted near-tie
+            g = gpu_out[t - out_t0] if gpu_out is not None and t >= out_t0 else None
+            _compare_step(spec, unit, t, orc, q[i], kk[i], vv[i], g, gpu_evicted[t], stats, tol)
     if t_stop is None:
         assert np.array_equal(orc.slot_token, gpu_slot_token.astype(np.int64)), f"unit {unit}: slot_token differs"
         n = orc.n
@@ -127,16 +175,77 @@ def check_unit(spec: StreamSpec, seed: int, unit, gpu_out, gpu_evicted, gpu_slot
     return stats
 
 
+def check_window(spec: StreamSpec, seed: int, unit, t0, t1, slot_token_t0, gpu_out, gpu_evicted):
+    """PROPERTY check, not parity from the start: every step in [t0, t1) is a correct TOVA
+    transition from the state the run itself was in at t0.  That state is rebuilt from the
+    stream (rows) and the integer slot -> token map implied by the GPU's evicted log, so an
+    earlier wrong victim would go unnoticed here; what is checked is that, far into a long
+    stream, outputs and victims still follow from the cached rows.
+    gpu_out [t1 - t0, H, d], gpu_evicted [T]."""
+    from oracle.tova_oracle import TovaOracle
+
+    l, b = unit
+    tol = OUT_TOL[spec.dtype]
+    st = Stream(spec, seed, device="cpu", layers=[l], seqs=[b])
+    need = sorted(set(int(x) for x in slot_token_t0 if x >= 0))
+    rows_k, rows_v = {}, {}
+    orc = TovaOracle(spec.k, spec.H, spec.H_kv, spec.d)
+    stats = _new_stats(unit, t1 - t0)
+    needed = set(need)
+    for a in range(0, t1, 2048):
+        bnd = min(t1, a + 2048)
+        c = st.chunk(a, bnd, need_q=bnd > t0)
+        if a < t0:
+            kk = c["k"][:, 0, 0]
+            vv = c["v"][:, 0, 0]
+            for t in range(a, min(bnd, t0)):
+                if t in needed:
+                    rows_k[t] = kk[t - a].double().numpy()
+                    rows_v[t] = vv[t - a].double().numpy()
+        if bnd > t0:
+            if orc.t == 0:       # lay the state down once, just before the first checked step
+                for slot, tk in enumerate(slot_token_t0):
+                    if tk >= 0:
+                        orc.K[:, slot] = rows_k[int(tk)]
+                        orc.V[:, slot] = rows_v[int(tk)]
+                orc.slot_token[:] = slot_token_t0
+                orc.n = int((slot_token_t0 >= 0).sum())
+                orc.t = t0
+            q = c["q"][:, 0, 0].double().numpy()
+            kk = c["k"][:, 0, 0].double().numpy()
+            vv = c["v"][:, 0, 0].double().numpy()
+            for t in range(max(a, t0), bnd):
+                _compare_step(spec, unit, t, orc, q[t - a], kk[t - a], vv[t - a], gpu_out[t - t0],
+                              gpu_evicted[t], stats, tol)
+    return stats
+
+
+def replay_slot_tokens(evicted_unit, k, t_stop):
+    """slot -> token map after t_stop steps, from one unit's evicted log alone (integers)."""
+    st = np.full(k, -1, dtype=np.int64)
+    for t in range(t_stop):
+        if t < k:
+            st[t] = t
+        else:
+            e = int(evicted_unit[t])
+            if e < k:
+                st[e] = t
+    return st
+
+
 def _check_unit_star(args):
     return check_unit(*args)
 
 
-def check_units(spec, seed, units, res, workers: int = 1, t_stop=None):
+def check_units(spec, seed, units, res, workers: int = 1, t_stop=None, out=None, out_t0=None):
     """Checks every sampled unit; with workers > 1 in spawned CPU-only processes."""
     jobs = []
+    out = res["out"] if out is None else out
+    out_t0 = res.get("out_t0", 0) if out_t0 is None else out_t0
     for ui, (l, b) in enumerate(units):
-        jobs.append((spec, seed, (l, b), res["out"][:, ui], res["evicted"][:, l, b],
-                     res["slot_token"][l, b], res["K"][ui], res["V"][ui], t_stop))
+        jobs.append((spec, seed, (l, b), out[:, ui], res["evicted"][:, l, b],
+                     res["slot_token"][l, b], res["K"][ui], res["V"][ui], t_stop, res.get("prefill", False),
+                     out_t0))
     if workers <= 1 or len(jobs) == 1:
         return [check_unit(*j) for j in jobs]
     import multiprocessing as mp
@@ -149,7 +258,7 @@ def check_global_invariants(spec, res):
     ev = res["evicted"]
     k = spec.k
     fill = min(k, spec.T)
-    assert (ev[:fill] == -1).all(), "a unit evicted before its cache was full"
+    assert (ev[:fill] == -1).all(), "a unit evicted before its cache was full"  # (prefill: never written)
     if spec.T > k:
         assert ((ev[k:] >= 0) & (ev[k:] <= k)).all(), "victim out of range after capacity"
     assert (res["occupancy"] == min(spec.T, k)).all()

@@ -265,16 +265,18 @@ class Stream:
         self._walk = {}
 
     # ---- main entry --------------------------------------------------------
-    def chunk(self, t0: int, t1: int) -> Dict[str, torch.Tensor]:
+    def chunk(self, t0: int, t1: int, need_q: bool = True) -> Dict[str, torch.Tensor]:
+        """Steps t0..t1-1.  With need_q=False the queries are not generated (the returned
+        "q" is None): used to lay down cached rows without stepping through them."""
         s = self.spec
         assert 0 <= t0 < t1 <= s.T, (t0, t1, s.T)
         T = t1 - t0
-        q = self._gauss(_T_Q, self._idx["q"], t0, t1)
+        q = self._gauss(_T_Q, self._idx["q"], t0, t1) if need_q else None
         k = self._gauss(_T_K, self._idx["kv"], t0, t1)
         v = self._gauss(_T_V, self._idx["kv"], t0, t1)
         if s.elem_scale != 1.0:
             c = float(np.float32(s.elem_scale))
-            q, k, v = q * c, k * c, v * c
+            q, k, v = (q * c if need_q else None), k * c, v * c
 
         if s.drift_sigma > 0.0:
             if t0 != self._walk_t:
@@ -293,7 +295,7 @@ class Stream:
                 self._walk[name] = w[-1].clone()
                 mu = w.to(torch.float32) * c    # |w| < 2^24: exact conversion, one rounding
                 if name == "q":
-                    q = q + mu
+                    q = q + mu if need_q else None
                 elif name == "k":
                     k = k + mu
                 else:
@@ -318,11 +320,12 @@ class Stream:
             if bool(m.any()):
                 m = m.to(self.device).view(T, 1, len(self.seqs), 1, 1)
                 k = torch.where(m, k + self._k_bias, k)
-        if s.q_align != 0.0:
+        if s.q_align != 0.0 and need_q:
             q = q + self._q_bias
 
         dt = s.torch_dtype
-        return {"q": q.to(dt).contiguous(), "k": k.to(dt).contiguous(), "v": v.to(dt).contiguous()}
+        return {"q": q.to(dt).contiguous() if need_q else None,
+                "k": k.to(dt).contiguous(), "v": v.to(dt).contiguous()}
 
     def boosted(self, t0: int, t1: int) -> torch.Tensor:
         """[T, Ls, Bs] bool: which tokens got the key-norm boost (for inspection)."""
