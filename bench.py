@@ -40,7 +40,7 @@ def algorithmic_bytes_per_step(spec) -> int:
     return per_unit * spec.L * spec.B
 
 
-def gpu_leg(spec, seed, steps, warmup, device, chunk=256):
+def gpu_leg(spec, seed, steps, warmup, device, chunk=256, prefill=False):
     import torch
     from paper_2401_06104_amd import TovaCache
     from workloads import Stream
@@ -63,7 +63,19 @@ def gpu_leg(spec, seed, steps, warmup, device, chunk=256):
                 outs.append(ev)
         return outs
 
-    run(0, spec.k)                                   # fill: untimed, same entry point
+    if prefill:
+        # lay the first k tokens down directly (slot j = token j, what k fill steps produce), so that
+        # every step-kernel dispatch of this process runs at full occupancy (used for profiling)
+        for a in range(0, spec.k, chunk):
+            b = min(spec.k, a + chunk)
+            c = stream.chunk(a, b, need_q=False)
+            cache.K[:, :, :, a:b, :] = c["k"].permute(1, 2, 3, 0, 4)
+            cache.V[:, :, :, a:b, :] = c["v"].permute(1, 2, 3, 0, 4)
+        cache.occupancy.fill_(spec.k)
+        cache.slot_token.copy_(torch.arange(spec.k, dtype=torch.int32, device=dev).expand_as(cache.slot_token))
+        cache.set_tokens_seen(spec.k)
+    else:
+        run(0, spec.k)                               # fill: untimed, same entry point
     if warmup:
         run(spec.k, spec.k + warmup)                 # untimed full-occupancy steps
     # stage every timed input in HBM first
@@ -146,6 +158,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hbm-variant", action="store_true",
                     help="skip the extra 32-layer run whose 8 GiB cache cannot sit in the last-level cache")
+    ap.add_argument("--prefill", action="store_true",
+                    help="lay the first k tokens down directly instead of running k fill steps, so that every "
+                         "step-kernel dispatch in the process is a full-occupancy one (for rocprofv3 --stats)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy kernel of known size (1 GiB in, 1 GiB out) five "
                          "times, so that hardware byte counters collected over this run can be scaled")
@@ -162,7 +177,7 @@ def main():
     from workloads import spec_for
 
     spec = spec_for("c3_mistral_gqa", L=args.layers, T=1024 + args.warmup + args.steps)
-    g = gpu_leg(spec, args.seed, args.steps, args.warmup, "cuda:0")
+    g = gpu_leg(spec, args.seed, args.steps, args.warmup, "cuda:0", prefill=args.prefill)
     ms_per_step = g["event_ms"] / args.steps
     abytes = algorithmic_bytes_per_step(spec)
     achieved = abytes / (ms_per_step * 1e-3) / 1e9
