@@ -25,6 +25,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+# Bytes that left L2 per launch of the step kernel on this workload, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this script, each scaled by what the same counter reads for a 1 GiB copy kernel
+# (summary: profiles/tova_step_kernel_c3_mistral_gqa.txt).  Not measured live.
+PROFILED_TRAFFIC_BYTES_PER_LAUNCH = 274.8e6
 
 
 def algorithmic_bytes_per_step(spec) -> int:
@@ -194,7 +198,8 @@ def main():
                                "at full occupancy", "seed": args.seed, "plan": g["plan"],
                    "sequence_steps_per_s": 1e3 / ms_per_step * spec.L * spec.B},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": PROFILED_TRAFFIC_BYTES_PER_LAUNCH if spec.L == 1 else None,
                      "kernel": "tova_step_kernel<bf16, d=128, G=4>", "algorithmic_bytes_per_launch": abytes,
                      "avg_launch_us": ms_per_step * 1e3},
         "sane": g["sane"], "new_token_dropped_frac": g["new_token_dropped_frac"],
