@@ -25,12 +25,12 @@ size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Resolved {
   int L, B, k, H, H_kv, G, D, esize, bf16;
-  int units, pairs, S, R, kp, NT, grid, lds;
+  int units, pairs, S, R, kp, NT, grid, lds, st_off, spin_limit, force_slow;
   float scale;
   size_t kv_bytes, state_bytes, scratch_bytes;
   size_t v_off;                                   // in kv_mem
   size_t occ_off, slot_off;                       // in state_mem
-  size_t cnt_pair_off, cnt_unit_off, cnt_bytes;   // in scratch_mem
+  size_t cnt_pair_off, cnt_unit_off, cnt_pub_off, slow_off, cnt_bytes;   // in scratch_mem
   size_t sg_off, escr_off, stats_off, accp_off;
 };
 
@@ -61,34 +61,60 @@ int resolve(const tova_config_t* c, Resolved* r) {
   const int k = r->k;
   int S = c->n_splits;
   if (S <= 0) {
-    S = (r->pairs >= kTargetBlocks) ? 1 : (kTargetBlocks + r->pairs - 1) / r->pairs;
+    int target = kTargetBlocks;
+    if (const char* e = std::getenv("TOVA_TARGET_BLOCKS")) {  // tuning aid
+      int v = std::atoi(e);
+      if (v >= 1 && v <= (1 << 20)) target = v;
+    }
+    S = (r->pairs >= target) ? 1 : (target + r->pairs - 1) / r->pairs;
     int smax = k / kMinRowsPerSplit;
     if (smax < 1) smax = 1;
     if (S > smax) S = smax;
   }
-  const int big_cap = kMaxLdsBytes / 4 - kSmallFloats;  // floats available for the big LDS area
-  const int r_cap = big_cap / G - 1;                    // logits of R slots + the new token
-  const int s_lds = (k + r_cap - 1) / r_cap;
-  if (S < s_lds) S = s_lds;
   if (S > k) S = k;
-  int R = (k + S - 1) / S;
-  S = (k + R - 1) / R;
-  r->S = S; r->R = R;
-  r->kp = (int)round_up((size_t)k + 1, 64);
-
-  int NT = (R >= 256) ? 512 : 256;
+  int nt_env = 0;
   if (const char* e = std::getenv("TOVA_BLOCK_THREADS")) {  // tuning aid: 64..512, multiple of 64
     int v = std::atoi(e);
-    if (v >= 64 && v <= 512 && v % 64 == 0) NT = v;
+    if (v >= 64 && v <= 512 && v % 64 == 0) nt_env = v;
   }
-  r->NT = NT;
-  long long big = (long long)(R + 1) * G;
-  const long long red = (long long)(NT / 64) * G * r->D;
-  if (red > big) big = red;
-  if ((long long)S * G + G > big) big = (long long)S * G + G;
-  if (big > big_cap) return TOVA_ENOSUP;
+  const int big_cap = kMaxLdsBytes / 4 - kSmallFloats;  // floats available for the big LDS area
+  // LDS: logits / exp values of R slots + the new token; the cross-wave reduction area reuses that
+  // memory after the PV pass; with several chunks per KV head a small area behind both holds all
+  // chunks' softmax statistics and the finisher's merge weights.
+  int R = (k + S - 1) / S, NT;
+  long long big, st_off;
+  for (;;) {
+    S = (k + R - 1) / R;  // no dead chunks
+    const long long e_fl = ((long long)(R + 1) * G + 3) / 4 * 4;
+    bool ok = false;
+    // wide groups need ~150 VGPRs: three waves per SIMD, i.e. three 256-thread blocks per CU but only
+    // one 512-thread block
+    const int cand[2] = {nt_env ? nt_env : ((R >= 512 && G < 8) ? 512 : 256), 256};
+    for (int ci = 0; ci < 2 && !ok; ++ci) {
+      NT = cand[ci];
+      const long long red_fl = (long long)(NT / 64) * G * r->D;
+      st_off = e_fl > red_fl ? e_fl : red_fl;
+      big = st_off + (S > 1 ? 3LL * S * G + 2LL * G : 0);
+      ok = (big <= big_cap);
+    }
+    if (ok) break;
+    if (R == 1) return TOVA_ENOSUP;
+    R -= (R >= 8) ? R / 8 : 1;  // smaller chunks until the chunk fits
+  }
+  r->S = S; r->R = R; r->NT = NT; r->st_off = (int)st_off;
+  r->kp = (int)round_up((size_t)k + 1, 64);
   r->lds = (int)((kSmallFloats + big) * 4);
   r->grid = (r->pairs + 7) / 8 * 8 * S;
+  // A chunk looks this many more times (about a microsecond apart) for its siblings' statistics
+  // before it leaves its score rows to the pair's finisher.  Only worth it when all workgroups of
+  // the grid are resident at once, which ~3 blocks per CU on 256 CUs allow.
+  r->spin_limit = (r->grid <= 768) ? 24 : 0;
+  if (const char* e = std::getenv("TOVA_SPIN_LIMIT")) {  // tuning aid / test hook
+    int v = std::atoi(e);
+    if (v >= 0 && v <= 4096) r->spin_limit = v;
+  }
+  r->force_slow = 0;
+  if (const char* e = std::getenv("TOVA_FORCE_SLOW_MERGE")) r->force_slow = (std::atoi(e) != 0);  // test hook
 
   // ---- caller-owned buffers ----
   const size_t kv_one = (size_t)r->pairs * k * r->D * r->esize;
@@ -101,6 +127,8 @@ int resolve(const tova_config_t* c, Resolved* r) {
   size_t off = 0;
   r->cnt_pair_off = off; off += round_up((size_t)r->pairs * 4, kAlign);
   r->cnt_unit_off = off; off += round_up((size_t)r->units * 4, kAlign);
+  r->cnt_pub_off = off; off += round_up((size_t)r->pairs * 4, kAlign);
+  r->slow_off = off; off += round_up((size_t)r->pairs * S * 4, kAlign);
   r->cnt_bytes = off;
   r->sg_off = off; off += round_up((size_t)r->pairs * r->kp * 4, kAlign);
   r->escr_off = r->stats_off = r->accp_off = off;
@@ -215,6 +243,9 @@ int tova_decode_steps(tova_cache_t* c, int32_t n_steps, const void* q, const voi
   p.slot_token = reinterpret_cast<int32_t*>(c->state + r.slot_off);
   p.cnt_pair = reinterpret_cast<int32_t*>(c->scratch + r.cnt_pair_off);
   p.cnt_unit = reinterpret_cast<int32_t*>(c->scratch + r.cnt_unit_off);
+  p.cnt_pub = reinterpret_cast<int32_t*>(c->scratch + r.cnt_pub_off);
+  p.slow_flag = reinterpret_cast<int32_t*>(c->scratch + r.slow_off);
+  p.st_off = r.st_off; p.spin_limit = r.spin_limit; p.force_slow = r.force_slow;
   p.sg = reinterpret_cast<float*>(c->scratch + r.sg_off);
   p.escr = reinterpret_cast<float*>(c->scratch + r.escr_off);
   p.stats = reinterpret_cast<float*>(c->scratch + r.stats_off);

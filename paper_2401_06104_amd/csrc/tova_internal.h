@@ -27,6 +27,11 @@ struct StepParams {
   float* accp;         // [pairs][S][G][d]   chunk-local PV partials  (S > 1 only)
   int32_t* cnt_pair;   // [pairs] arrival counters, zero between launches
   int32_t* cnt_unit;   // [units]
+  int32_t* cnt_pub;    // [pairs] chunks that have published their softmax statistics (S > 1 only)
+  int32_t* slow_flag;  // [pairs][S] chunk left its exp values in escr for the finisher (S > 1 only)
+  int32_t st_off;      // float offset, inside the big LDS area, of the chunk-statistics area (S > 1)
+  int32_t spin_limit;  // how often a chunk re-reads the published count before giving up (S > 1)
+  int32_t force_slow;  // test hook: no chunk finishes its own scores
   int32_t pairs;       // units * H_kv
   int32_t H, H_kv, k;
   int32_t n;           // rows cached before this step, min(t, k)

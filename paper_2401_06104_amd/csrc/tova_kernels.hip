@@ -206,28 +206,81 @@ __device__ __forceinline__ void st_agent(float* p, float v) {
 __device__ __forceinline__ float ld_agent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void st_agent_i(int32_t* p, int32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int32_t ld_agent_i(const int32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ float2 ld_agent2(const float* p) {  // p is 8-byte aligned
   unsigned long long r = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_AGENT);
   return make_float2(__uint_as_float((uint32_t)r), __uint_as_float((uint32_t)(r >> 32)));
 }
 
-// Elects the last of `expected` arrivals on `counter`.  All threads of the block call it
-// after writing their results with st_agent; it returns true in every thread of exactly one
-// block, which may then read what the others wrote with ld_agent.  The finisher resets the
-// counter for the next step.  Nobody waits for anybody: every block leaves at once.
-__device__ __forceinline__ bool last_arrival(int32_t* counter, int expected, int* flag_lds, int tid) {
+// Arrival on a counter.  All threads of the block call it after writing their results with
+// st_agent; it adds `add` to the counter once the block's stores have completed and returns the
+// counter's previous value to every thread.  The caller decides from that value whether it is
+// the last one, in which case it may read what the others wrote (ld_agent) and must reset the
+// counter (reset_counter) for the next step.  Nobody waits for anybody.
+__device__ __forceinline__ int arrive(int32_t* counter, int add, int* flag_lds, int tid) {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // keep the stores above this point
   __builtin_amdgcn_s_waitcnt(0);                          // ... and wait until they have completed
   __syncthreads();
-  if (tid == 0) {
-    int prev = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    int last = (prev == expected - 1);
-    if (last) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    *flag_lds = last;
-  }
+  if (tid == 0)
+    flag_lds[1] = __hip_atomic_fetch_add(counter, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
-  return *flag_lds != 0;
+  return flag_lds[1];
+}
+__device__ __forceinline__ void reset_counter(int32_t* counter, int tid) {
+  if (tid == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Unit finisher: per-thread argmin over the head-summed scores of the k+1 candidates.
+// sgu[h * kp + j] is KV head h's partial for candidate j.  A thread owns candidate pairs
+// (2m, 2m+1), m = tid + i * nt, sums the H_kv partials in head order and keeps the lowest
+// (ascending j, strict <, so the lowest index wins ties).  The loads bypass the caches, so
+// JB * HB of them are issued before the first is used.
+template <int JB, int HB>
+__device__ __forceinline__ void scan_scores(const float* sgu, int H_kv, int kp, int k, int tid, int nt,
+                                            float& best, int& bj) {
+  const int npair2 = (k + 2) / 2;  // candidate pairs covering 0..k
+  for (int m0 = tid; m0 < npair2; m0 += nt * JB) {
+    float s0[JB], s1[JB];
+#pragma unroll
+    for (int b = 0; b < JB; ++b) s0[b] = s1[b] = 0.f;
+    for (int h0 = 0; h0 < H_kv; h0 += HB) {
+      float2 raw[JB][HB];
+#pragma unroll
+      for (int b = 0; b < JB; ++b) {
+        const int mm = m0 + b * nt;
+#pragma unroll
+        for (int u = 0; u < HB; ++u) {
+          raw[b][u] = make_float2(0.f, 0.f);
+          if (mm < npair2 && h0 + u < H_kv) raw[b][u] = ld_agent2(sgu + (size_t)(h0 + u) * kp + 2 * mm);
+        }
+      }
+#pragma unroll
+      for (int b = 0; b < JB; ++b)
+#pragma unroll
+        for (int u = 0; u < HB; ++u) {
+          s0[b] += raw[b][u].x;
+          s1[b] += raw[b][u].y;
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < JB; ++b) {
+      const int j0 = 2 * (m0 + b * nt);
+      if (j0 <= k && s0[b] < best) {
+        best = s0[b];
+        bj = j0;
+      }
+      if (j0 + 1 <= k && s1[b] < best) {
+        best = s1[b];
+        bj = j0 + 1;
+      }
+    }
+  }
 }
 
 // ------------------------------------------------------------------ kernel
@@ -237,26 +290,27 @@ __device__ __forceinline__ bool last_arrival(int32_t* counter, int expected, int
 //    rows while the cross-lane sum per (row, head) needs only log2(LK) DPP steps;
 //  * PV pass: one chunk per lane (LV = CH lanes per row), no cross-lane work in
 //    the loop, G * VEC accumulators per lane.
-template <typename T, int D>
+template <typename T, int D, int G>
 struct Geo {
   static constexpr int VEC = Elem<T>::VEC;
   static constexpr int CH = D / VEC;
   static constexpr int CK = (CH >= 8) ? 2 : 1;
   static constexpr int LK = CH / CK;
   static constexpr int RK = 64 / LK;  // rows per wave pass, logit pass
-  static constexpr int UK = 2;        // passes per register buffer (two buffers in flight)
+  static constexpr int UK = (G >= 8) ? 1 : 2;  // passes per register buffer (two buffers in flight);
+                                               // fewer for wide groups, whose q fragments fill the registers
   static constexpr int LV = CH;
   static constexpr int RV = 64 / LV;  // rows per wave pass, PV pass
-  static constexpr int UV = 4;
+  static constexpr int UV = (G >= 8) ? 2 : 4;
   static_assert(D % VEC == 0 && CH <= 64 && (CH & (CH - 1)) == 0, "row geometry");
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
 
 template <typename T, int D, int G>
-__global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
+__global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const StepParams p) {
   using E = Elem<T>;
-  using Ge = Geo<T, D>;
+  using Ge = Geo<T, D, G>;
   constexpr int VEC = Ge::VEC, CK = Ge::CK, LK = Ge::LK, RK = Ge::RK, UK = Ge::UK;
   constexpr int LV = Ge::LV, RV = Ge::RV, UV = Ge::UV;
 
@@ -418,9 +472,23 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
   // ... and the barrier inside this one completes e_lds for the PV pass.
   block_reduce<G, false>(Z, small + kMaxWaves * G, lane, wave, nw);
 
-  // Score contributions leave LDS now (each thread re-reads only what it wrote itself).
-  if (full) {
-    if (S == 1) {
+  // Score contributions leave LDS before the PV pass (each thread re-reads only exp values it
+  // wrote itself, so no barrier is needed in front).
+  //  * one chunk per KV head: Z is final.
+  //  * several chunks: the chunk publishes its (max, sum) and looks, a bounded number of times,
+  //    whether its siblings have published theirs.  They run on neighbouring CUs at the same
+  //    time, so normally they have: the chunk then rescales its exp values to final
+  //    probabilities itself.  If not (a sibling was scheduled much later) it leaves the exp
+  //    values in scratch for the pair's finisher.  No wave ever waits without bound.
+  const int nact = c_new + 1;         // chunks of this pair that run this step
+  float* sl = big + p.st_off;         // [nact][G][2]  all chunks' (max, sum)
+  float* wl = sl + 2 * nact * G;      // [nact][G]     2^(m_c - m_g)   (pair finisher)
+  float* zl = wl + nact * G;          // [G]           global sum      (pair finisher)
+  const float* stp = p.stats + (size_t)pair * S * G * 2;
+  bool have_stats = false;            // sl holds the final statistics of every chunk
+  int slow = 0;                       // this chunk's score rows are left to the pair finisher
+  if (S == 1) {
+    if (full) {
       float rz[G];
 #pragma unroll
       for (int g = 0; g < G; ++g) rz[g] = 1.0f / Z[g];
@@ -431,11 +499,64 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
         for (int g = 0; g < G; ++g) a = fmaf(e_lds[i * G + g], rz[g], a);
         st_agent(sg + i, a);
       }
-    } else {
-      float* es = p.escr + ((size_t)pair * p.kp + r0) * G;
-      for (int i = tid; i < nloc; i += nt) {
+    }
+  } else {
+    if (wave == 0) {  // wave-uniform: the stores and the counter update are this wave's alone
+      if (lane < G) {
+        float mg = m[0], zg = Z[0];
 #pragma unroll
-        for (int g = 0; g < G; ++g) st_agent(es + i * G + g, e_lds[i * G + g]);
+        for (int g = 1; g < G; ++g) {
+          mg = (lane == g) ? m[g] : mg;
+          zg = (lane == g) ? Z[g] : zg;
+        }
+        float* st = p.stats + (((size_t)pair * S + chunk) * G + lane) * 2;
+        st_agent(st, mg);
+        st_agent(st + 1, zg);
+      }
+      if (full) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);
+        if (lane == 0) {
+          int seen = __hip_atomic_fetch_add(p.cnt_pub + pair, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+          for (int it = 0; it < p.spin_limit && seen != nact; ++it) {  // bounded: then the slow route
+            __builtin_amdgcn_s_sleep(16);
+            seen = ld_agent_i(p.cnt_pub + pair);
+          }
+          flag_lds[0] = (seen == nact && !p.force_slow) ? 1 : 0;
+        }
+      }
+    }
+    if (full) {
+      __syncthreads();
+      have_stats = (flag_lds[0] != 0);
+      if (have_stats) {
+        for (int x = tid; x < nact * G * 2; x += nt) sl[x] = ld_agent(stp + x);
+        __syncthreads();
+        float f[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float mg = -INFINITY;
+          for (int c = 0; c < nact; ++c) mg = fmaxf(mg, sl[(c * G + g) * 2]);
+          float zg = 0.f;
+          for (int c = 0; c < nact; ++c)
+            zg += sl[(c * G + g) * 2 + 1] * __builtin_amdgcn_exp2f(sl[(c * G + g) * 2] - mg);
+          f[g] = __builtin_amdgcn_exp2f(m[g] - mg) / zg;
+        }
+        float* sg = p.sg + (size_t)pair * p.kp + r0;
+        for (int i = tid; i < nloc; i += nt) {
+          float a = 0.f;
+#pragma unroll
+          for (int g = 0; g < G; ++g) a = fmaf(e_lds[i * G + g], f[g], a);
+          st_agent(sg + i, a);
+        }
+      } else {
+        slow = 1;
+        float* es = p.escr + ((size_t)pair * p.kp + r0) * G;
+        for (int i = tid; i < nloc; i += nt) {
+#pragma unroll
+          for (int g = 0; g < G; ++g) st_agent(es + i * G + g, e_lds[i * G + g]);
+        }
+        if (tid == 0) st_agent_i(p.slow_flag + (size_t)pair * S + chunk, 1);
       }
     }
   }
@@ -487,7 +608,7 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
     for (int v = 0; v < VEC; ++v) {
       acc[g][v] = column_sum<LV>(acc[g][v]);
     }
-  __syncthreads();  // everyone is done reading e_lds; reuse the area
+  __syncthreads();  // everyone is done reading e_lds; the reduction area reuses it
   float* red = big;  // [nw][G*D]
   if (rv == 0) {
 #pragma unroll
@@ -498,6 +619,10 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
   __syncthreads();
 
   T* outb = reinterpret_cast<T*>(p.out) + ((size_t)unit * p.H + (size_t)kvh * G) * D;
+  constexpr int ROW16 = D * (int)sizeof(T) / 16;  // 16-byte pieces per row
+  bool pair_last = true;  // this block completes its (unit, KV head)
+  int unit_add = 1;       // what it contributes to the unit's arrival count (S > 1: per chunk)
+
   if (S == 1) {
     for (int x = tid; x < G * D; x += nt) {
       float a = red[x];
@@ -509,183 +634,193 @@ __global__ __launch_bounds__(512) void tova_step_kernel(const StepParams p) {
       E::store(outb + x, a / zg);
     }
   } else {
+    // ---------------- phase 4a: several chunks per (unit, KV head) ----------------
     float* ap = p.accp + ((size_t)pair * S + chunk) * (G * D);
     for (int x = tid; x < G * D; x += nt) {
       float a = red[x];
       for (int w = 1; w < nw; ++w) a += red[w * G * D + x];
       st_agent(ap + x, a);
     }
-    if (tid < G) {
-      float mg = m[0], zg = Z[0];
-#pragma unroll
-      for (int g = 1; g < G; ++g) {
-        mg = (tid == g) ? m[g] : mg;
-        zg = (tid == g) ? Z[g] : zg;
-      }
-      float* st = p.stats + (((size_t)pair * S + chunk) * G + tid) * 2;
-      st_agent(st, mg);
-      st_agent(st + 1, zg);
-    }
-  }
-
-  // ---------------- phase 4a: merge the chunks of this (unit, KV head) ----------------
-  if (S > 1) {
-    const int nact = c_new + 1;  // chunks that ran this step
+    int n_slow = slow;
     if (nact > 1) {
-      if (!last_arrival(p.cnt_pair + pair, nact, flag_lds, tid)) return;
+      // arrivals in the low half of the counter, chunks that need the finisher's help in the high half
+      const int prev = arrive(p.cnt_pair + pair, 1 + (slow << 16), flag_lds, tid);
+      pair_last = ((prev & 0xffff) == nact - 1);
+      n_slow += prev >> 16;
     } else {
       __syncthreads();
     }
-    // global normalisers (log2 domain): m_g = max_c m_c, Z_g = sum_c Z_c 2^(m_c - m_g)
-    float* wl = big;                  // [nact][G]  2^(m_c - m_g)
-    float* zl = big + nact * G;       // [G]
-    __syncthreads();
-    if (tid < G) {
-      const float* st = p.stats + ((size_t)pair * S * G + tid) * 2;
-      float mg = -INFINITY;
-      for (int c = 0; c < nact; ++c) mg = fmaxf(mg, ld_agent(st + (size_t)c * G * 2));
-      float zg = 0.f;
-      for (int c = 0; c < nact; ++c) {
-        float w = __builtin_amdgcn_exp2f(ld_agent(st + (size_t)c * G * 2) - mg);
-        wl[c * G + tid] = w;
-        zg += ld_agent(st + (size_t)c * G * 2 + 1) * w;
+    unit_add = slow ? 0 : 1;
+    if (pair_last) {
+      // ---- pair finisher: global normalisers (log2 domain) m_g = max_c m_c, Z_g = sum_c Z_c 2^(m_c - m_g)
+      reset_counter(p.cnt_pair + pair, tid);
+      reset_counter(p.cnt_pub + pair, tid);
+      if (!have_stats) {  // (below capacity, or a sibling had not published when this chunk looked)
+        for (int x = tid; x < nact * G * 2; x += nt) sl[x] = ld_agent(stp + x);  // all in flight at once
+        __syncthreads();
       }
-      zl[tid] = zg;
-    }
-    __syncthreads();
-    const float* ap = p.accp + (size_t)pair * S * (G * D);
-    for (int x = tid; x < G * D; x += nt) {
-      const int g = x / D;
-      float a = 0.f;
-      for (int c = 0; c < nact; ++c) a = fmaf(ld_agent(ap + (size_t)c * G * D + x), wl[c * G + g], a);
-      E::store(outb + x, a / zl[g]);
-    }
-    if (full) {
-      const float* es = p.escr + (size_t)pair * p.kp * G;
-      float* sg = p.sg + (size_t)pair * p.kp;
-      for (int j = tid; j <= n; j += nt) {
-        const int c = min(j / R, c_new);
-        float a = 0.f;
+      if (tid < G) {
+        float mg = -INFINITY;
+        for (int c = 0; c < nact; ++c) mg = fmaxf(mg, sl[(c * G + tid) * 2]);
+        float zg = 0.f;
+        for (int c = 0; c < nact; ++c) {
+          float w = __builtin_amdgcn_exp2f(sl[(c * G + tid) * 2] - mg);
+          wl[c * G + tid] = w;
+          zg += sl[(c * G + tid) * 2 + 1] * w;
+        }
+        zl[tid] = zg;
+      }
+      __syncthreads();
+      if (full && n_slow > 0) {
+        // score rows of chunks that could not finish their own (rare: flags are read one by one)
+        const float* es = p.escr + (size_t)pair * p.kp * G;
+        float* sg = p.sg + (size_t)pair * p.kp;
+        for (int c = 0; c < nact; ++c) {
+          if (ld_agent_i(p.slow_flag + (size_t)pair * S + c) == 0) continue;  // block-uniform
+          const int j0 = c * R;
+          const int j1 = (c == c_new) ? n + 1 : min(j0 + R, n);
+          constexpr int JB = 4;  // rows per thread whose loads are issued together
+          for (int jb = j0 + tid; jb < j1; jb += nt * JB) {
+            float ev[JB][G];
 #pragma unroll
-        for (int g = 0; g < G; ++g) a += ld_agent(es + (size_t)j * G + g) * wl[c * G + g] / zl[g];
-        st_agent(sg + j, a);
+            for (int b = 0; b < JB; ++b) {
+              const int j = jb + b * nt;
+#pragma unroll
+              for (int g = 0; g < G; ++g) ev[b][g] = (j < j1) ? ld_agent(es + (size_t)j * G + g) : 0.f;
+            }
+#pragma unroll
+            for (int b = 0; b < JB; ++b) {
+              const int j = jb + b * nt;
+              float a = 0.f;
+#pragma unroll
+              for (int g = 0; g < G; ++g) a = fmaf(ev[b][g], wl[c * G + g] / zl[g], a);
+              if (j < j1) st_agent(sg + j, a);
+            }
+          }
+          if (tid == 0) st_agent_i(p.slow_flag + (size_t)pair * S + c, 0);
+        }
+        unit_add += n_slow;  // ... on whose behalf this block now arrives at the unit's counter
       }
     }
   }
 
   // ---------------- phase 4b: state update ----------------
-  constexpr int ROW16 = D * (int)sizeof(T) / 16;  // 16-byte pieces per row
   if (!full) {
     // below capacity (App. B: num_kv <= cache_max_size): the new row takes slot n
-    if (tid < ROW16) {
-      reinterpret_cast<V16*>(const_cast<T*>(Kb) - (size_t)r0 * D + (size_t)n * D)[tid] =
-          reinterpret_cast<const V16*>(knew)[tid];
-      reinterpret_cast<V16*>(const_cast<T*>(Vb) - (size_t)r0 * D + (size_t)n * D)[tid] =
-          reinterpret_cast<const V16*>(vnew)[tid];
+    if (pair_last) {
+      if (tid < ROW16) {
+        reinterpret_cast<V16*>(const_cast<T*>(Kb) - (size_t)r0 * D + (size_t)n * D)[tid] =
+            reinterpret_cast<const V16*>(knew)[tid];
+        reinterpret_cast<V16*>(const_cast<T*>(Vb) - (size_t)r0 * D + (size_t)n * D)[tid] =
+            reinterpret_cast<const V16*>(vnew)[tid];
+      }
+      if (kvh == 0 && tid == 0) {
+        if (p.evicted) p.evicted[unit] = -1;
+        p.slot_token[(size_t)unit * k + n] = p.t;
+        p.occupancy[unit] = n + 1;
+      }
     }
-    if (kvh == 0 && tid == 0) {
-      if (p.evicted) p.evicted[unit] = -1;
-      p.slot_token[(size_t)unit * k + n] = p.t;
-      p.occupancy[unit] = n + 1;
+  } else {
+    // The unit's counter collects one arrival per (KV head, chunk); whoever completes the count
+    // knows that every score row is written and that nobody reads the unit's K/V any more.
+    const int expected = p.H_kv * nact;
+    bool unit_last = false;
+    if (expected == 1) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();
+      unit_last = true;
+    } else if (unit_add > 0) {
+      const int prev = arrive(p.cnt_unit + unit, unit_add, flag_lds, tid);
+      unit_last = (prev + unit_add == expected);
+      if (unit_last) reset_counter(p.cnt_unit + unit, tid);
     }
-    return;
+    if (unit_last) {
+      // Head-mean score over the k+1 candidates (as a sum: the factor 1/H does not move the
+      // argmin), KV-head partials added in head order; lowest index wins ties.
+      const float* sgu = p.sg + (size_t)unit * p.H_kv * p.kp;
+      // the incoming row will most likely be stored: fetch this thread's piece of it now, so that
+      // its latency overlaps the score loads
+      const T* kn = reinterpret_cast<const T*>(p.k_new) + (size_t)unit * p.H_kv * D;
+      const T* vn = reinterpret_cast<const T*>(p.v_new) + (size_t)unit * p.H_kv * D;
+      V16 pk = V16{{0u, 0u, 0u, 0u}}, pv = V16{{0u, 0u, 0u, 0u}};
+      if (tid < p.H_kv * ROW16) {
+        pk = reinterpret_cast<const V16*>(kn)[tid];  // rows of consecutive KV heads are contiguous
+        pv = reinterpret_cast<const V16*>(vn)[tid];
+      }
+      float best = INFINITY;
+      int bj = 0x7fffffff;
+      constexpr int JM = (G >= 8) ? 2 : 1;  // the wide-group kernel has registers to spare here
+      if (p.H_kv <= 2)
+        scan_scores<8 * JM, 2>(sgu, p.H_kv, p.kp, k, tid, nt, best, bj);
+      else if (p.H_kv <= 4)
+        scan_scores<4 * JM, 4>(sgu, p.H_kv, p.kp, k, tid, nt, best, bj);
+      else
+        scan_scores<2 * JM, 8>(sgu, p.H_kv, p.kp, k, tid, nt, best, bj);
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) {
+        float ob = __shfl_xor(best, o);
+        int oj = __shfl_xor(bj, o);
+        if (ob < best || (ob == best && oj < bj)) {
+          best = ob;
+          bj = oj;
+        }
+      }
+      float* bv = small + 256;
+      int* bi = reinterpret_cast<int*>(small + 256 + kMaxWaves);
+      if (lane == 0) {
+        bv[wave] = best;
+        bi[wave] = bj;
+      }
+      __syncthreads();
+      best = bv[0];
+      bj = bi[0];
+      for (int w = 1; w < nw; ++w) {
+        float ob = bv[w];
+        int oj = bi[w];
+        if (ob < best || (ob == best && oj < bj)) {
+          best = ob;
+          bj = oj;
+        }
+      }
+      if (bj > k) bj = k;  // only reachable with non-finite scores
+      if (bj < k) {
+        T* Ku = reinterpret_cast<T*>(p.K) + ((size_t)unit * p.H_kv * k + bj) * D;
+        T* Vu = reinterpret_cast<T*>(p.V) + ((size_t)unit * p.H_kv * k + bj) * D;
+        for (int x = tid; x < p.H_kv * ROW16; x += nt) {
+          const int h = x / ROW16, c = x - h * ROW16;
+          if (x >= nt) {  // (only when a unit's new rows have more 16-byte pieces than the block has threads)
+            pk = reinterpret_cast<const V16*>(kn)[x];
+            pv = reinterpret_cast<const V16*>(vn)[x];
+          }
+          reinterpret_cast<V16*>(Ku + (size_t)h * k * D)[c] = pk;
+          reinterpret_cast<V16*>(Vu + (size_t)h * k * D)[c] = pv;
+        }
+      }
+      if (tid == 0) {
+        if (p.evicted) p.evicted[unit] = bj;
+        if (bj < k) p.slot_token[(size_t)unit * k + bj] = p.t;
+        p.occupancy[unit] = k;
+      }
+    }
   }
 
-  if (p.H_kv > 1) {
-    if (!last_arrival(p.cnt_unit + unit, p.H_kv, flag_lds, tid)) return;
-  } else {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-  }
-  // Head-mean score over the k+1 candidates (as a sum: the factor 1/H does not move the
-  // argmin), KV-head partials added in head order; lowest index wins ties.  Candidates are
-  // read two at a time and all of a thread's loads are issued before the first is used: the
-  // loads bypass the caches, so their latency must be overlapped, not serialised.
-  const float* sgu = p.sg + (size_t)unit * p.H_kv * p.kp;
-  const int npair2 = (k + 2) / 2;  // candidate pairs (2m, 2m+1) covering 0..k
-  float best = INFINITY;
-  int bj = 0x7fffffff;
-  constexpr int JB = 2, HB = 8;
-  for (int m0 = tid; m0 < npair2; m0 += nt * JB) {
-    float s0[JB], s1[JB];
+  // ---------------- the pair finisher merges the chunks' PV partials (off the critical path) ----------------
+  if (S > 1 && pair_last) {
+    const float* apf = p.accp + (size_t)pair * S * (G * D);
+    for (int x = tid; x < G * D; x += nt) {
+      const int g = x / D;
+      float a = 0.f;
+      constexpr int CB = 8;  // partials whose loads are issued together
+      for (int c0 = 0; c0 < nact; c0 += CB) {
+        float pv[CB];
 #pragma unroll
-    for (int b = 0; b < JB; ++b) s0[b] = s1[b] = 0.f;
-    for (int h0 = 0; h0 < p.H_kv; h0 += HB) {
-      float2 raw[JB][HB];
+        for (int u = 0; u < CB; ++u) pv[u] = (c0 + u < nact) ? ld_agent(apf + (size_t)(c0 + u) * G * D + x) : 0.f;
 #pragma unroll
-      for (int b = 0; b < JB; ++b) {
-        const int mm = m0 + b * nt;
-#pragma unroll
-        for (int u = 0; u < HB; ++u) {
-          raw[b][u] = make_float2(0.f, 0.f);
-          if (mm < npair2 && h0 + u < p.H_kv) raw[b][u] = ld_agent2(sgu + (size_t)(h0 + u) * p.kp + 2 * mm);
-        }
+        for (int u = 0; u < CB; ++u) a = (c0 + u < nact) ? fmaf(pv[u], wl[(c0 + u) * G + g], a) : a;
       }
-#pragma unroll
-      for (int b = 0; b < JB; ++b)
-#pragma unroll
-        for (int u = 0; u < HB; ++u) {
-          s0[b] += raw[b][u].x;
-          s1[b] += raw[b][u].y;
-        }
+      E::store(outb + x, a / zl[g]);
     }
-#pragma unroll
-    for (int b = 0; b < JB; ++b) {
-      const int j0 = 2 * (m0 + b * nt);
-      if (j0 <= k && s0[b] < best) {
-        best = s0[b];
-        bj = j0;
-      }
-      if (j0 + 1 <= k && s1[b] < best) {
-        best = s1[b];
-        bj = j0 + 1;
-      }
-    }
-  }
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) {
-    float ob = __shfl_xor(best, o);
-    int oj = __shfl_xor(bj, o);
-    if (ob < best || (ob == best && oj < bj)) {
-      best = ob;
-      bj = oj;
-    }
-  }
-  float* bv = small + 256;
-  int* bi = reinterpret_cast<int*>(small + 256 + kMaxWaves);
-  __syncthreads();
-  if (lane == 0) {
-    bv[wave] = best;
-    bi[wave] = bj;
-  }
-  __syncthreads();
-  best = bv[0];
-  bj = bi[0];
-  for (int w = 1; w < nw; ++w) {
-    float ob = bv[w];
-    int oj = bi[w];
-    if (ob < best || (ob == best && oj < bj)) {
-      best = ob;
-      bj = oj;
-    }
-  }
-  if (bj > k) bj = k;  // only reachable with non-finite scores
-  if (bj < k) {
-    T* Ku = reinterpret_cast<T*>(p.K) + ((size_t)unit * p.H_kv * k + bj) * D;
-    T* Vu = reinterpret_cast<T*>(p.V) + ((size_t)unit * p.H_kv * k + bj) * D;
-    const T* kn = reinterpret_cast<const T*>(p.k_new) + (size_t)unit * p.H_kv * D;
-    const T* vn = reinterpret_cast<const T*>(p.v_new) + (size_t)unit * p.H_kv * D;
-    for (int x = tid; x < p.H_kv * ROW16; x += nt) {
-      const int h = x / ROW16, c = x - h * ROW16;
-      reinterpret_cast<V16*>(Ku + (size_t)h * k * D)[c] = reinterpret_cast<const V16*>(kn + (size_t)h * D)[c];
-      reinterpret_cast<V16*>(Vu + (size_t)h * k * D)[c] = reinterpret_cast<const V16*>(vn + (size_t)h * D)[c];
-    }
-  }
-  if (tid == 0) {
-    if (p.evicted) p.evicted[unit] = bj;
-    if (bj < k) p.slot_token[(size_t)unit * k + bj] = p.t;
-    p.occupancy[unit] = k;
   }
 }
 

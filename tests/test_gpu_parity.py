@@ -184,3 +184,23 @@ def test_c5_yi_long_full_stream():
                                                    ev[:, 30, 0]))
         print(f"[parity]   from start: {a.get()}", flush=True)
         print(f"[parity]   window    : {b.get()}", flush=True)
+
+
+# ---- split cache: the path where a chunk cannot finish its own scores -------------------------
+@pytest.mark.parametrize("dtype,d,H,H_kv,k,T,L,B,splits", [
+    ("f32", 64, 8, 4, 100, 260, 1, 2, 3),
+    ("bf16", 128, 32, 4, 513, 700, 2, 1, 5),
+    ("bf16", 128, 8, 8, 300, 500, 1, 2, 16),
+])
+def test_split_finisher_handles_every_chunk(dtype, d, H, H_kv, k, T, L, B, splits, monkeypatch):
+    """Normally a chunk rescales its own exp values once its siblings have published their
+    softmax statistics; when one has not, the pair's finisher does it from scratch memory.
+    TOVA_FORCE_SLOW_MERGE makes every chunk take that second route."""
+    monkeypatch.setenv("TOVA_FORCE_SLOW_MERGE", "1")
+    spec = StreamSpec(f"slow_{dtype}_d{d}_h{H}_{H_kv}_k{k}", L=L, B=B, H=H, H_kv=H_kv, d=d, dtype=dtype,
+                      k=k, T=T, sink="first", n_sinks=2)
+    units = [(l, b) for l in range(L) for b in range(B)][:2]
+    stats, res = _run(spec, seed=300 + k, units=units, n_splits=splits, workers=2)
+    assert res["layout"][0] == splits
+    if dtype == "f32":
+        assert all(s["mismatches"] == 0 for s in stats)
