@@ -72,6 +72,8 @@ typedef struct {
   size_t v_offset;          /* kv_mem:    V  [L][B][H_kv][k][d]                 */
   size_t occupancy_offset;  /* state_mem: int32 [L][B]    rows in use, min(t,k) */
   size_t slot_token_offset; /* state_mem: int32 [L][B][k] token index held by a slot, -1 = empty */
+  size_t error_flag_offset; /* state_mem: int32, 0 = fine; set by a multi-step launch that gave up
+                               waiting (see tova_decode_steps); the steps after that were not done */
   int32_t n_splits;         /* resolved split count S                            */
   int32_t rows_per_split;   /* slots per chunk                                   */
   int32_t block_threads;    /* workgroup size the step kernel is launched with   */
@@ -109,7 +111,15 @@ int tova_decode_step(tova_cache_t* cache, const void* q, const void* k_new, cons
 
 /* n_steps consecutive decode steps with inputs resident in device memory:
  * the arrays of tova_decode_step with a leading [n_steps] dimension
- * (evicted: [n_steps][L][B], may be NULL).  Equivalent to n_steps calls. */
+ * (evicted: [n_steps][L][B], may be NULL).  Same results as n_steps calls.
+ * Once the cache is full, and if every workgroup of a step fits on the device at the same time
+ * with one chunk per KV head, the remaining steps run in ONE launch: each workgroup stays with
+ * its (sequence, KV head) for all steps, so sequences advance independently of one another and
+ * the only wait in the kernel is a workgroup's wait for the victim of its own sequence's current
+ * step.  That wait is bounded; should it ever run out, the kernel sets the int32 at
+ * error_flag_offset of state_mem and stops early (check it after synchronising the stream when
+ * results matter; tova_cache_init clears it).  The environment variable TOVA_MULTI_STEP=0 keeps
+ * one launch per step. */
 int tova_decode_steps(tova_cache_t* cache, int32_t n_steps, const void* q, const void* k_new,
                       const void* v_new, void* out, int32_t* evicted, void* hip_stream);
 

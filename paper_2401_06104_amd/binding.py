@@ -33,7 +33,7 @@ class TovaConfig(ctypes.Structure):
 
 class TovaLayout(ctypes.Structure):
     _fields_ = [("k_offset", c_size_t), ("v_offset", c_size_t), ("occupancy_offset", c_size_t),
-                ("slot_token_offset", c_size_t), ("n_splits", c_int32), ("rows_per_split", c_int32),
+                ("slot_token_offset", c_size_t), ("error_flag_offset", c_size_t), ("n_splits", c_int32), ("rows_per_split", c_int32),
                 ("block_threads", c_int32), ("grid_blocks", c_int32), ("lds_bytes", c_int32)]
 
 
@@ -153,6 +153,11 @@ class TovaCache:
         o = self.layout.slot_token_offset
         n = c.n_layers * c.batch * c.capacity_k
         return self.state_mem[o:o + 4 * n].view(self._torch.int32).view(c.n_layers, c.batch, c.capacity_k)
+
+    @property
+    def error_flag(self):
+        o = self.layout.error_flag_offset
+        return self.state_mem[o:o + 4].view(self._torch.int32)
 
     @property
     def tokens_seen(self) -> int:

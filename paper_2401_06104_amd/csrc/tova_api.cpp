@@ -25,12 +25,12 @@ size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Resolved {
   int L, B, k, H, H_kv, G, D, esize, bf16;
-  int units, pairs, S, R, kp, NT, grid, lds, st_off, spin_limit, force_slow;
+  int units, pairs, S, R, kp, NT, grid, lds, st_off, spin_limit, force_slow, persist_spin, multi_step, multi_grid;
   float scale;
   size_t kv_bytes, state_bytes, scratch_bytes;
   size_t v_off;                                   // in kv_mem
-  size_t occ_off, slot_off;                       // in state_mem
-  size_t cnt_pair_off, cnt_unit_off, cnt_pub_off, slow_off, cnt_bytes;   // in scratch_mem
+  size_t occ_off, slot_off, err_off;              // in state_mem
+  size_t cnt_pair_off, cnt_unit_off, cnt_pub_off, slow_off, pstate_off, cnt_bytes;   // in scratch_mem
   size_t sg_off, escr_off, stats_off, accp_off;
 };
 
@@ -115,6 +115,14 @@ int resolve(const tova_config_t* c, Resolved* r) {
   }
   r->force_slow = 0;
   if (const char* e = std::getenv("TOVA_FORCE_SLOW_MERGE")) r->force_slow = (std::atoi(e) != 0);  // test hook
+  // multi-step launches (decided for good in tova_cache_init, which can ask the device)
+  r->multi_step = (S == 1);
+  if (const char* e = std::getenv("TOVA_MULTI_STEP")) r->multi_step = r->multi_step && (std::atoi(e) != 0);
+  r->persist_spin = 1 << 22;  // polls of ~0.2 us or more each: seconds, i.e. "something is broken"
+  if (const char* e = std::getenv("TOVA_MULTI_STEP_SPIN")) {  // test hook: make the wait run out
+    int v = std::atoi(e);
+    if (v >= 0) r->persist_spin = v;
+  }
 
   // ---- caller-owned buffers ----
   const size_t kv_one = (size_t)r->pairs * k * r->D * r->esize;
@@ -122,13 +130,15 @@ int resolve(const tova_config_t* c, Resolved* r) {
   r->kv_bytes = 2 * kv_one;
   r->occ_off = 0;
   r->slot_off = round_up((size_t)r->units * 4, kAlign);
-  r->state_bytes = r->slot_off + round_up((size_t)r->units * k * 4, kAlign);
+  r->err_off = r->slot_off + round_up((size_t)r->units * k * 4, kAlign);
+  r->state_bytes = r->err_off + kAlign;
 
   size_t off = 0;
   r->cnt_pair_off = off; off += round_up((size_t)r->pairs * 4, kAlign);
   r->cnt_unit_off = off; off += round_up((size_t)r->units * 4, kAlign);
   r->cnt_pub_off = off; off += round_up((size_t)r->pairs * 4, kAlign);
   r->slow_off = off; off += round_up((size_t)r->pairs * S * 4, kAlign);
+  r->pstate_off = off; off += round_up((size_t)r->units * 8, kAlign);
   r->cnt_bytes = off;
   r->sg_off = off; off += round_up((size_t)r->pairs * r->kp * 4, kAlign);
   r->escr_off = r->stats_off = r->accp_off = off;
@@ -180,6 +190,7 @@ int tova_cache_layout(const tova_config_t* cfg, tova_layout_t* layout) {
   layout->v_offset = r.v_off;
   layout->occupancy_offset = r.occ_off;
   layout->slot_token_offset = r.slot_off;
+  layout->error_flag_offset = r.err_off;
   layout->n_splits = r.S;
   layout->rows_per_split = r.R;
   layout->block_threads = r.NT;
@@ -214,6 +225,18 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
                               (size_t)r.units * r.k, s);
   if (e == hipSuccess)
     e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->scratch), 0, r.cnt_bytes / 4, s);
+  if (e == hipSuccess)
+    e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->state + r.err_off), 0, 1, s);
+  // A multi-step launch needs all its blocks resident at once (blocks of a unit wait for each
+  // other's results): its grid is capped at what the device can hold, and each block then walks
+  // several (unit, KV head) pairs per step.
+  c->r.multi_grid = 0;
+  if (c->r.multi_step) {
+    const int cap = tova::resident_blocks(r.bf16, r.D, r.G, r.NT, r.lds) / 8 * 8;
+    const int want = (r.pairs + 7) / 8 * 8;
+    c->r.multi_grid = want < cap ? want : cap;   // never more blocks than fit at once
+    if (c->r.multi_grid < 8) c->r.multi_step = 0;
+  }
   if (e != hipSuccess) {
     delete c;
     return hip_fail(e, "tova_cache_init");
@@ -254,7 +277,13 @@ int tova_decode_steps(tova_cache_t* c, int32_t n_steps, const void* q, const voi
   p.S = r.S; p.R = r.R; p.kp = r.kp; p.scale = r.scale;
   const tova::LaunchPlan lp{r.grid, r.NT, r.lds};
 
-  for (int32_t i = 0; i < n_steps; ++i) {
+  p.q_stride = (int64_t)(q_step / r.esize);
+  p.kv_stride = (int64_t)(kv_step / r.esize);
+  p.pstate = reinterpret_cast<unsigned long long*>(c->scratch + r.pstate_off);
+  p.error_flag = reinterpret_cast<int32_t*>(c->state + r.err_off);
+  p.persist_spin = r.persist_spin;
+
+  for (int32_t i = 0; i < n_steps;) {
     p.q = static_cast<const char*>(q) + (size_t)i * q_step;
     p.k_new = static_cast<const char*>(k_new) + (size_t)i * kv_step;
     p.v_new = static_cast<const char*>(v_new) + (size_t)i * kv_step;
@@ -262,9 +291,18 @@ int tova_decode_steps(tova_cache_t* c, int32_t n_steps, const void* q, const voi
     p.evicted = evicted ? evicted + (size_t)i * r.units : nullptr;
     p.n = (int32_t)(c->t < r.k ? c->t : r.k);
     p.t = (int32_t)c->t;
-    hipError_t e = tova::launch_step(r.bf16, r.D, r.G, p, lp, s);
+    // all remaining steps in one launch once the cache is full (see tova.h)
+    const int32_t m = (r.multi_step && c->t >= r.k && n_steps - i >= 2) ? n_steps - i : 1;
+    p.n_iter = m;
+    p.persistent = (m > 1);
+    hipError_t e = hipSuccess;
+    if (m > 1)  // the units' state words start from "no step finished"
+      e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(p.pstate), 0, (size_t)r.units * 2, s);
+    const tova::LaunchPlan lpm{r.multi_grid, r.NT, r.lds};
+    if (e == hipSuccess) e = tova::launch_step(r.bf16, r.D, r.G, p, m > 1 ? lpm : lp, s);
     if (e != hipSuccess) return hip_fail(e, "tova_decode_step launch");
-    c->t += 1;
+    c->t += m;
+    i += m;
   }
   return TOVA_OK;
 }

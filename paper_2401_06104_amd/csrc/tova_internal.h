@@ -32,6 +32,13 @@ struct StepParams {
   int32_t st_off;      // float offset, inside the big LDS area, of the chunk-statistics area (S > 1)
   int32_t spin_limit;  // how often a chunk re-reads the published count before giving up (S > 1)
   int32_t force_slow;  // test hook: no chunk finishes its own scores
+  // multi-step launch
+  int32_t n_iter;      // decode steps handled by this launch (1 for a per-step launch)
+  int32_t persistent;  // blocks keep their (unit, KV head) over n_iter steps and wait for victims
+  int32_t persist_spin;          // polls of the unit's state word before a block gives up
+  int64_t q_stride, kv_stride;   // elements between consecutive steps of q / out and of k_new / v_new
+  unsigned long long* pstate;    // [units] (victim << 32) | (token index + 1) of the unit's last finished step
+  int32_t* error_flag;           // set when a block gave up waiting
   int32_t pairs;       // units * H_kv
   int32_t H, H_kv, k;
   int32_t n;           // rows cached before this step, min(t, k)
@@ -48,6 +55,9 @@ struct LaunchPlan {
 hipError_t launch_step(int dtype_is_bf16, int D, int G, const StepParams& p, const LaunchPlan& lp,
                        hipStream_t stream);
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_t stream);
+// how many blocks of the step kernel (given instantiation, block size, dynamic LDS) fit on the
+// current device at once; 0 if the query fails
+int resident_blocks(int dtype_is_bf16, int D, int G, int block, int lds_bytes);
 
 }  // namespace tova
 #endif

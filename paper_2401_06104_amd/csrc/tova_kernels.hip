@@ -212,6 +212,12 @@ __device__ __forceinline__ void st_agent_i(int32_t* p, int32_t v) {
 __device__ __forceinline__ int32_t ld_agent_i(const int32_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void st_agent_u64(unsigned long long* p, unsigned long long v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long ld_agent_u64(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ float2 ld_agent2(const float* p) {  // p is 8-byte aligned
   unsigned long long r = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_AGENT);
@@ -307,7 +313,7 @@ struct Geo {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-template <typename T, int D, int G>
+template <typename T, int D, int G, bool MULTI>
 __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const StepParams p) {
   using E = Elem<T>;
   using Ge = Geo<T, D, G>;
@@ -319,22 +325,49 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
   float* big = small + kSmallFloats;
   int* flag_lds = reinterpret_cast<int*>(small + 480);
 
-  const int tid = threadIdx.x;
   const int nt = blockDim.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
   const int nw = nt >> 6;
 
-  // blockIdx -> (pair = (unit, KV head), chunk).  Consecutive block ids go to
-  // consecutive XCDs, so the S chunks of one pair are placed on the same XCD
-  // (their partial results then meet in one L2).
+  // Per-step launch (MULTI == false): blockIdx -> (pair = (unit, KV head), chunk); one pass.
+  // Consecutive block ids go to consecutive XCDs, so the S chunks of one pair are placed on the
+  // same XCD (their partial results then meet in one L2).
+  //
+  // Multi-step launch (MULTI == true; one chunk per KV head, cache full, every block of the grid
+  // resident): block b keeps the pairs b, b + gridDim, ... for all n_iter steps and walks them in
+  // (step, pair) order.  There is no grid-wide barrier between steps: units advance independently,
+  // and the only wait is a block's wait for the victim of a unit's previous step when it comes
+  // back to one of that unit's pairs (every wait is for work that is earlier in the common order,
+  // so some block can always make progress).  Each block stores the incoming row of its own pairs
+  // itself, so cached rows are only ever written and read by one and the same block.
   const int S = p.S, R = p.R, k = p.k, n = p.n;
-  const int xcd = blockIdx.x & 7;
-  const int wq = blockIdx.x >> 3;
-  const int pair = (wq / S) * 8 + xcd;
-  const int chunk = wq % S;
   const int c_new = min(n / R, S - 1);  // the chunk that also takes the incoming token
-  if (pair >= p.pairs || chunk > c_new) return;
+  const bool full = (n == k);
+  constexpr int ROW16 = D * (int)sizeof(T) / 16;  // 16-byte pieces per row
+  int pair0, chunk, pstride;
+  if (MULTI) {
+    pair0 = blockIdx.x;
+    chunk = 0;
+    pstride = gridDim.x;
+  } else {
+    const int xcd = blockIdx.x & 7;
+    const int wq = blockIdx.x >> 3;
+    pair0 = (wq / S) * 8 + xcd;
+    chunk = wq % S;
+    pstride = 0x40000000;  // one pair per block
+    if (pair0 >= p.pairs || chunk > c_new) return;
+  }
+  const int n_pass = MULTI ? p.n_iter + 1 : 1;  // (the extra pass only stores the last step's rows)
+
+  for (int it = 0; it < n_pass; ++it) {
+  // (a per-step launch makes exactly one trip through both loops, and the compiler can see that)
+  for (int pair = pair0, trip = 0; MULTI ? (pair < p.pairs) : (trip == 0); pair += pstride, ++trip) {
+  // In a multi-step launch the thread index is re-read through an opaque copy in every pass:
+  // otherwise the compiler hoists the lane-dependent address arithmetic of the whole body out of
+  // the loops and keeps it in registers across them (+40 VGPRs and spills).
+  int tid = threadIdx.x;
+  if (MULTI) asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
+  const int wave = MULTI ? __builtin_amdgcn_readfirstlane(tid >> 6) : (tid >> 6);
   const int unit = pair / p.H_kv;
   const int kvh = pair - unit * p.H_kv;
   const int r0 = chunk * R;
@@ -342,13 +375,51 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
   const int ncached = r1 - r0;                 // cached rows of this chunk
   const bool has_new = (chunk == c_new);       // local candidate `ncached` is the incoming token
   const int nloc = ncached + (has_new ? 1 : 0);  // local candidates, >= 1
-  const bool full = (n == k);
-
   const T* Kb = reinterpret_cast<const T*>(p.K) + ((size_t)pair * k + r0) * D;
   const T* Vb = reinterpret_cast<const T*>(p.V) + ((size_t)pair * k + r0) * D;
-  const T* knew = reinterpret_cast<const T*>(p.k_new) + (size_t)pair * D;
-  const T* vnew = reinterpret_cast<const T*>(p.v_new) + (size_t)pair * D;
-  const T* qb = reinterpret_cast<const T*>(p.q) + ((size_t)unit * p.H + (size_t)kvh * G) * D;
+  const int tok = p.t + it;  // index of the incoming token
+
+  if (MULTI && it > 0) {
+    // Wait (bounded) for the victim of this unit's previous step, then put that step's incoming
+    // row of this KV head into the freed slot.  If the wait runs out -- it cannot while all blocks
+    // are resident, which the host checks before choosing this launch mode -- the block raises the
+    // cache's error flag and leaves; every other block sees the flag in its own wait and leaves too.
+    if (tid == 0) {
+      unsigned long long w = 0;
+      int ok = 0;
+      for (int spin = 0;; ++spin) {
+        w = ld_agent_u64(p.pstate + unit);
+        if ((int)(uint32_t)w == tok) {
+          ok = 1;
+          break;
+        }
+        if (spin >= p.persist_spin || ld_agent_i(p.error_flag) != 0) break;
+        __builtin_amdgcn_s_sleep(4);
+      }
+      if (!ok) st_agent_i(p.error_flag, 1);
+      flag_lds[2] = ok;
+      flag_lds[3] = (int)(w >> 32);
+    }
+    __syncthreads();
+    if (flag_lds[2] == 0) return;  // block-uniform
+    const int vic = flag_lds[3];
+    if (vic < k && tid < ROW16) {
+      const T* kprev = reinterpret_cast<const T*>(p.k_new) + (size_t)(it - 1) * p.kv_stride + (size_t)pair * D;
+      const T* vprev = reinterpret_cast<const T*>(p.v_new) + (size_t)(it - 1) * p.kv_stride + (size_t)pair * D;
+      reinterpret_cast<V16*>(const_cast<T*>(Kb) + (size_t)vic * D)[tid] = reinterpret_cast<const V16*>(kprev)[tid];
+      reinterpret_cast<V16*>(const_cast<T*>(Vb) + (size_t)vic * D)[tid] = reinterpret_cast<const V16*>(vprev)[tid];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();  // the row is in place for this block's pass over the pair
+    if (it == p.n_iter) continue;
+  }
+
+  const T* knew = reinterpret_cast<const T*>(p.k_new) + (size_t)it * p.kv_stride + (size_t)pair * D;
+  const T* vnew = reinterpret_cast<const T*>(p.v_new) + (size_t)it * p.kv_stride + (size_t)pair * D;
+  const T* qb = reinterpret_cast<const T*>(p.q) + (size_t)it * p.q_stride +
+                ((size_t)unit * p.H + (size_t)kvh * G) * D;
+  int32_t* const evp = p.evicted ? p.evicted + (size_t)it * (p.pairs / p.H_kv) : nullptr;
 
   float* e_lds = big;  // [nloc][G]: logits (log2 domain), then exp values
   const float scale2 = p.scale * kLog2e;  // softmax is evaluated as 2^(l2 - max l2)
@@ -618,8 +689,7 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
   }
   __syncthreads();
 
-  T* outb = reinterpret_cast<T*>(p.out) + ((size_t)unit * p.H + (size_t)kvh * G) * D;
-  constexpr int ROW16 = D * (int)sizeof(T) / 16;  // 16-byte pieces per row
+  T* outb = reinterpret_cast<T*>(p.out) + (size_t)it * p.q_stride + ((size_t)unit * p.H + (size_t)kvh * G) * D;
   bool pair_last = true;  // this block completes its (unit, KV head)
   int unit_add = 1;       // what it contributes to the unit's arrival count (S > 1: per chunk)
 
@@ -715,8 +785,8 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
             reinterpret_cast<const V16*>(vnew)[tid];
       }
       if (kvh == 0 && tid == 0) {
-        if (p.evicted) p.evicted[unit] = -1;
-        p.slot_token[(size_t)unit * k + n] = p.t;
+        if (evp) evp[unit] = -1;
+        p.slot_token[(size_t)unit * k + n] = tok;
         p.occupancy[unit] = n + 1;
       }
     }
@@ -741,10 +811,10 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
       const float* sgu = p.sg + (size_t)unit * p.H_kv * p.kp;
       // the incoming row will most likely be stored: fetch this thread's piece of it now, so that
       // its latency overlaps the score loads
-      const T* kn = reinterpret_cast<const T*>(p.k_new) + (size_t)unit * p.H_kv * D;
-      const T* vn = reinterpret_cast<const T*>(p.v_new) + (size_t)unit * p.H_kv * D;
+      const T* kn = reinterpret_cast<const T*>(p.k_new) + (size_t)it * p.kv_stride + (size_t)unit * p.H_kv * D;
+      const T* vn = reinterpret_cast<const T*>(p.v_new) + (size_t)it * p.kv_stride + (size_t)unit * p.H_kv * D;
       V16 pk = V16{{0u, 0u, 0u, 0u}}, pv = V16{{0u, 0u, 0u, 0u}};
-      if (tid < p.H_kv * ROW16) {
+      if (!MULTI && tid < p.H_kv * ROW16) {
         pk = reinterpret_cast<const V16*>(kn)[tid];  // rows of consecutive KV heads are contiguous
         pv = reinterpret_cast<const V16*>(vn)[tid];
       }
@@ -784,7 +854,7 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
         }
       }
       if (bj > k) bj = k;  // only reachable with non-finite scores
-      if (bj < k) {
+      if (bj < k && !MULTI) {
         T* Ku = reinterpret_cast<T*>(p.K) + ((size_t)unit * p.H_kv * k + bj) * D;
         T* Vu = reinterpret_cast<T*>(p.V) + ((size_t)unit * p.H_kv * k + bj) * D;
         for (int x = tid; x < p.H_kv * ROW16; x += nt) {
@@ -798,9 +868,18 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
         }
       }
       if (tid == 0) {
-        if (p.evicted) p.evicted[unit] = bj;
-        if (bj < k) p.slot_token[(size_t)unit * k + bj] = p.t;
-        p.occupancy[unit] = k;
+        // (written through: in a multi-step launch the finishers of successive steps sit on
+        // different XCDs, and a slot's entry may be rewritten a few steps later)
+        if (evp) st_agent_i(evp + unit, bj);
+        if (bj < k) st_agent_i(p.slot_token + (size_t)unit * k + bj, tok);
+        st_agent_i(p.occupancy + unit, k);
+        if (MULTI) {
+          // Multi-step launch: publish the victim; every block stores the row of its own KV head
+          // when it comes back to the pair.  The arrival counter's reset must have landed before
+          // anyone can arrive again.
+          __builtin_amdgcn_s_waitcnt(0);
+          st_agent_u64(p.pstate + unit, ((unsigned long long)(uint32_t)bj << 32) | (uint32_t)(tok + 1));
+        }
       }
     }
   }
@@ -822,6 +901,40 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
       E::store(outb + x, a / zl[g]);
     }
   }
+
+  if (MULTI) __syncthreads();  // LDS is free for the block's next pair
+  }  // pairs of this block
+  }  // passes
+}
+
+// Blocks of the step kernel that can be resident on the device at once.
+template <typename T, int D, int G>
+int resident_blocks_one(int block, int lds) {
+  int per_cu = 0, dev = 0, cus = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tova_step_kernel<T, D, G, true>, block, (size_t)lds) != hipSuccess)
+    return 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  return per_cu * cus;
+}
+template <typename T, int D>
+int resident_blocks_g(int G, int block, int lds) {
+  switch (G) {
+    case 1: return resident_blocks_one<T, D, 1>(block, lds);
+    case 2: return resident_blocks_one<T, D, 2>(block, lds);
+    case 4: return resident_blocks_one<T, D, 4>(block, lds);
+    case 8: return resident_blocks_one<T, D, 8>(block, lds);
+    default: return 0;
+  }
+}
+template <typename T>
+int resident_blocks_d(int D, int G, int block, int lds) {
+  switch (D) {
+    case 32: return resident_blocks_g<T, 32>(G, block, lds);
+    case 64: return resident_blocks_g<T, 64>(G, block, lds);
+    case 128: return resident_blocks_g<T, 128>(G, block, lds);
+    default: return 0;
+  }
 }
 
 __global__ void tova_fill_i32_kernel(int32_t* dst, int32_t value, size_t count) {
@@ -832,8 +945,10 @@ __global__ void tova_fill_i32_kernel(int32_t* dst, int32_t value, size_t count) 
 
 template <typename T, int D, int G>
 hipError_t launch_one(const StepParams& p, const LaunchPlan& lp, hipStream_t stream) {
-  hipLaunchKernelGGL((tova_step_kernel<T, D, G>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes,
-                     stream, p);
+  if (p.persistent)
+    hipLaunchKernelGGL((tova_step_kernel<T, D, G, true>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes, stream, p);
+  else
+    hipLaunchKernelGGL((tova_step_kernel<T, D, G, false>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes, stream, p);
   return hipGetLastError();
 }
 
@@ -863,6 +978,11 @@ hipError_t launch_d(int D, int G, const StepParams& p, const LaunchPlan& lp, hip
 hipError_t launch_step(int dtype_is_bf16, int D, int G, const StepParams& p, const LaunchPlan& lp,
                        hipStream_t stream) {
   return dtype_is_bf16 ? launch_d<bf16_t>(D, G, p, lp, stream) : launch_d<float>(D, G, p, lp, stream);
+}
+
+int resident_blocks(int dtype_is_bf16, int D, int G, int block, int lds_bytes) {
+  return dtype_is_bf16 ? resident_blocks_d<bf16_t>(D, G, block, lds_bytes)
+                       : resident_blocks_d<float>(D, G, block, lds_bytes);
 }
 
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_t stream) {

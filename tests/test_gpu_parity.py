@@ -204,3 +204,45 @@ def test_split_finisher_handles_every_chunk(dtype, d, H, H_kv, k, T, L, B, split
     assert res["layout"][0] == splits
     if dtype == "f32":
         assert all(s["mismatches"] == 0 for s in stats)
+
+
+# ---- multi-step launches --------------------------------------------------------------------
+def test_multi_step_launch_matches_per_step_launches(monkeypatch):
+    """tova_decode_steps runs all full-occupancy steps of a call in one launch when it can; the
+    results must be bit-identical to one launch per step (TOVA_MULTI_STEP=0)."""
+    from paper_2401_06104_amd import TovaCache
+    from workloads import Stream
+    spec = spec_for("c3_mistral_gqa", B=16, k=256, T=256 + 300)
+    outs = []
+    for mode in ("1", "0"):
+        monkeypatch.setenv("TOVA_MULTI_STEP", mode)
+        cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype, n_splits=1)
+        assert cache.layout.n_splits == 1            # multi-step launches need one chunk per KV head
+        c = Stream(spec, 11, device="cuda:0").chunk(0, spec.T)
+        out = torch.empty_like(c["q"])
+        ev = torch.empty(spec.T, spec.L, spec.B, dtype=torch.int32, device="cuda:0")
+        cache.decode_steps(c["q"], c["k"], c["v"], out, ev)
+        torch.cuda.synchronize()
+        assert int(cache.error_flag.item()) == 0
+        outs.append((out.cpu(), ev.cpu(), cache.slot_token.cpu(), cache.K.cpu(), cache.V.cpu()))
+        cache.destroy()
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_multi_step_wait_runs_out_cleanly(monkeypatch):
+    """Failure handling, forced from the host: with a wait budget of zero polls the workgroups of
+    a multi-step launch cannot get their unit's victim; every one of them must then leave, the
+    kernel must end, and the cache's error flag must be set.  (Nothing hangs: the wait is bounded.)"""
+    from paper_2401_06104_amd import TovaCache
+    from workloads import Stream
+    monkeypatch.setenv("TOVA_MULTI_STEP", "1")
+    monkeypatch.setenv("TOVA_MULTI_STEP_SPIN", "0")
+    spec = spec_for("c3_mistral_gqa", B=16, k=128, T=128 + 40)
+    cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype, n_splits=1)
+    c = Stream(spec, 12, device="cuda:0").chunk(0, spec.T)
+    out = torch.empty_like(c["q"])
+    cache.decode_steps(c["q"], c["k"], c["v"], out, None)
+    torch.cuda.synchronize()
+    assert int(cache.error_flag.item()) == 1
+    cache.destroy()
