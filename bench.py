@@ -5,11 +5,13 @@ Workload (the configuration the headline metric is quoted on): Mistral-7B-shaped
 32 query heads / 8 KV heads, head_dim 128, bf16, batch 64, cache capacity k = 1024.  The cache
 is first filled through the same API (1024 untimed steps), then `--steps` decode steps at full
 occupancy are timed in one tova_decode_steps call with all inputs already resident in HBM.
-One "step" = one token for each of the 64 sequences = one launch of the fused kernel.
+One "step" = one token for each of the 64 sequences = one pass of the fused kernel over every
+(sequence, KV head); the timed call runs all its steps in ONE launch of that kernel when the
+device can hold all its workgroups at once (otherwise one launch per step).
 
 Prints ONE JSON line (see README / DESIGN for the fields).  `roofline` is the fused step
-kernel against the HBM roofline: algorithmic bytes per launch / average launch duration measured
-with HIP events on the launch stream over the timed region.  `cpu_baseline` is the fp64 oracle
+kernel against the HBM roofline: algorithmic bytes per launch (bytes per step x steps per launch)
+/ average launch duration measured with HIP events on the launch stream over the timed region.  `cpu_baseline` is the fp64 oracle
 timed on host cores on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -25,10 +27,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
-# Bytes that left L2 per launch of the step kernel on this workload, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this script, each scaled by what the same counter reads for a 1 GiB copy kernel
-# (summary: profiles/tova_step_kernel_c3_mistral_gqa.txt).  Not measured live.
-PROFILED_TRAFFIC_BYTES_PER_LAUNCH = 274.8e6
+# Bytes that left L2 per decode step of the step kernel on this workload, from rocprofv3 --pmc FETCH_SIZE
+# and WRITE_SIZE runs of this script (512 steps per launch), each scaled by what the same counter reads
+# for a 1 GiB copy kernel (summary: profiles/tova_step_kernel_c3_mistral_gqa.txt).  Not measured live.
+PROFILED_TRAFFIC_BYTES_PER_STEP = 274.4e6
 
 
 def algorithmic_bytes_per_step(spec) -> int:
@@ -104,7 +106,8 @@ def gpu_leg(spec, seed, steps, warmup, device, chunk=256, prefill=False):
     ev_host = evicted.cpu()
     ok = bool(((ev_host >= 0) & (ev_host <= spec.k)).all()) and cache.tokens_seen == need
     lay = cache.layout
-    plan = dict(n_splits=lay.n_splits, rows_per_split=lay.rows_per_split, block_threads=lay.block_threads,
+    multi = cache.multi_step_blocks
+    plan = dict(multi_step_blocks=multi, n_splits=lay.n_splits, rows_per_split=lay.rows_per_split, block_threads=lay.block_threads,
                 grid_blocks=lay.grid_blocks, lds_bytes=lay.lds_bytes)
     cache.destroy()
     return dict(wall_s=wall, event_ms=ev_ms, plan=plan, sane=ok,
@@ -185,6 +188,7 @@ def main():
     ms_per_step = g["event_ms"] / args.steps
     abytes = algorithmic_bytes_per_step(spec)
     achieved = abytes / (ms_per_step * 1e-3) / 1e9
+    steps_per_launch = args.steps if g["plan"]["multi_step_blocks"] else 1
     result = {
         "metric": "TOVA decode steps/sec and achieved HBM GB/s (% of peak), 1 MI355X",
         "value": 1e3 / ms_per_step,
@@ -199,9 +203,12 @@ def main():
                    "sequence_steps_per_s": 1e3 / ms_per_step * spec.L * spec.B},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": PROFILED_TRAFFIC_BYTES_PER_LAUNCH if spec.L == 1 else None,
-                     "kernel": "tova_step_kernel<bf16, d=128, G=4>", "algorithmic_bytes_per_launch": abytes,
-                     "avg_launch_us": ms_per_step * 1e3},
+                     "traffic": PROFILED_TRAFFIC_BYTES_PER_STEP * steps_per_launch if spec.L == 1 else None,
+                     "kernel": "tova_step_kernel<bf16, d=128, G=4, multi-step>" if steps_per_launch > 1
+                               else "tova_step_kernel<bf16, d=128, G=4, per-step>",
+                     "steps_per_launch": steps_per_launch, "algorithmic_bytes_per_step": abytes,
+                     "algorithmic_bytes_per_launch": abytes * steps_per_launch,
+                     "avg_launch_us": ms_per_step * 1e3 * steps_per_launch},
         "sane": g["sane"], "new_token_dropped_frac": g["new_token_dropped_frac"],
         "wall_s_timed_region": g["wall_s"],
     }

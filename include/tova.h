@@ -123,6 +123,11 @@ int tova_decode_step(tova_cache_t* cache, const void* q, const void* k_new, cons
 int tova_decode_steps(tova_cache_t* cache, int32_t n_steps, const void* q, const void* k_new,
                       const void* v_new, void* out, int32_t* evicted, void* hip_stream);
 
+/* How tova_decode_steps launches once the cache is full (decided in tova_cache_init, which asks
+ * the device how many workgroups fit): *blocks = 0 -> one launch per step; otherwise the number
+ * of workgroups of the single launch that runs all remaining steps of a call.  HOST out pointer. */
+int tova_cache_multi_step_blocks(const tova_cache_t* cache, int32_t* blocks);
+
 /* Number of tokens the cache has seen since tova_cache_init (HOST out pointer). */
 int tova_cache_tokens_seen(const tova_cache_t* cache, int64_t* t);
 

@@ -59,12 +59,14 @@ def load_library() -> ctypes.CDLL:
     lib.tova_decode_steps.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                       c_void_p, c_void_p]
     lib.tova_cache_tokens_seen.argtypes = [c_void_p, POINTER(c_int64)]
+    lib.tova_cache_multi_step_blocks.argtypes = [c_void_p, POINTER(c_int32)]
     lib.tova_cache_set_tokens_seen.argtypes = [c_void_p, c_int64]
     lib.tova_cache_destroy.argtypes = [c_void_p]
     lib.tova_strerror.argtypes = [c_int]
     lib.tova_strerror.restype = c_char_p
     for name in ("tova_cache_bytes", "tova_cache_layout", "tova_cache_init", "tova_decode_step",
                  "tova_decode_steps", "tova_cache_tokens_seen", "tova_cache_set_tokens_seen",
+                 "tova_cache_multi_step_blocks",
                  "tova_cache_destroy"):
         getattr(lib, name).restype = c_int
     _LIB = lib
@@ -158,6 +160,14 @@ class TovaCache:
     def error_flag(self):
         o = self.layout.error_flag_offset
         return self.state_mem[o:o + 4].view(self._torch.int32)
+
+    @property
+    def multi_step_blocks(self) -> int:
+        b = c_int32()
+        rc = self.lib.tova_cache_multi_step_blocks(self._h, byref(b))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_cache_multi_step_blocks")
+        return b.value
 
     @property
     def tokens_seen(self) -> int:

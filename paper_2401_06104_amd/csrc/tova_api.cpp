@@ -312,6 +312,12 @@ int tova_decode_step(tova_cache_t* c, const void* q, const void* k_new, const vo
   return tova_decode_steps(c, 1, q, k_new, v_new, out, evicted, hip_stream);
 }
 
+int tova_cache_multi_step_blocks(const tova_cache_t* c, int32_t* blocks) {
+  if (!c || !blocks) return TOVA_EINVAL;
+  *blocks = c->r.multi_step ? c->r.multi_grid : 0;
+  return TOVA_OK;
+}
+
 int tova_cache_tokens_seen(const tova_cache_t* c, int64_t* t) {
   if (!c || !t) return TOVA_EINVAL;
   *t = c->t;
