@@ -116,7 +116,7 @@ int resolve(const tova_config_t* c, Resolved* r) {
   r->force_slow = 0;
   if (const char* e = std::getenv("TOVA_FORCE_SLOW_MERGE")) r->force_slow = (std::atoi(e) != 0);  // test hook
   // multi-step launches (decided for good in tova_cache_init, which can ask the device)
-  r->multi_step = (S == 1);
+  r->multi_step = 1;
   if (const char* e = std::getenv("TOVA_MULTI_STEP")) r->multi_step = r->multi_step && (std::atoi(e) != 0);
   r->persist_spin = 1 << 22;  // polls of ~0.2 us or more each: seconds, i.e. "something is broken"
   if (const char* e = std::getenv("TOVA_MULTI_STEP_SPIN")) {  // test hook: make the wait run out
@@ -145,7 +145,7 @@ int resolve(const tova_config_t* c, Resolved* r) {
   if (S > 1) {
     r->escr_off = off; off += round_up((size_t)r->pairs * r->kp * G * 4, kAlign);
     r->stats_off = off; off += round_up((size_t)r->pairs * S * G * 2 * 4, kAlign);
-    r->accp_off = off; off += round_up((size_t)r->pairs * S * G * r->D * 4, kAlign);
+    r->accp_off = off; off += 2 * round_up((size_t)r->pairs * S * G * r->D * 4, kAlign);  // two parity copies
   }
   r->scratch_bytes = off;
   return TOVA_OK;
@@ -233,7 +233,7 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
   c->r.multi_grid = 0;
   if (c->r.multi_step) {
     const int cap = tova::resident_blocks(r.bf16, r.D, r.G, r.NT, r.lds) / 8 * 8;
-    const int want = (r.pairs + 7) / 8 * 8;
+    const int want = r.grid;
     c->r.multi_grid = want < cap ? want : cap;   // never more blocks than fit at once
     if (c->r.multi_grid < 8) c->r.multi_step = 0;
   }
@@ -273,6 +273,7 @@ int tova_decode_steps(tova_cache_t* c, int32_t n_steps, const void* q, const voi
   p.escr = reinterpret_cast<float*>(c->scratch + r.escr_off);
   p.stats = reinterpret_cast<float*>(c->scratch + r.stats_off);
   p.accp = reinterpret_cast<float*>(c->scratch + r.accp_off);
+  p.accp_half = (int64_t)(round_up((size_t)r.pairs * r.S * r.G * r.D * 4, kAlign) / 4);
   p.pairs = r.pairs; p.H = r.H; p.H_kv = r.H_kv; p.k = r.k;
   p.S = r.S; p.R = r.R; p.kp = r.kp; p.scale = r.scale;
   const tova::LaunchPlan lp{r.grid, r.NT, r.lds};

@@ -24,7 +24,8 @@ struct StepParams {
   float* sg;           // [pairs][kp]        per-KV-head partial of the score vector
   float* escr;         // [pairs][kp][G]     chunk-local exp values   (S > 1 only)
   float* stats;        // [pairs][S][G][2]   chunk-local (max, sum)   (S > 1 only)
-  float* accp;         // [pairs][S][G][d]   chunk-local PV partials  (S > 1 only)
+  float* accp;         // [2][pairs][S][G][d] chunk-local PV partials, by token parity (S > 1 only)
+  int64_t accp_half;   // floats per parity copy
   int32_t* cnt_pair;   // [pairs] arrival counters, zero between launches
   int32_t* cnt_unit;   // [units]
   int32_t* cnt_pub;    // [pairs] chunks that have published their softmax statistics (S > 1 only)

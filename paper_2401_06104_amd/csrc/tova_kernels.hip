@@ -343,24 +343,23 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
   const int c_new = min(n / R, S - 1);  // the chunk that also takes the incoming token
   const bool full = (n == k);
   constexpr int ROW16 = D * (int)sizeof(T) / 16;  // 16-byte pieces per row
-  int pair0, chunk, pstride;
-  if (MULTI) {
-    pair0 = blockIdx.x;
-    chunk = 0;
-    pstride = gridDim.x;
-  } else {
-    const int xcd = blockIdx.x & 7;
-    const int wq = blockIdx.x >> 3;
-    pair0 = (wq / S) * 8 + xcd;
-    chunk = wq % S;
-    pstride = 0x40000000;  // one pair per block
-    if (pair0 >= p.pairs || chunk > c_new) return;
+  // Work items are (pair, chunk) with the chunk index fastest; item li of XCD x is pair
+  // (li / S) * 8 + x, so the chunks of a pair, and the pairs of a unit, sit on neighbouring blocks.
+  const int xcd = blockIdx.x & 7;
+  const int li0 = blockIdx.x >> 3;
+  const int li_stride = MULTI ? (int)(gridDim.x >> 3) : 0x40000000;  // per-step launch: one item per block
+  const int li_end = ((p.pairs + 7) >> 3) * S;
+  if (!MULTI) {
+    if ((li0 / S) * 8 + xcd >= p.pairs || li0 % S > c_new) return;
   }
   const int n_pass = MULTI ? p.n_iter + 1 : 1;  // (the extra pass only stores the last step's rows)
 
   for (int it = 0; it < n_pass; ++it) {
   // (a per-step launch makes exactly one trip through both loops, and the compiler can see that)
-  for (int pair = pair0, trip = 0; MULTI ? (pair < p.pairs) : (trip == 0); pair += pstride, ++trip) {
+  for (int li = li0, trip = 0; MULTI ? (li < li_end) : (trip == 0); li += li_stride, ++trip) {
+  const int pair = (li / S) * 8 + xcd;
+  const int chunk = li % S;
+  if (MULTI && pair >= p.pairs) continue;
   // In a multi-step launch the thread index is re-read through an opaque copy in every pass:
   // otherwise the compiler hoists the lane-dependent address arithmetic of the whole body out of
   // the loops and keeps it in registers across them (+40 VGPRs and spills).
@@ -403,11 +402,11 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
     __syncthreads();
     if (flag_lds[2] == 0) return;  // block-uniform
     const int vic = flag_lds[3];
-    if (vic < k && tid < ROW16) {
+    if (vic >= r0 && vic < r1 && tid < ROW16) {  // (vic == k: the incoming token was dropped) the chunk that owns the slot
       const T* kprev = reinterpret_cast<const T*>(p.k_new) + (size_t)(it - 1) * p.kv_stride + (size_t)pair * D;
       const T* vprev = reinterpret_cast<const T*>(p.v_new) + (size_t)(it - 1) * p.kv_stride + (size_t)pair * D;
-      reinterpret_cast<V16*>(const_cast<T*>(Kb) + (size_t)vic * D)[tid] = reinterpret_cast<const V16*>(kprev)[tid];
-      reinterpret_cast<V16*>(const_cast<T*>(Vb) + (size_t)vic * D)[tid] = reinterpret_cast<const V16*>(vprev)[tid];
+      reinterpret_cast<V16*>(const_cast<T*>(Kb) + (size_t)(vic - r0) * D)[tid] = reinterpret_cast<const V16*>(kprev)[tid];
+      reinterpret_cast<V16*>(const_cast<T*>(Vb) + (size_t)(vic - r0) * D)[tid] = reinterpret_cast<const V16*>(vprev)[tid];
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_s_waitcnt(0);
@@ -705,7 +704,9 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
     }
   } else {
     // ---------------- phase 4a: several chunks per (unit, KV head) ----------------
-    float* ap = p.accp + ((size_t)pair * S + chunk) * (G * D);
+    // (two copies by token parity: in a multi-step launch the finisher may still be merging step t
+    // when a sibling already writes its partial of step t + 1)
+    float* ap = p.accp + (size_t)(tok & 1) * p.accp_half + ((size_t)pair * S + chunk) * (G * D);
     for (int x = tid; x < G * D; x += nt) {
       float a = red[x];
       for (int w = 1; w < nw; ++w) a += red[w * G * D + x];
@@ -886,7 +887,7 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
 
   // ---------------- the pair finisher merges the chunks' PV partials (off the critical path) ----------------
   if (S > 1 && pair_last) {
-    const float* apf = p.accp + (size_t)pair * S * (G * D);
+    const float* apf = p.accp + (size_t)(tok & 1) * p.accp_half + (size_t)pair * S * (G * D);
     for (int x = tid; x < G * D; x += nt) {
       const int g = x / D;
       float a = 0.f;
