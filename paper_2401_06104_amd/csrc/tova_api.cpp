@@ -15,7 +15,8 @@ namespace {
 
 constexpr size_t kAlign = 256;
 constexpr int kTargetBlocks = 512;     // two workgroups per CU on 256 CUs
-constexpr int kMinRowsPerSplit = 32;   // below this a chunk is all launch overhead
+constexpr size_t kMinBytesPerSplit = 256 * 1024;  // K+V bytes of a chunk below which splitting only adds
+                                                  // hand-offs (each costs ~1 us of memory round trip)
 constexpr int kSmallFloats = 512;      // must match the kernel's fixed LDS area
 constexpr int kMaxLdsBytes = 64 * 1024;
 
@@ -25,7 +26,7 @@ size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Resolved {
   int L, B, k, H, H_kv, G, D, esize, bf16;
-  int units, pairs, S, R, kp, NT, grid, lds, st_off, spin_limit, force_slow, persist_spin, multi_step, multi_grid;
+  int units, pairs, S, R, kp, NT, grid, lds, st_off, spin_limit, force_slow, persist_spin, multi_step, multi_grid, spin_env;
   float scale;
   size_t kv_bytes, state_bytes, scratch_bytes;
   size_t v_off;                                   // in kv_mem
@@ -67,7 +68,8 @@ int resolve(const tova_config_t* c, Resolved* r) {
       if (v >= 1 && v <= (1 << 20)) target = v;
     }
     S = (r->pairs >= target) ? 1 : (target + r->pairs - 1) / r->pairs;
-    int smax = k / kMinRowsPerSplit;
+    const size_t pair_bytes = 2 * (size_t)k * r->D * r->esize;  // K + V of one KV head
+    int smax = (int)(pair_bytes / kMinBytesPerSplit);
     if (smax < 1) smax = 1;
     if (S > smax) S = smax;
   }
@@ -107,11 +109,12 @@ int resolve(const tova_config_t* c, Resolved* r) {
   r->grid = (r->pairs + 7) / 8 * 8 * S;
   // A chunk looks this many more times (about a microsecond apart) for its siblings' statistics
   // before it leaves its score rows to the pair's finisher.  Only worth it when all workgroups of
-  // the grid are resident at once, which ~3 blocks per CU on 256 CUs allow.
-  r->spin_limit = (r->grid <= 768) ? 24 : 0;
+  // the grid are resident at once: tova_cache_init asks the device and clears it otherwise.
+  r->spin_limit = 24;
+  r->spin_env = 0;
   if (const char* e = std::getenv("TOVA_SPIN_LIMIT")) {  // tuning aid / test hook
     int v = std::atoi(e);
-    if (v >= 0 && v <= 4096) r->spin_limit = v;
+    if (v >= 0 && v <= 4096) { r->spin_limit = v; r->spin_env = 1; }
   }
   r->force_slow = 0;
   if (const char* e = std::getenv("TOVA_FORCE_SLOW_MERGE")) r->force_slow = (std::atoi(e) != 0);  // test hook
@@ -231,8 +234,9 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
   // other's results): its grid is capped at what the device can hold, and each block then walks
   // several (unit, KV head) pairs per step.
   c->r.multi_grid = 0;
+  const int cap = tova::resident_blocks(r.bf16, r.D, r.G, r.NT, r.lds) / 8 * 8;
+  if (!r.spin_env && r.grid > cap) c->r.spin_limit = 0;
   if (c->r.multi_step) {
-    const int cap = tova::resident_blocks(r.bf16, r.D, r.G, r.NT, r.lds) / 8 * 8;
     const int want = r.grid;
     c->r.multi_grid = want < cap ? want : cap;   // never more blocks than fit at once
     if (c->r.multi_grid < 8) c->r.multi_step = 0;

@@ -49,6 +49,8 @@ struct bf16_t {
   uint16_t x;
 };
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 template <typename T>
 struct Elem;
@@ -305,6 +307,10 @@ struct Geo {
   static constexpr int RK = 64 / LK;  // rows per wave pass, logit pass
   static constexpr int UK = (G >= 8) ? 1 : 2;  // passes per register buffer (two buffers in flight);
                                                // fewer for wide groups, whose q fragments fill the registers
+  // Wide bf16 groups run the logit pass on the matrix cores (see the kernel): q.K^T for 16 rows x
+  // up to 16 heads per v_mfma_f32_16x16x32_bf16, which takes the register file and the VALU out
+  // of the picture (8 heads of q fragments alone are 64 VGPRs on the vector path).
+  static constexpr bool MFMA_K = (sizeof(T) == 2) && (G >= 8) && (G <= 16) && (D % 32 == 0);
   static constexpr int LV = CH;
   static constexpr int RV = 64 / LV;  // rows per wave pass, PV pass
   static constexpr int UV = (G >= 8) ? 2 : 4;
@@ -314,7 +320,7 @@ struct Geo {
 constexpr float kLog2e = 1.4426950408889634f;
 
 template <typename T, int D, int G, bool MULTI>
-__global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const StepParams p) {
+__global__ __launch_bounds__(512, 4) void tova_step_kernel(const StepParams p) {
   using E = Elem<T>;
   using Ge = Geo<T, D, G>;
   constexpr int VEC = Ge::VEC, CK = Ge::CK, LK = Ge::LK, RK = Ge::RK, UK = Ge::UK;
@@ -427,7 +433,81 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
   float m[G], Z[G];  // chunk-local softmax statistics (log2 domain)
 #pragma unroll
   for (int g = 0; g < G; ++g) m[g] = -INFINITY;
-  {
+  if constexpr (Ge::MFMA_K) {
+    // Matrix-core logit pass.  One v_mfma_f32_16x16x32_bf16 contracts 32 elements of d for 16
+    // cached rows (A: lane l holds row l % 16, eight consecutive elements) against 16 heads
+    // (B: lane l holds head l % 16, the same eight elements; heads >= G are zero); D / 32 of them
+    // cover a row.  Which eight elements a lane holds is free as long as A and B agree: MFMA kk
+    // takes the 16-byte chunk kk * 4 + l / 16, so the four lanes of a row load 64 contiguous bytes.
+    // Result register r of lane l is the logit of row (l / 16) * 4 + r for head l % 16.
+    constexpr int KK = D / 32;
+    constexpr int UM = 2;  // 16-row tiles per register buffer
+    const int r16 = lane & 15, c4 = lane >> 4;
+    V16 qm[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      qm[kk] = V16{{0u, 0u, 0u, 0u}};
+      if (r16 < G) qm[kk] = *reinterpret_cast<const V16*>(qb + r16 * D + (kk * 4 + c4) * 8);
+    }
+    float mh = -INFINITY;  // running maximum of head r16 over the rows this lane sees
+    auto load_tile = [&](V16(&dst)[UM][KK], int base) {
+#pragma unroll
+      for (int u = 0; u < UM; ++u) {
+        const int i = base + u * 16 + r16;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) dst[u][kk] = V16{{0u, 0u, 0u, 0u}};
+        if (i < ncached) {
+          const T* row = Kb + (size_t)i * D;
+#pragma unroll
+          for (int kk = 0; kk < KK; ++kk) dst[u][kk] = *reinterpret_cast<const V16*>(row + (kk * 4 + c4) * 8);
+        }
+      }
+    };
+    auto logits16 = [&](const V16(&a)[KK], int row0, int nvalid) {  // rows row0 .. row0 + 15
+      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[kk]),
+                                                      __builtin_bit_cast(bf16x8_t, qm[kk]), acc, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int i = row0 + c4 * 4 + r;
+        const float l2 = acc[r] * scale2;
+        if (r16 < G && i < nvalid) {
+          mh = fmaxf(mh, l2);
+          e_lds[i * G + r16] = l2;
+        }
+      }
+    };
+    constexpr int TILE = 16 * UM;
+    const int stride = nw * TILE;
+    int base = wave * TILE;
+    V16 bufA[UM][KK], bufB[UM][KK];
+    const bool new_here = has_new && (wave == nw - 1);  // wave-uniform
+    V16 kn[KK];
+    if (new_here) {  // the incoming token as row 0 of an otherwise empty tile
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        kn[kk] = V16{{0u, 0u, 0u, 0u}};
+        if (r16 == 0) kn[kk] = *reinterpret_cast<const V16*>(knew + (kk * 4 + c4) * 8);
+      }
+    }
+    load_tile(bufA, base);
+    if (new_here) logits16(kn, ncached, ncached + 1);  // candidate `ncached` (App. B: the last column)
+    while (base < ncached) {  // two register buffers: the next tile is in flight while this one is used
+      load_tile(bufB, base + stride);
+#pragma unroll
+      for (int u = 0; u < UM; ++u) logits16(bufA[u], base + u * 16, ncached);
+      base += stride;
+      if (base >= ncached) break;
+      load_tile(bufA, base + stride);
+#pragma unroll
+      for (int u = 0; u < UM; ++u) logits16(bufB[u], base + u * 16, ncached);
+      base += stride;
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) m[g] = (g == r16) ? mh : -INFINITY;
+  } else {
     const int lk = lane % LK;  // position inside the row
     const int rk = lane / LK;  // which of the RK rows of a wave pass
     V16 qf[G][CK];
@@ -672,19 +752,49 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
     basev += stridev;
   }
   // combine the RV row groups of the wave, then the waves (in wave order)
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) {
-      acc[g][v] = column_sum<LV>(acc[g][v]);
-    }
-  __syncthreads();  // everyone is done reading e_lds; the reduction area reuses it
   float* red = big;  // [nw][G*D]
-  if (rv == 0) {
+  if constexpr (LV == 16 && (G * VEC) % 4 == 0) {
+    // Four row groups of 16 lanes.  Transposing reduction: swapping rows between the registers of
+    // two different values and adding halves the number of live registers at each of the two
+    // stages (odd/even rows, then upper/lower half), and leaves the total of value 4 j + r in row
+    // r of register j -- so all 64 lanes, not 16, write the wave's result to LDS.
+    constexpr int NV = G * VEC;
+    float b[NV / 2];
+#pragma unroll
+    for (int j = 0; j < NV / 2; ++j) {
+      unsigned x = __builtin_bit_cast(unsigned, acc[(2 * j) / VEC][(2 * j) % VEC]);
+      unsigned y = __builtin_bit_cast(unsigned, acc[(2 * j + 1) / VEC][(2 * j + 1) % VEC]);
+      swap_rows16(x, y);  // x: rows 0,2 keep value 2j, rows 1,3 get value 2j+1 of the row below/above
+      b[j] = __builtin_bit_cast(float, x) + __builtin_bit_cast(float, y);
+    }
+    float c[NV / 4];
+#pragma unroll
+    for (int j = 0; j < NV / 4; ++j) {
+      unsigned x = __builtin_bit_cast(unsigned, b[2 * j]);
+      unsigned y = __builtin_bit_cast(unsigned, b[2 * j + 1]);
+      swap_rows32(x, y);
+      c[j] = __builtin_bit_cast(float, x) + __builtin_bit_cast(float, y);
+    }
+    __syncthreads();  // everyone is done reading e_lds; the reduction area reuses it
+#pragma unroll
+    for (int j = 0; j < NV / 4; ++j) {
+      const int idx = 4 * j + rv;  // value index g * VEC + v held by this lane's row
+      red[(wave * G + idx / VEC) * D + lv * VEC + idx % VEC] = c[j];
+    }
+  } else {
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) red[(wave * G + g) * D + lv * VEC + v] = acc[g][v];
+      for (int v = 0; v < VEC; ++v) {
+        acc[g][v] = column_sum<LV>(acc[g][v]);
+      }
+    __syncthreads();  // everyone is done reading e_lds; the reduction area reuses it
+    if (rv == 0) {
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) red[(wave * G + g) * D + lv * VEC + v] = acc[g][v];
+    }
   }
   __syncthreads();
 
@@ -821,7 +931,7 @@ __global__ __launch_bounds__(512, (G >= 8) ? 2 : 4) void tova_step_kernel(const 
       }
       float best = INFINITY;
       int bj = 0x7fffffff;
-      constexpr int JM = (G >= 8) ? 2 : 1;  // the wide-group kernel has registers to spare here
+      constexpr int JM = 1;
       if (p.H_kv <= 2)
         scan_scores<8 * JM, 2>(sgu, p.H_kv, p.kp, k, tid, nt, best, bj);
       else if (p.H_kv <= 4)

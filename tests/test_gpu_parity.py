@@ -100,9 +100,9 @@ def test_identical_keys_evict_slot_zero():
 
 # ---- the paper-shaped configs ----------------------------------------------------------------
 def test_c2_llama7b_layer_prefix():
-    """Config 2 shape (split over 16 chunks per head), first 1100 tokens."""
+    """Config 2 shape, forced to 16 slot chunks per head (32-row chunks), first 1100 tokens."""
     spec = spec_for("c2_llama7b_layer", T=1100)
-    stats, res = _run(spec, seed=2, units=[(0, 0)])
+    stats, res = _run(spec, seed=2, units=[(0, 0)], n_splits=16)
     assert res["layout"][0] == 16
 
 

@@ -77,7 +77,8 @@ def test_validation_errors():
 @pytest.mark.parametrize("c,expect_S", [
     (cfg(), 1),                                                        # tiny: one chunk
     (cfg(B=64, k=1024, H=32, Hkv=8, d=128, dt=TOVA_BF16), 1),          # 512 (seq, KV head) pairs
-    (cfg(k=512, H=32, Hkv=32, d=128, dt=TOVA_BF16), 16),               # 32 pairs -> split
+    (cfg(k=512, H=32, Hkv=32, d=128, dt=TOVA_BF16), 1),                # 32 pairs, but only 256 KiB each
+    (cfg(k=2048, H=32, Hkv=32, d=128, dt=TOVA_BF16), 4),               # 32 pairs of 1 MiB -> split
     (cfg(L=32, k=4096, H=32, Hkv=4, d=128, dt=TOVA_BF16), 4),          # 128 pairs -> split
     (cfg(L=32, B=64, k=4096, H=32, Hkv=32, d=128, dt=TOVA_BF16), 1),
 ])
