@@ -320,7 +320,7 @@ struct Geo {
 constexpr float kLog2e = 1.4426950408889634f;
 
 template <typename T, int D, int G, bool MULTI>
-__global__ __launch_bounds__(512, 4) void tova_step_kernel(const StepParams p) {
+__global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kernel(const StepParams p) {
   using E = Elem<T>;
   using Ge = Geo<T, D, G>;
   constexpr int VEC = Ge::VEC, CK = Ge::CK, LK = Ge::LK, RK = Ge::RK, UK = Ge::UK;
