@@ -802,7 +802,10 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
   bool pair_last = true;  // this block completes its (unit, KV head)
   int unit_add = 1;       // what it contributes to the unit's arrival count (S > 1: per chunk)
 
-  if (S == 1) {
+  // One chunk per KV head: the block's own PV sums are final.  When the cache is full the stores
+  // are issued after the arrival below, so that they do not sit between this block's last read of
+  // K/V and the arrival (which waits for the block's outstanding stores).
+  auto store_out_single = [&]() {
     for (int x = tid; x < G * D; x += nt) {
       float a = red[x];
       for (int w = 1; w < nw; ++w) a += red[w * G * D + x];
@@ -812,6 +815,9 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
       for (int g = 1; g < G; ++g) zg = (x / D == g) ? Z[g] : zg;
       E::store(outb + x, a / zg);
     }
+  };
+  if (S == 1) {
+    if (!full) store_out_single();
   } else {
     // ---------------- phase 4a: several chunks per (unit, KV head) ----------------
     // (two copies by token parity: in a multi-step launch the finisher may still be merging step t
@@ -916,6 +922,7 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
       unit_last = (prev + unit_add == expected);
       if (unit_last) reset_counter(p.cnt_unit + unit, tid);
     }
+    if (S == 1) store_out_single();
     if (unit_last) {
       // Head-mean score over the k+1 candidates (as a sum: the factor 1/H does not move the
       // argmin), KV-head partials added in head order; lowest index wins ties.
