@@ -51,6 +51,8 @@ SWEEP = [
     ("bf16", 64, 16, 8, 130, 300, 2, 2, 4),
     ("bf16", 32, 8, 2, 77, 200, 1, 5, 0),
     ("bf16", 128, 2, 1, 640, 900, 1, 9, 2),     # more units than one XCD round
+    ("bf16", 64, 8, 8, 48, 120, 8, 40, 1),      # 2560 (unit, KV head) pairs: more than fit on the device at
+                                                # once, so a multi-step launch walks several pairs per block
 ]
 
 
@@ -59,6 +61,8 @@ def test_shape_sweep(dtype, d, H, H_kv, k, T, L, B, splits):
     spec = StreamSpec(f"sweep_{dtype}_d{d}_h{H}_{H_kv}_k{k}", L=L, B=B, H=H, H_kv=H_kv, d=d, dtype=dtype,
                       k=k, T=T, sink="first", n_sinks=2)
     units = [(l, b) for l in range(L) for b in range(B)][:4]
+    if L * B > 16:
+        units = [(0, 0), (L // 2, B // 3), (L - 1, B - 1)]
     stats, _ = _run(spec, seed=100 + k, units=units, n_splits=splits, workers=4)
     if dtype == "f32":
         assert all(s["mismatches"] == 0 for s in stats)

@@ -72,6 +72,8 @@ def test_validation_errors():
     assert lib.tova_decode_steps(None, 3, None, None, None, None, None, None) == TOVA_EINVAL
     assert lib.tova_cache_destroy(None) == TOVA_EINVAL
     assert lib.tova_cache_tokens_seen(None, None) == TOVA_EINVAL
+    assert lib.tova_cache_set_tokens_seen(None, 0) == TOVA_EINVAL
+    assert lib.tova_cache_multi_step_blocks(None, None) == TOVA_EINVAL
 
 
 @pytest.mark.parametrize("c,expect_S", [
@@ -96,6 +98,7 @@ def test_launch_plan(c, expect_S):
     esize = 2 if c.dtype == TOVA_BF16 else 4
     assert kv == 2 * pairs * k * c.head_dim * esize and lay.v_offset == kv // 2 and lay.k_offset == 0
     assert st >= lay.slot_token_offset + 4 * c.n_layers * c.batch * k
+    assert lay.slot_token_offset + 4 * c.n_layers * c.batch * k <= lay.error_flag_offset <= st - 4
     assert lay.slot_token_offset >= 4 * c.n_layers * c.batch
 
 
