@@ -16,5 +16,5 @@ What is pinned and what is not:
     example); they are trusted only because the routine that produces them
     passes the pins above.
 """
-from .tova_oracle import TovaOracle, run_stream  # noqa: F401
+from .tova_oracle import TovaOracle, TovaHeadOracle, run_stream  # noqa: F401
 from .tova_literal import tova_policy, LiteralTova  # noqa: F401

@@ -25,6 +25,14 @@ Readings the paper leaves open (all listed in the design notes):
   * with grouped-query attention the mean runs over all H query heads and the
     one victim is shared by every KV head.
 
+Two variants from the paper's policy ablation (App. A) are covered as well:
+  * TOVA+i: the first i tokens are additionally never dropped (`pinned=i`); they
+    occupy slots 0..i-1 from the fill phase on, so the argmin simply skips those
+    candidates;
+  * TOVA-head: every head keeps its own set of tokens (TovaHeadOracle); with
+    grouped-query attention a "head" is a KV head with the G query heads it serves,
+    averaged as in the layer variant.
+
 Everything is float64; inputs are whatever the caller rounded them to
 (bf16 / fp32 values convert to float64 exactly).
 """
@@ -45,9 +53,11 @@ class StepResult:
 
 
 class TovaOracle:
-    def __init__(self, k: int, H: int, H_kv: int, d: int, scale: Optional[float] = None):
+    def __init__(self, k: int, H: int, H_kv: int, d: int, scale: Optional[float] = None, pinned: int = 0):
         assert k >= 1 and H >= 1 and H_kv >= 1 and H % H_kv == 0 and d >= 1
+        assert 0 <= pinned < k
         self.k, self.H, self.H_kv, self.d = k, H, H_kv, d
+        self.pinned = pinned                         # TOVA+i: tokens 0..i-1 (= slots 0..i-1) are kept
         self.G = H // H_kv
         self.scale = (1.0 / np.sqrt(float(d))) if scale is None or scale <= 0 else float(scale)
         self.K = np.zeros((H_kv, k, d), dtype=np.float64)
@@ -84,11 +94,13 @@ class TovaOracle:
 
     # -- step 3b: victim = argmin, lowest index on ties -------------------------
     @staticmethod
-    def select(s):
-        j = int(np.argmin(s))                                     # first occurrence of the minimum
-        rest = np.delete(s, j)
-        gap = float(np.min(rest) - s[j]) if rest.size else float("inf")
-        return j, gap
+    def select(s, pinned: int = 0):
+        """Victim among the candidates pinned..len(s)-1 (pinned = 0: all of them)."""
+        cand = s[pinned:]
+        j = int(np.argmin(cand))                                  # first occurrence of the minimum
+        rest = np.delete(cand, j)
+        gap = float(np.min(rest) - cand[j]) if rest.size else float("inf")
+        return j + pinned, gap
 
     # -- step 3c: state update ---------------------------------------------------
     def update(self, evicted: int, k_new, v_new):
@@ -116,9 +128,26 @@ class TovaOracle:
             self.update(-1, k_new, v_new)
             return StepResult(out, -1, float("inf"), None)
         s = self.scores(p)
-        j, gap = self.select(s)
+        j, gap = self.select(s, self.pinned)
         self.update(j if force_victim is None else int(force_victim), k_new, v_new)
         return StepResult(out, j, gap, s)
+
+
+class TovaHeadOracle:
+    """TOVA-head (App. A): every KV head keeps its own multi-state and drops its own row.
+    KV head g with its G query heads is an independent TovaOracle(k, G, 1, d)."""
+
+    def __init__(self, k: int, H: int, H_kv: int, d: int, scale: Optional[float] = None, pinned: int = 0):
+        assert H % H_kv == 0
+        self.k, self.H, self.H_kv, self.d, self.G = k, H, H_kv, d, H // H_kv
+        self.heads = [TovaOracle(k, self.G, 1, d, scale, pinned) for _ in range(H_kv)]
+
+    def step(self, q, k_new, v_new):
+        """q [H, d], k_new / v_new [H_kv, d] -> list of StepResult, one per KV head."""
+        q = np.asarray(q, dtype=np.float64).reshape(self.H_kv, self.G, self.d)
+        k_new = np.asarray(k_new, dtype=np.float64).reshape(self.H_kv, 1, self.d)
+        v_new = np.asarray(v_new, dtype=np.float64).reshape(self.H_kv, 1, self.d)
+        return [self.heads[g].step(q[g], k_new[g], v_new[g]) for g in range(self.H_kv)]
 
 
 def run_stream(k: int, q, k_new, v_new, scale: Optional[float] = None):

@@ -109,7 +109,7 @@ def _compare_step(spec, unit, t, orc, q, kk, vv, gpu_out_t, ge, stats, tol):
         orc.update(-1, kk, vv)
         return
     s = orc.scores(p)
-    j, gap = orc.select(s)
+    j, gap = orc.select(s, orc.pinned)
     stats["evict_steps"] += 1
     stats["min_gap"] = min(stats["min_gap"], gap)
     if gap < GAP_EXEMPT:

@@ -23,14 +23,14 @@ class WrongGroup(TovaOracle):                    # h % H_kv instead of h // G
 
 class ArgMax(TovaOracle):                        # wrong sign in the victim rule
     @staticmethod
-    def select(s):
+    def select(s, pinned=0):
         j = int(np.argmax(s))
         return j, 0.0
 
 
 class LastOnTies(TovaOracle):                    # highest instead of lowest index on ties
     @staticmethod
-    def select(s):
+    def select(s, pinned=0):
         j = int(len(s) - 1 - np.argmin(s[::-1]))
         rest = np.delete(s, j)
         return j, float(np.min(rest) - s[j])
@@ -38,7 +38,7 @@ class LastOnTies(TovaOracle):                    # highest instead of lowest ind
 
 class NewTokenImmune(TovaOracle):                # argmin over cached rows only
     @staticmethod
-    def select(s):
+    def select(s, pinned=0):
         j = int(np.argmin(s[:-1]))
         rest = np.delete(s, j)
         return j, float(np.min(rest) - s[j])

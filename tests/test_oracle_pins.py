@@ -58,3 +58,61 @@ def test_c1_stream_is_well_separated():
     _, ev, gap, _ = run_stream(spec.k, q, kk, vv)
     assert np.isfinite(gap[spec.k:]).all()
     assert gap[spec.k:].min() > 0.0
+
+
+# ---- variants of the policy ablation (App. A): TOVA+i and TOVA-head ---------------------------
+def test_pinned_tokens_never_leave_and_rule_is_argmin_over_the_rest():
+    """TOVA+i: brute force from the raw stream, with the first i tokens excluded from the argmin."""
+    import math
+    rng = np.random.default_rng(77)
+    for (k, H, H_kv, d, pinned) in [(5, 4, 2, 4, 1), (6, 3, 3, 2, 4), (3, 2, 1, 3, 2)]:
+        T = 5 * k
+        q, kk, vv = rng.standard_normal((T, H, d)), rng.standard_normal((T, H_kv, d)), rng.standard_normal((T, H_kv, d))
+        orc = TovaOracle(k, H, H_kv, d, pinned=pinned)
+        ref = TovaOracle(k, H, H_kv, d)                    # plain policy on the same stream, for contrast
+        retained, differs = [], False
+        for t in range(T):
+            before = orc.slot_token.copy()
+            r = orc.step(q[t], kk[t], vv[t])
+            rr = ref.step(q[t], kk[t], vv[t])
+            cand = retained + [t]
+            if len(cand) <= k:
+                retained = cand
+                assert r.evicted == -1
+            else:
+                s = pins._brute_scores(q[t], [kk[c] for c in cand], H // H_kv, 1.0 / math.sqrt(d))
+                free = [c for c in range(len(cand)) if cand[c] >= pinned]
+                victim = cand[min(free, key=lambda c: s[c])]
+                tok = t if r.evicted == k else int(before[r.evicted])
+                assert tok == victim and tok >= pinned
+                retained = [c for c in cand if c != victim]
+            assert all(i in orc.slot_token for i in range(min(pinned, t + 1)))
+            differs = differs or (set(orc.slot_token.tolist()) != set(ref.slot_token.tolist()))
+        assert differs, "pinning never changed anything on this stream: the check has no teeth"
+
+
+def test_head_variant_is_independent_per_kv_head():
+    """TOVA-head: each KV head evolves exactly like a stand-alone layer that has only that head
+    (and its G query heads); with a single KV head it coincides with the layer variant."""
+    from oracle.tova_oracle import TovaHeadOracle
+    rng = np.random.default_rng(5)
+    k, H, H_kv, d, T = 4, 6, 3, 5, 30
+    q, kk, vv = rng.standard_normal((T, H, d)), rng.standard_normal((T, H_kv, d)), rng.standard_normal((T, H_kv, d))
+    ho = TovaHeadOracle(k, H, H_kv, d)
+    solo = [TovaOracle(k, H // H_kv, 1, d) for _ in range(H_kv)]
+    layer = TovaOracle(k, H, H_kv, d)
+    same_as_layer = True
+    for t in range(T):
+        rs = ho.step(q[t], kk[t], vv[t])
+        rl = layer.step(q[t], kk[t], vv[t])
+        for g in range(H_kv):
+            r1 = solo[g].step(q[t, 2 * g:2 * g + 2], kk[t, g:g + 1], vv[t, g:g + 1])
+            assert rs[g].evicted == r1.evicted and np.array_equal(rs[g].out, r1.out)
+            same_as_layer = same_as_layer and rs[g].evicted == rl.evicted
+    assert not same_as_layer, "heads never disagreed with the layer-wide victim on this stream"
+    one = TovaHeadOracle(k, 4, 1, d)
+    lay = TovaOracle(k, 4, 1, d)
+    for t in range(T):
+        a = one.step(q[t, :4], kk[t, :1], vv[t, :1])[0]
+        b = lay.step(q[t, :4], kk[t, :1], vv[t, :1])
+        assert a.evicted == b.evicted and np.array_equal(a.out, b.out)
