@@ -64,6 +64,13 @@ typedef struct {
   int32_t dtype;        /* TOVA_F32 or TOVA_BF16: type of q, k, v, K, V and out        */
   float softmax_scale;  /* <= 0 selects 1 / sqrt(d)                                    */
   int32_t n_splits;     /* 0 = automatic; S >= 1 asks for S slot chunks per KV head    */
+  /* Variants of the paper's policy ablation (App. A); 0 / 0 is the policy described above.        */
+  int32_t n_pinned;     /* TOVA+i: the first i tokens are never dropped, 0 <= i < k (they hold  */
+                        /* slots 0..i-1 from the fill phase on and are skipped by the argmin)   */
+  int32_t per_head;     /* TOVA-head: nonzero = every KV head (with the H / H_kv query heads it */
+                        /* serves, averaged) keeps its own rows and drops its own victim.  Then */
+                        /* evicted, occupancy and slot_token have a trailing [H_kv] dimension   */
+                        /* after [L][B]: evicted [L][B][H_kv], slot_token [L][B][H_kv][k].      */
 } tova_config_t;
 
 /* Where things live inside the caller's buffers (byte offsets). */

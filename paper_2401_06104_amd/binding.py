@@ -28,7 +28,8 @@ class TovaError(RuntimeError):
 class TovaConfig(ctypes.Structure):
     _fields_ = [("n_layers", c_int32), ("batch", c_int32), ("capacity_k", c_int32),
                 ("n_q_heads", c_int32), ("n_kv_heads", c_int32), ("head_dim", c_int32),
-                ("dtype", c_int32), ("softmax_scale", c_float), ("n_splits", c_int32)]
+                ("dtype", c_int32), ("softmax_scale", c_float), ("n_splits", c_int32),
+                ("n_pinned", c_int32), ("per_head", c_int32)]
 
 
 class TovaLayout(ctypes.Structure):
@@ -105,14 +106,16 @@ class TovaCache:
 
     def __init__(self, n_layers: int, batch: int, capacity_k: int, n_q_heads: int, n_kv_heads: int,
                  head_dim: int, dtype="bf16", softmax_scale: float = 0.0, n_splits: int = 0,
-                 device="cuda:0", stream=None):
+                 device="cuda:0", stream=None, n_pinned: int = 0, per_head: bool = False):
         import torch
         self._torch = torch
         self.lib = load_library()
         code = {"f32": TOVA_F32, "fp32": TOVA_F32, "float32": TOVA_F32, torch.float32: TOVA_F32,
                 "bf16": TOVA_BF16, "bfloat16": TOVA_BF16, torch.bfloat16: TOVA_BF16}[dtype]
         self.cfg = TovaConfig(n_layers, batch, capacity_k, n_q_heads, n_kv_heads, head_dim, code,
-                              float(softmax_scale), int(n_splits))
+                              float(softmax_scale), int(n_splits), int(n_pinned), int(bool(per_head)))
+        # shape of evicted / occupancy (slot_token: + [k]); TOVA-head keeps them per KV head
+        self.state_shape = (n_layers, batch, n_kv_heads) if per_head else (n_layers, batch)
         self.torch_dtype = torch.float32 if code == TOVA_F32 else torch.bfloat16
         self.device = torch.device(device)
         self.layout = tova_cache_layout(self.cfg)
@@ -145,16 +148,20 @@ class TovaCache:
 
     @property
     def occupancy(self):
-        c = self.cfg
         o = self.layout.occupancy_offset
-        return self.state_mem[o:o + 4 * c.n_layers * c.batch].view(self._torch.int32).view(c.n_layers, c.batch)
+        n = 1
+        for x in self.state_shape:
+            n *= x
+        return self.state_mem[o:o + 4 * n].view(self._torch.int32).view(self.state_shape)
 
     @property
     def slot_token(self):
         c = self.cfg
         o = self.layout.slot_token_offset
-        n = c.n_layers * c.batch * c.capacity_k
-        return self.state_mem[o:o + 4 * n].view(self._torch.int32).view(c.n_layers, c.batch, c.capacity_k)
+        n = c.capacity_k
+        for x in self.state_shape:
+            n *= x
+        return self.state_mem[o:o + 4 * n].view(self._torch.int32).view(*self.state_shape, c.capacity_k)
 
     @property
     def error_flag(self):
@@ -195,7 +202,7 @@ class TovaCache:
         self._check("k_new", k_new, (c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
         self._check("v_new", v_new, (c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
         self._check("out", out, (c.n_layers, c.batch, c.n_q_heads, c.head_dim))
-        ev = self._evicted_ptr(evicted, (c.n_layers, c.batch))
+        ev = self._evicted_ptr(evicted, self.state_shape)
         rc = self.lib.tova_decode_step(self._h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
                                        out.data_ptr(), ev, _stream_handle(stream))
         if rc != TOVA_OK:
@@ -208,7 +215,7 @@ class TovaCache:
         self._check("k_new", k_new, (T, c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
         self._check("v_new", v_new, (T, c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
         self._check("out", out, (T, c.n_layers, c.batch, c.n_q_heads, c.head_dim))
-        ev = self._evicted_ptr(evicted, (T, c.n_layers, c.batch))
+        ev = self._evicted_ptr(evicted, (T, *self.state_shape))
         rc = self.lib.tova_decode_steps(self._h, T, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
                                         out.data_ptr(), ev, _stream_handle(stream))
         if rc != TOVA_OK:

@@ -26,6 +26,7 @@ size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Resolved {
   int L, B, k, H, H_kv, G, D, esize, bf16;
+  int n_pinned, per_head;
   int units, pairs, S, R, kp, NT, grid, lds, st_off, spin_limit, force_slow, persist_spin, multi_step, multi_grid, spin_env;
   float scale;
   size_t kv_bytes, state_bytes, scratch_bytes;
@@ -43,6 +44,7 @@ int resolve(const tova_config_t* c, Resolved* r) {
   if (c->n_q_heads % c->n_kv_heads != 0) return TOVA_EINVAL;
   if (c->dtype != TOVA_F32 && c->dtype != TOVA_BF16) return TOVA_EINVAL;
   if (!(c->softmax_scale == c->softmax_scale)) return TOVA_EINVAL;  // NaN
+  if (c->n_pinned < 0 || c->n_pinned >= c->capacity_k) return TOVA_EINVAL;
   const int G = c->n_q_heads / c->n_kv_heads;
   if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return TOVA_ENOSUP;
   if (G != 1 && G != 2 && G != 4 && G != 8) return TOVA_ENOSUP;
@@ -56,6 +58,15 @@ int resolve(const tova_config_t* c, Resolved* r) {
   r->H_kv = c->n_kv_heads; r->G = G; r->D = c->head_dim;
   r->bf16 = (c->dtype == TOVA_BF16); r->esize = r->bf16 ? 2 : 4;
   r->units = (int)units; r->pairs = (int)pairs;
+  r->n_pinned = c->n_pinned;
+  r->per_head = (c->per_head != 0);
+  if (r->per_head) {
+    // TOVA-head is the same computation with every KV head as a unit of its own: q [L][B][H][d] is
+    // [L*B*H_kv][G][d], K/V [L][B][H_kv][k][d] is [L*B*H_kv][1][k][d]; nothing else changes.
+    r->units = (int)pairs;
+    r->H = G;
+    r->H_kv = 1;
+  }
   r->scale = c->softmax_scale > 0.f ? c->softmax_scale : (float)(1.0 / std::sqrt((double)r->D));
 
   // ---- split count: enough workgroups to fill 256 CUs, chunks that fit LDS ----
@@ -278,7 +289,7 @@ int tova_decode_steps(tova_cache_t* c, int32_t n_steps, const void* q, const voi
   p.stats = reinterpret_cast<float*>(c->scratch + r.stats_off);
   p.accp = reinterpret_cast<float*>(c->scratch + r.accp_off);
   p.accp_half = (int64_t)(round_up((size_t)r.pairs * r.S * r.G * r.D * 4, kAlign) / 4);
-  p.pairs = r.pairs; p.H = r.H; p.H_kv = r.H_kv; p.k = r.k;
+  p.pairs = r.pairs; p.H = r.H; p.H_kv = r.H_kv; p.k = r.k; p.n_pinned = r.n_pinned;
   p.S = r.S; p.R = r.R; p.kp = r.kp; p.scale = r.scale;
   const tova::LaunchPlan lp{r.grid, r.NT, r.lds};
 

@@ -42,6 +42,7 @@ struct StepParams {
   int32_t* error_flag;           // set when a block gave up waiting
   int32_t pairs;       // units * H_kv
   int32_t H, H_kv, k;
+  int32_t n_pinned;    // candidates 0..n_pinned-1 are never the victim
   int32_t n;           // rows cached before this step, min(t, k)
   int32_t S, R;        // chunks per KV head, slots per chunk
   int32_t kp;          // k + 1 rounded up to 64: stride of sg / escr

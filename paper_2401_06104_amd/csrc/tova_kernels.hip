@@ -247,11 +247,12 @@ __device__ __forceinline__ void reset_counter(int32_t* counter, int tid) {
 // Unit finisher: per-thread argmin over the head-summed scores of the k+1 candidates.
 // sgu[h * kp + j] is KV head h's partial for candidate j.  A thread owns candidate pairs
 // (2m, 2m+1), m = tid + i * nt, sums the H_kv partials in head order and keeps the lowest
-// (ascending j, strict <, so the lowest index wins ties).  The loads bypass the caches, so
+// (ascending j, strict <, so the lowest index wins ties; candidates below n_pinned are kept out:
+// TOVA+i, App. A).  The loads bypass the caches, so
 // JB * HB of them are issued before the first is used.
 template <int JB, int HB>
-__device__ __forceinline__ void scan_scores(const float* sgu, int H_kv, int kp, int k, int tid, int nt,
-                                            float& best, int& bj) {
+__device__ __forceinline__ void scan_scores(const float* sgu, int H_kv, int kp, int k, int n_pinned, int tid,
+                                            int nt, float& best, int& bj) {
   const int npair2 = (k + 2) / 2;  // candidate pairs covering 0..k
   for (int m0 = tid; m0 < npair2; m0 += nt * JB) {
     float s0[JB], s1[JB];
@@ -279,11 +280,11 @@ __device__ __forceinline__ void scan_scores(const float* sgu, int H_kv, int kp, 
 #pragma unroll
     for (int b = 0; b < JB; ++b) {
       const int j0 = 2 * (m0 + b * nt);
-      if (j0 <= k && s0[b] < best) {
+      if (j0 >= n_pinned && j0 <= k && s0[b] < best) {
         best = s0[b];
         bj = j0;
       }
-      if (j0 + 1 <= k && s1[b] < best) {
+      if (j0 + 1 >= n_pinned && j0 + 1 <= k && s1[b] < best) {
         best = s1[b];
         bj = j0 + 1;
       }
@@ -940,11 +941,11 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
       int bj = 0x7fffffff;
       constexpr int JM = 1;
       if (p.H_kv <= 2)
-        scan_scores<8 * JM, 2>(sgu, p.H_kv, p.kp, k, tid, nt, best, bj);
+        scan_scores<8 * JM, 2>(sgu, p.H_kv, p.kp, k, p.n_pinned, tid, nt, best, bj);
       else if (p.H_kv <= 4)
-        scan_scores<4 * JM, 4>(sgu, p.H_kv, p.kp, k, tid, nt, best, bj);
+        scan_scores<4 * JM, 4>(sgu, p.H_kv, p.kp, k, p.n_pinned, tid, nt, best, bj);
       else
-        scan_scores<2 * JM, 8>(sgu, p.H_kv, p.kp, k, tid, nt, best, bj);
+        scan_scores<2 * JM, 8>(sgu, p.H_kv, p.kp, k, p.n_pinned, tid, nt, best, bj);
 #pragma unroll
       for (int o = 32; o >= 1; o >>= 1) {
         float ob = __shfl_xor(best, o);

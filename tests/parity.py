@@ -27,20 +27,25 @@ GAP_EXEMPT = 1e-6
 
 def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: int = 256,
             single_step_calls: bool = False, device="cuda:0", prefill: bool = False, keep=None,
-            progress: bool = False):
+            progress: bool = False, n_pinned: int = 0, per_head: bool = False):
     """units: list of (layer, seq) whose outputs are kept.  Returns a dict of CPU arrays.
 
     prefill=True skips the fill phase: the first k tokens are laid down directly (slot j holds
     token j, which is exactly what k fill steps produce -- App. B's no-op branch) and stepping
     starts at token k through tova_cache_set_tokens_seen.
-    keep: list of (t0, t1) step ranges whose outputs are kept (default: all steps)."""
+    keep: list of (t0, t1) step ranges whose outputs are kept (default: all steps).
+    n_pinned / per_head: the TOVA+i / TOVA-head variants (App. A).  With per_head the results come
+    back in the equivalent layer-mode view -- B * H_kv sequences of one KV head with G query heads
+    each (the stream's flat element order is the same) -- and `units` are (layer, b * H_kv + kvh)."""
     from paper_2401_06104_amd import TovaCache
 
     dev = torch.device(device)
     cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype,
-                      n_splits=n_splits, device=dev)
+                      n_splits=n_splits, device=dev, n_pinned=n_pinned, per_head=per_head)
     stream = Stream(spec, seed, device=dev)
-    evicted = torch.full((spec.T, spec.L, spec.B), -1, dtype=torch.int32, device=dev)
+    evicted = torch.full((spec.T, *cache.state_shape), -1, dtype=torch.int32, device=dev)
+    Bv = spec.B * spec.H_kv if per_head else spec.B              # sequences / heads per sequence of the view
+    Hv, Hkv_v = (spec.H // spec.H_kv, 1) if per_head else (spec.H, spec.H_kv)
     ul = torch.tensor([u[0] for u in units], device=dev)
     ub = torch.tensor([u[1] for u in units], device=dev)
     t_begin = spec.k if prefill else 0
@@ -70,18 +75,18 @@ def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: 
         for (a, b) in keep:
             lo, hi = max(a, t0), min(b, t1)
             if lo < hi:
-                outs[(a, b)].append(out[lo - t0:hi - t0][:, ul, ub].float().cpu())
+                outs[(a, b)].append(out[lo - t0:hi - t0].view(-1, spec.L, Bv, Hv, spec.d)[:, ul, ub].float().cpu())
         if progress and (t0 // chunk_steps) % 16 == 0:
             torch.cuda.synchronize(dev)
             print(f"[parity]   gpu at step {t1}/{spec.T}", flush=True)
     torch.cuda.synchronize(dev)
     res = {
         "out": {r: (torch.cat(v).numpy() if v else None) for r, v in outs.items()},   # [t, n_units, H, d] f32
-        "evicted": evicted.cpu().numpy(),                     # [T, L, B]
-        "slot_token": cache.slot_token.cpu().numpy(),         # [L, B, k]
-        "occupancy": cache.occupancy.cpu().numpy(),
-        "K": cache.K[ul, ub].float().cpu().numpy(),           # [n_units, H_kv, k, d]
-        "V": cache.V[ul, ub].float().cpu().numpy(),
+        "evicted": evicted.view(spec.T, spec.L, Bv).cpu().numpy(),                  # [T, L, B]
+        "slot_token": cache.slot_token.view(spec.L, Bv, spec.k).cpu().numpy(),      # [L, B, k]
+        "occupancy": cache.occupancy.view(spec.L, Bv).cpu().numpy(),
+        "K": cache.K.view(spec.L, Bv, Hkv_v, spec.k, spec.d)[ul, ub].float().cpu().numpy(),   # [n_units, H_kv, k, d]
+        "V": cache.V.view(spec.L, Bv, Hkv_v, spec.k, spec.d)[ul, ub].float().cpu().numpy(),
         "layout": (cache.layout.n_splits, cache.layout.rows_per_split, cache.layout.block_threads,
                    cache.layout.grid_blocks),
         "tokens_seen": cache.tokens_seen,
@@ -130,7 +135,7 @@ def _new_stats(unit, steps):
 
 
 def check_unit(spec: StreamSpec, seed: int, unit, gpu_out, gpu_evicted, gpu_slot_token, gpu_K, gpu_V,
-               t_stop=None, prefill=False, out_t0=0):
+               t_stop=None, prefill=False, out_t0=0, n_pinned=0):
     """Steps the oracle over unit=(layer, seq) from the start of the stream (or, with prefill,
     from the state "slot j holds token j") and compares with the GPU's log.
     gpu_out [t, H, d] holds steps out_t0.. ; gpu_evicted [T]; gpu_slot_token [k]; gpu_K / gpu_V
@@ -142,7 +147,7 @@ def check_unit(spec: StreamSpec, seed: int, unit, gpu_out, gpu_evicted, gpu_slot
     T = spec.T if t_stop is None else t_stop
     tol = OUT_TOL[spec.dtype]
     st = Stream(spec, seed, device="cpu", layers=[l], seqs=[b])
-    orc = TovaOracle(spec.k, spec.H, spec.H_kv, spec.d)
+    orc = TovaOracle(spec.k, spec.H, spec.H_kv, spec.d, pinned=n_pinned)
     stats = _new_stats(unit, T)
     kk_all, vv_all = [], []
     for t0 in range(0, T, 512):
@@ -237,7 +242,7 @@ def _check_unit_star(args):
     return check_unit(*args)
 
 
-def check_units(spec, seed, units, res, workers: int = 1, t_stop=None, out=None, out_t0=None):
+def check_units(spec, seed, units, res, workers: int = 1, t_stop=None, out=None, out_t0=None, n_pinned=0):
     """Checks every sampled unit; with workers > 1 in spawned CPU-only processes."""
     jobs = []
     out = res["out"] if out is None else out
@@ -245,7 +250,7 @@ def check_units(spec, seed, units, res, workers: int = 1, t_stop=None, out=None,
     for ui, (l, b) in enumerate(units):
         jobs.append((spec, seed, (l, b), out[:, ui], res["evicted"][:, l, b],
                      res["slot_token"][l, b], res["K"][ui], res["V"][ui], t_stop, res.get("prefill", False),
-                     out_t0))
+                     out_t0, n_pinned))
     if workers <= 1 or len(jobs) == 1:
         return [check_unit(*j) for j in jobs]
     import multiprocessing as mp

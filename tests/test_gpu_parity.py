@@ -250,3 +250,33 @@ def test_multi_step_wait_runs_out_cleanly(monkeypatch):
     torch.cuda.synchronize()
     assert int(cache.error_flag.item()) == 1
     cache.destroy()
+
+
+# ---- variants of the policy ablation (App. A) -----------------------------------------------
+@pytest.mark.parametrize("dtype,H,H_kv,k,pinned,splits", [("f32", 4, 4, 24, 1, 0), ("bf16", 16, 4, 200, 4, 0),
+                                                          ("bf16", 8, 2, 150, 4, 3)])
+def test_variant_pinned_first_tokens(dtype, H, H_kv, k, pinned, splits):
+    """TOVA+i: the first i tokens are never dropped."""
+    spec = StreamSpec(f"pinned{pinned}_{dtype}", L=2, B=3, H=H, H_kv=H_kv, d=64, dtype=dtype, k=k, T=k + 250)
+    units = [(0, 0), (1, 2)]
+    res = parity.run_gpu(spec, 31, units, n_splits=splits, n_pinned=pinned)
+    parity.check_global_invariants(spec, res)
+    assert (res["slot_token"][:, :, :pinned] == torch.arange(pinned).numpy()).all()
+    assert (res["evicted"][k:] >= pinned).all()
+    for s in parity.check_units(spec, 31, units, res, workers=2, n_pinned=pinned):
+        print(f"[parity]   {s}", flush=True)
+
+
+@pytest.mark.parametrize("dtype,H,H_kv,k,splits", [("f32", 8, 4, 40, 0), ("bf16", 32, 8, 256, 0), ("bf16", 16, 2, 300, 4)])
+def test_variant_per_head(dtype, H, H_kv, k, splits):
+    """TOVA-head: every KV head drops its own victim.  It is the layer-wide computation with each
+    KV head as a sequence of its own (same flat data order), which is how it is checked."""
+    spec = StreamSpec(f"perhead_{dtype}", L=2, B=3, H=H, H_kv=H_kv, d=64, dtype=dtype, k=k, T=k + 200)
+    view = spec.replace(B=spec.B * H_kv, H=H // H_kv, H_kv=1)      # what the oracle steps through
+    units = [(0, 0), (0, H_kv - 1), (1, view.B - 1)]
+    res = parity.run_gpu(spec, 41, units, n_splits=splits, per_head=True)
+    parity.check_global_invariants(view, res)
+    ev = res["evicted"][k:].reshape(-1, spec.L, spec.B, H_kv)
+    assert (ev != ev[..., :1]).any(), "all heads always agreed: the variant was not exercised"
+    for s in parity.check_units(view, 41, units, res, workers=3):
+        print(f"[parity]   {s}", flush=True)

@@ -111,3 +111,15 @@ def test_forced_splits_are_normalised():
     # a chunk that would not fit LDS is split further, whatever was asked
     lay = tova_cache_layout(cfg(k=1 << 16, H=8, Hkv=1, d=128, dt=TOVA_BF16, S=1))
     assert lay.n_splits > 1 and lay.lds_bytes <= 64 * 1024
+
+
+def test_variant_fields():
+    c = TovaConfig(2, 3, 64, 8, 4, 64, TOVA_BF16, 0.0, 0, 0, 0)
+    kv0, st0, _ = tova_cache_bytes(c)
+    for bad in (-1, 64, 65):
+        with pytest.raises(TovaError) as e:
+            tova_cache_bytes(TovaConfig(2, 3, 64, 8, 4, 64, TOVA_BF16, 0.0, 0, bad, 0))
+        assert e.value.status == TOVA_EINVAL
+    kv1, st1, _ = tova_cache_bytes(TovaConfig(2, 3, 64, 8, 4, 64, TOVA_BF16, 0.0, 0, 4, 1))
+    assert kv1 == kv0                      # same cache, ...
+    assert st1 >= 4 * 2 * 3 * 4 * 64 > st0 - 1024   # ... but a slot -> token map per KV head
