@@ -280,3 +280,34 @@ def test_variant_per_head(dtype, H, H_kv, k, splits):
     assert (ev != ev[..., :1]).any(), "all heads always agreed: the variant was not exercised"
     for s in parity.check_units(view, 41, units, res, workers=3):
         print(f"[parity]   {s}", flush=True)
+
+
+# ---- API corners -----------------------------------------------------------------------------
+def test_side_stream_custom_scale_and_zero_steps():
+    """Work is enqueued on the stream the caller names (not the default one), softmax_scale
+    overrides 1/sqrt(d), and a call with zero steps is a no-op."""
+    import numpy as np
+    from oracle.tova_oracle import TovaOracle
+    from paper_2401_06104_amd import TovaCache
+    from workloads import Stream
+    spec = StreamSpec("side", L=1, B=2, H=4, H_kv=2, d=64, dtype="f32", k=20, T=90)
+    scale = 0.31
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype="f32", softmax_scale=scale,
+                          stream=side)
+        c = Stream(spec, 9, device="cuda:0").chunk(0, spec.T)
+        out = torch.empty_like(c["q"])
+        ev = torch.empty(spec.T, spec.L, spec.B, dtype=torch.int32, device="cuda:0")
+        cache.decode_steps(c["q"][:0], c["k"][:0], c["v"][:0], out[:0], ev[:0], stream=side)
+        assert cache.tokens_seen == 0
+        cache.decode_steps(c["q"], c["k"], c["v"], out, ev, stream=side)
+    side.synchronize()
+    assert cache.tokens_seen == spec.T and int(cache.error_flag.item()) == 0
+    orc = TovaOracle(spec.k, spec.H, spec.H_kv, spec.d, scale=scale)
+    q, kk, vv = (c[n][:, 0, 1].double().cpu().numpy() for n in "qkv")
+    for t in range(spec.T):
+        r = orc.step(q[t], kk[t], vv[t])
+        assert r.evicted == int(ev[t, 0, 1])
+        np.testing.assert_allclose(out[t, 0, 1].double().cpu().numpy(), r.out, rtol=0, atol=1e-5 * np.abs(r.out).max())
+    cache.destroy()
