@@ -86,6 +86,9 @@ typedef struct {
   int32_t block_threads;    /* workgroup size the step kernel is launched with   */
   int32_t grid_blocks;      /* workgroups per step                               */
   int32_t lds_bytes;        /* dynamic LDS per workgroup                         */
+  int32_t unit_workgroups;  /* nonzero: a workgroup handles a whole (layer, sequence) unit, its KV
+                               heads in turn (chosen when L * B alone fills the device); grid_blocks
+                               is then L * B, walked by at most a device-filling number of workgroups */
 } tova_layout_t;
 
 /* Sizes of the three caller-owned DEVICE buffers.  kv_bytes is exactly

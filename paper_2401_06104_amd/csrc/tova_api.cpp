@@ -15,6 +15,7 @@ namespace {
 
 constexpr size_t kAlign = 256;
 constexpr int kTargetBlocks = 512;     // two workgroups per CU on 256 CUs
+constexpr int kUnitModeUnits = 256;    // from one unit per CU on, a workgroup takes a whole unit
 constexpr size_t kMinBytesPerSplit = 256 * 1024;  // K+V bytes of a chunk below which splitting only adds
                                                   // hand-offs (each costs ~1 us of memory round trip)
 constexpr int kSmallFloats = 512;      // must match the kernel's fixed LDS area
@@ -28,6 +29,7 @@ struct Resolved {
   int L, B, k, H, H_kv, G, D, esize, bf16;
   int n_pinned, per_head;
   int units, pairs, S, R, kp, NT, grid, lds, st_off, spin_limit, force_slow, persist_spin, multi_step, multi_grid, spin_env;
+  int unit_mode;  // one workgroup per unit instead of one per (unit, KV head, chunk)
   float scale;
   size_t kv_bytes, state_bytes, scratch_bytes;
   size_t v_off;                                   // in kv_mem
@@ -116,8 +118,21 @@ int resolve(const tova_config_t* c, Resolved* r) {
   }
   r->S = S; r->R = R; r->NT = NT; r->st_off = (int)st_off;
   r->kp = (int)round_up((size_t)k + 1, 64);
+  // With at least as many units as workgroups that fill the device, a workgroup takes a whole unit
+  // and goes through its KV heads one after the other: the head-summed scores stay in LDS (a
+  // [k + 1] row behind the big area) and no workgroup ever needs another one's results.
+  r->unit_mode = (S == 1 && r->units >= kUnitModeUnits);
+  if (const char* e = std::getenv("TOVA_UNIT_MODE")) {  // tuning aid / test hook: 0 = never, 1 = whenever possible
+    const int v = std::atoi(e);
+    r->unit_mode = (v != 0) && S == 1;
+  }
+  if (r->unit_mode) {
+    const long long s_fl = ((long long)k + 1 + 3) / 4 * 4;
+    if (big + s_fl <= big_cap) big += s_fl;
+    else r->unit_mode = 0;
+  }
   r->lds = (int)((kSmallFloats + big) * 4);
-  r->grid = (r->pairs + 7) / 8 * 8 * S;
+  r->grid = r->unit_mode ? r->units : (r->pairs + 7) / 8 * 8 * S;
   // A chunk looks this many more times (about a microsecond apart) for its siblings' statistics
   // before it leaves its score rows to the pair's finisher.  Only worth it when all workgroups of
   // the grid are resident at once: tova_cache_init asks the device and clears it otherwise.
@@ -210,6 +225,7 @@ int tova_cache_layout(const tova_config_t* cfg, tova_layout_t* layout) {
   layout->block_threads = r.NT;
   layout->grid_blocks = r.grid;
   layout->lds_bytes = r.lds;
+  layout->unit_workgroups = r.unit_mode;
   return TOVA_OK;
 }
 
@@ -245,9 +261,23 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
   // other's results): its grid is capped at what the device can hold, and each block then walks
   // several (unit, KV head) pairs per step.
   c->r.multi_grid = 0;
-  const int cap = tova::resident_blocks(r.bf16, r.D, r.G, r.NT, r.lds) / 8 * 8;
+  const int cap = tova::resident_blocks(r.bf16, r.D, r.G, r.NT, r.lds, r.unit_mode) / 8 * 8;
   if (!r.spin_env && r.grid > cap) c->r.spin_limit = 0;
-  if (c->r.multi_step) {
+  if (r.unit_mode) {
+    // every launch walks the units with a grid that just fills the device (nothing waits for
+    // anything, so this is a matter of efficiency only)
+    // Measured on MI355X: with one query head per KV head one workgroup per CU streams best (the
+    // fewer concurrent streams, the better for HBM); wider groups have more arithmetic per byte
+    // to hide and want two.
+    const int cus = tova::device_cus();
+    int want = cus > 0 ? cus * (r.G >= 4 ? 2 : 1) : r.grid;
+    if (cap >= 8 && want > cap) want = cap;
+    c->r.multi_grid = want < r.grid ? want : r.grid;
+    if (const char* e = std::getenv("TOVA_UNIT_GRID")) {  // tuning aid
+      const int v = std::atoi(e);
+      if (v >= 1 && v <= r.grid) c->r.multi_grid = v;
+    }
+  } else if (c->r.multi_step) {
     const int want = r.grid;
     c->r.multi_grid = want < cap ? want : cap;   // never more blocks than fit at once
     if (c->r.multi_grid < 8) c->r.multi_step = 0;
@@ -311,11 +341,12 @@ int tova_decode_steps(tova_cache_t* c, int32_t n_steps, const void* q, const voi
     const int32_t m = (r.multi_step && c->t >= r.k && n_steps - i >= 2) ? n_steps - i : 1;
     p.n_iter = m;
     p.persistent = (m > 1);
+    p.unit_mode = r.unit_mode;
     hipError_t e = hipSuccess;
-    if (m > 1)  // the units' state words start from "no step finished"
+    if (m > 1 && !r.unit_mode)  // the units' state words start from "no step finished"
       e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(p.pstate), 0, (size_t)r.units * 2, s);
     const tova::LaunchPlan lpm{r.multi_grid, r.NT, r.lds};
-    if (e == hipSuccess) e = tova::launch_step(r.bf16, r.D, r.G, p, m > 1 ? lpm : lp, s);
+    if (e == hipSuccess) e = tova::launch_step(r.bf16, r.D, r.G, p, (m > 1 || r.unit_mode) ? lpm : lp, s);
     if (e != hipSuccess) return hip_fail(e, "tova_decode_step launch");
     c->t += m;
     i += m;

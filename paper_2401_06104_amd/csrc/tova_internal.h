@@ -36,6 +36,8 @@ struct StepParams {
   // multi-step launch
   int32_t n_iter;      // decode steps handled by this launch (1 for a per-step launch)
   int32_t persistent;  // blocks keep their (unit, KV head) over n_iter steps and wait for victims
+  int32_t unit_mode;   // one block per unit, KV heads in turn: scores and victim stay inside the block
+                       // (st_off is then the float offset of the [k + 1] score row in the big LDS area)
   int32_t persist_spin;          // polls of the unit's state word before a block gives up
   int64_t q_stride, kv_stride;   // elements between consecutive steps of q / out and of k_new / v_new
   unsigned long long* pstate;    // [units] (victim << 32) | (token index + 1) of the unit's last finished step
@@ -59,7 +61,9 @@ hipError_t launch_step(int dtype_is_bf16, int D, int G, const StepParams& p, con
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_t stream);
 // how many blocks of the step kernel (given instantiation, block size, dynamic LDS) fit on the
 // current device at once; 0 if the query fails
-int resident_blocks(int dtype_is_bf16, int D, int G, int block, int lds_bytes);
+int resident_blocks(int dtype_is_bf16, int D, int G, int block, int lds_bytes, int unit_mode);
+// compute units of the current device; 0 if the query fails
+int device_cus();
 
 }  // namespace tova
 #endif

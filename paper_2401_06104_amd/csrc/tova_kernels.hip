@@ -320,8 +320,9 @@ struct Geo {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-template <typename T, int D, int G, bool MULTI>
+template <typename T, int D, int G, bool MULTI, bool UNIT = false>
 __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kernel(const StepParams p) {
+  static_assert(MULTI || !UNIT, "the one-block-per-unit form is built on the multi-step loop");
   using E = Elem<T>;
   using Ge = Geo<T, D, G>;
   constexpr int VEC = Ge::VEC, CK = Ge::CK, LK = Ge::LK, RK = Ge::RK, UK = Ge::UK;
@@ -346,6 +347,12 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
   // back to one of that unit's pairs (every wait is for work that is earlier in the common order,
   // so some block can always make progress).  Each block stores the incoming row of its own pairs
   // itself, so cached rows are only ever written and read by one and the same block.
+  //
+  // One block per unit (UNIT == true, chosen by the host when there are at least as many units as
+  // blocks that fit on the device; always one chunk per KV head): block b keeps the units b,
+  // b + gridDim, ... and goes through the KV heads of a unit one after the other.  The head-summed
+  // scores then never leave LDS and the victim is found by the block itself: no score rows in
+  // device memory, no counters, no waiting for other blocks, and the grid may have any size.
   const int S = p.S, R = p.R, k = p.k, n = p.n;
   const int c_new = min(n / R, S - 1);  // the chunk that also takes the incoming token
   const bool full = (n == k);
@@ -353,20 +360,21 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
   // Work items are (pair, chunk) with the chunk index fastest; item li of XCD x is pair
   // (li / S) * 8 + x, so the chunks of a pair, and the pairs of a unit, sit on neighbouring blocks.
   const int xcd = blockIdx.x & 7;
-  const int li0 = blockIdx.x >> 3;
-  const int li_stride = MULTI ? (int)(gridDim.x >> 3) : 0x40000000;  // per-step launch: one item per block
-  const int li_end = ((p.pairs + 7) >> 3) * S;
+  const int li0 = UNIT ? (int)blockIdx.x : (int)(blockIdx.x >> 3);
+  const int li_stride = UNIT ? (int)gridDim.x : MULTI ? (int)(gridDim.x >> 3) : 0x40000000;  // per-step launch: one item per block
+  const int li_end = UNIT ? p.pairs / p.H_kv : ((p.pairs + 7) >> 3) * S;
   if (!MULTI) {
     if ((li0 / S) * 8 + xcd >= p.pairs || li0 % S > c_new) return;
   }
-  const int n_pass = MULTI ? p.n_iter + 1 : 1;  // (the extra pass only stores the last step's rows)
+  // (without UNIT, an extra pass stores the last step's rows)
+  const int n_pass = UNIT ? p.n_iter : MULTI ? p.n_iter + 1 : 1;
 
   for (int it = 0; it < n_pass; ++it) {
   // (a per-step launch makes exactly one trip through both loops, and the compiler can see that)
   for (int li = li0, trip = 0; MULTI ? (li < li_end) : (trip == 0); li += li_stride, ++trip) {
-  const int pair = (li / S) * 8 + xcd;
-  const int chunk = li % S;
-  if (MULTI && pair >= p.pairs) continue;
+  const int pair0 = UNIT ? li * p.H_kv : (li / S) * 8 + xcd;  // the item's (first) pair
+  const int chunk = UNIT ? 0 : li % S;
+  if (MULTI && !UNIT && pair0 >= p.pairs) continue;
   // In a multi-step launch the thread index is re-read through an opaque copy in every pass:
   // otherwise the compiler hoists the lane-dependent address arithmetic of the whole body out of
   // the loops and keeps it in registers across them (+40 VGPRs and spills).
@@ -374,18 +382,18 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
   if (MULTI) asm volatile("" : "+v"(tid));
   const int lane = tid & 63;
   const int wave = MULTI ? __builtin_amdgcn_readfirstlane(tid >> 6) : (tid >> 6);
-  const int unit = pair / p.H_kv;
-  const int kvh = pair - unit * p.H_kv;
+  const int unit = UNIT ? li : pair0 / p.H_kv;
   const int r0 = chunk * R;
   const int r1 = min(r0 + R, n);
   const int ncached = r1 - r0;                 // cached rows of this chunk
   const bool has_new = (chunk == c_new);       // local candidate `ncached` is the incoming token
   const int nloc = ncached + (has_new ? 1 : 0);  // local candidates, >= 1
-  const T* Kb = reinterpret_cast<const T*>(p.K) + ((size_t)pair * k + r0) * D;
-  const T* Vb = reinterpret_cast<const T*>(p.V) + ((size_t)pair * k + r0) * D;
   const int tok = p.t + it;  // index of the incoming token
 
-  if (MULTI && it > 0) {
+  if (MULTI && !UNIT && it > 0) {
+    const int pair = pair0;
+    const T* Kb = reinterpret_cast<const T*>(p.K) + ((size_t)pair * k + r0) * D;
+    const T* Vb = reinterpret_cast<const T*>(p.V) + ((size_t)pair * k + r0) * D;
     // Wait (bounded) for the victim of this unit's previous step, then put that step's incoming
     // row of this KV head into the freed slot.  If the wait runs out -- it cannot while all blocks
     // are resident, which the host checks before choosing this launch mode -- the block raises the
@@ -421,14 +429,26 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
     if (it == p.n_iter) continue;
   }
 
+  int32_t* const evp = p.evicted ? p.evicted + (size_t)it * (p.pairs / p.H_kv) : nullptr;
+
+  float* e_lds = big;  // [nloc][G]: logits (log2 domain), then exp values
+  float* s_lds = big + p.st_off;  // UNIT: [k + 1] head-summed scores of the unit
+  const float scale2 = p.scale * kLog2e;  // softmax is evaluated as 2^(l2 - max l2)
+
+  for (int kv_i = 0; kv_i < (UNIT ? p.H_kv : 1); ++kv_i) {  // UNIT: the KV heads of the unit in turn
+  // (UNIT: a fresh opaque copy of the thread index per KV head, for the same reason as above)
+  int tid = threadIdx.x;
+  if (MULTI) asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
+  const int wave = MULTI ? __builtin_amdgcn_readfirstlane(tid >> 6) : (tid >> 6);
+  const int pair = pair0 + kv_i;
+  const int kvh = pair - unit * p.H_kv;
+  const T* Kb = reinterpret_cast<const T*>(p.K) + ((size_t)pair * k + r0) * D;
+  const T* Vb = reinterpret_cast<const T*>(p.V) + ((size_t)pair * k + r0) * D;
   const T* knew = reinterpret_cast<const T*>(p.k_new) + (size_t)it * p.kv_stride + (size_t)pair * D;
   const T* vnew = reinterpret_cast<const T*>(p.v_new) + (size_t)it * p.kv_stride + (size_t)pair * D;
   const T* qb = reinterpret_cast<const T*>(p.q) + (size_t)it * p.q_stride +
                 ((size_t)unit * p.H + (size_t)kvh * G) * D;
-  int32_t* const evp = p.evicted ? p.evicted + (size_t)it * (p.pairs / p.H_kv) : nullptr;
-
-  float* e_lds = big;  // [nloc][G]: logits (log2 domain), then exp values
-  const float scale2 = p.scale * kLog2e;  // softmax is evaluated as 2^(l2 - max l2)
 
   // ---------------- phase 1: logits ----------------
   float m[G], Z[G];  // chunk-local softmax statistics (log2 domain)
@@ -648,7 +668,10 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
         float a = 0.f;
 #pragma unroll
         for (int g = 0; g < G; ++g) a = fmaf(e_lds[i * G + g], rz[g], a);
-        st_agent(sg + i, a);
+        if (UNIT)
+          s_lds[i] = (kv_i == 0) ? a : s_lds[i] + a;  // (entry i is always this thread's; heads in order)
+        else
+          st_agent(sg + i, a);
       }
     }
   } else {
@@ -817,6 +840,10 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
       E::store(outb + x, a / zg);
     }
   };
+  if constexpr (UNIT) {
+    store_out_single();
+    __syncthreads();  // the reduction area (and with it the exp values) is free for the next KV head
+  } else {
   if (S == 1) {
     if (!full) store_out_single();
   } else {
@@ -1021,6 +1048,74 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
     }
   }
 
+  }  // !UNIT
+  }  // KV heads of the item
+
+  if constexpr (UNIT) {
+    // ---------------- the block's own victim and state update (Sec. 4; App. B) ----------------
+    const T* kn = reinterpret_cast<const T*>(p.k_new) + (size_t)it * p.kv_stride + (size_t)pair0 * D;
+    const T* vn = reinterpret_cast<const T*>(p.v_new) + (size_t)it * p.kv_stride + (size_t)pair0 * D;
+    int slot = n;  // below capacity (App. B: num_kv <= cache_max_size) the new row takes slot n
+    if (full) {
+      // argmin of the head sums (the factor 1/H does not move it): a thread goes through its
+      // candidates in ascending order with a strict <, so the lowest index wins ties; candidates
+      // below n_pinned are kept out (TOVA+i, App. A)
+      float best = INFINITY;
+      int bj = 0x7fffffff;
+      for (int j = tid; j <= k; j += nt) {
+        const float sj = s_lds[j];
+        if (j >= p.n_pinned && sj < best) {
+          best = sj;
+          bj = j;
+        }
+      }
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) {
+        float ob = __shfl_xor(best, o);
+        int oj = __shfl_xor(bj, o);
+        if (ob < best || (ob == best && oj < bj)) {
+          best = ob;
+          bj = oj;
+        }
+      }
+      float* bv = small + 256;
+      int* bi = reinterpret_cast<int*>(small + 256 + kMaxWaves);
+      if (lane == 0) {
+        bv[wave] = best;
+        bi[wave] = bj;
+      }
+      __syncthreads();
+      best = bv[0];
+      bj = bi[0];
+      for (int w = 1; w < nw; ++w) {
+        float ob = bv[w];
+        int oj = bi[w];
+        if (ob < best || (ob == best && oj < bj)) {
+          best = ob;
+          bj = oj;
+        }
+      }
+      if (bj > k) bj = k;  // only reachable with non-finite scores
+      slot = bj;
+    }
+    if (slot < k) {  // (slot == k: the incoming token itself was dropped)
+      T* Ku = reinterpret_cast<T*>(p.K) + ((size_t)pair0 * k + slot) * D;
+      T* Vu = reinterpret_cast<T*>(p.V) + ((size_t)pair0 * k + slot) * D;
+      for (int x = tid; x < p.H_kv * ROW16; x += nt) {  // rows of consecutive KV heads are contiguous in k_new
+        const int h = x / ROW16, c = x - h * ROW16;
+        reinterpret_cast<V16*>(Ku + (size_t)h * k * D)[c] = reinterpret_cast<const V16*>(kn)[x];
+        reinterpret_cast<V16*>(Vu + (size_t)h * k * D)[c] = reinterpret_cast<const V16*>(vn)[x];
+      }
+    }
+    if (tid == 0) {
+      if (evp) evp[unit] = full ? slot : -1;
+      if (slot < k) p.slot_token[(size_t)unit * k + slot] = tok;
+      p.occupancy[unit] = full ? k : n + 1;
+    }
+    // the rows must have landed before other waves of this block read them in the unit's next step
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+  }
   if (MULTI) __syncthreads();  // LDS is free for the block's next pair
   }  // pairs of this block
   }  // passes
@@ -1028,30 +1123,33 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
 
 // Blocks of the step kernel that can be resident on the device at once.
 template <typename T, int D, int G>
-int resident_blocks_one(int block, int lds) {
+int resident_blocks_one(int block, int lds, int unit_mode) {
   int per_cu = 0, dev = 0, cus = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tova_step_kernel<T, D, G, true>, block, (size_t)lds) != hipSuccess)
+  const hipError_t e =
+      unit_mode ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tova_step_kernel<T, D, G, true, true>, block, (size_t)lds)
+                : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tova_step_kernel<T, D, G, true, false>, block, (size_t)lds);
+  if (e != hipSuccess)
     return 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
   return per_cu * cus;
 }
 template <typename T, int D>
-int resident_blocks_g(int G, int block, int lds) {
+int resident_blocks_g(int G, int block, int lds, int unit_mode) {
   switch (G) {
-    case 1: return resident_blocks_one<T, D, 1>(block, lds);
-    case 2: return resident_blocks_one<T, D, 2>(block, lds);
-    case 4: return resident_blocks_one<T, D, 4>(block, lds);
-    case 8: return resident_blocks_one<T, D, 8>(block, lds);
+    case 1: return resident_blocks_one<T, D, 1>(block, lds, unit_mode);
+    case 2: return resident_blocks_one<T, D, 2>(block, lds, unit_mode);
+    case 4: return resident_blocks_one<T, D, 4>(block, lds, unit_mode);
+    case 8: return resident_blocks_one<T, D, 8>(block, lds, unit_mode);
     default: return 0;
   }
 }
 template <typename T>
-int resident_blocks_d(int D, int G, int block, int lds) {
+int resident_blocks_d(int D, int G, int block, int lds, int unit_mode) {
   switch (D) {
-    case 32: return resident_blocks_g<T, 32>(G, block, lds);
-    case 64: return resident_blocks_g<T, 64>(G, block, lds);
-    case 128: return resident_blocks_g<T, 128>(G, block, lds);
+    case 32: return resident_blocks_g<T, 32>(G, block, lds, unit_mode);
+    case 64: return resident_blocks_g<T, 64>(G, block, lds, unit_mode);
+    case 128: return resident_blocks_g<T, 128>(G, block, lds, unit_mode);
     default: return 0;
   }
 }
@@ -1064,7 +1162,9 @@ __global__ void tova_fill_i32_kernel(int32_t* dst, int32_t value, size_t count) 
 
 template <typename T, int D, int G>
 hipError_t launch_one(const StepParams& p, const LaunchPlan& lp, hipStream_t stream) {
-  if (p.persistent)
+  if (p.unit_mode)
+    hipLaunchKernelGGL((tova_step_kernel<T, D, G, true, true>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes, stream, p);
+  else if (p.persistent)
     hipLaunchKernelGGL((tova_step_kernel<T, D, G, true>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes, stream, p);
   else
     hipLaunchKernelGGL((tova_step_kernel<T, D, G, false>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes, stream, p);
@@ -1099,9 +1199,16 @@ hipError_t launch_step(int dtype_is_bf16, int D, int G, const StepParams& p, con
   return dtype_is_bf16 ? launch_d<bf16_t>(D, G, p, lp, stream) : launch_d<float>(D, G, p, lp, stream);
 }
 
-int resident_blocks(int dtype_is_bf16, int D, int G, int block, int lds_bytes) {
-  return dtype_is_bf16 ? resident_blocks_d<bf16_t>(D, G, block, lds_bytes)
-                       : resident_blocks_d<float>(D, G, block, lds_bytes);
+int resident_blocks(int dtype_is_bf16, int D, int G, int block, int lds_bytes, int unit_mode) {
+  return dtype_is_bf16 ? resident_blocks_d<bf16_t>(D, G, block, lds_bytes, unit_mode)
+                       : resident_blocks_d<float>(D, G, block, lds_bytes, unit_mode);
+}
+
+int device_cus() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  return cus;
 }
 
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_t stream) {

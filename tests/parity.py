@@ -89,6 +89,7 @@ def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: 
         "V": cache.V.view(spec.L, Bv, Hkv_v, spec.k, spec.d)[ul, ub].float().cpu().numpy(),
         "layout": (cache.layout.n_splits, cache.layout.rows_per_split, cache.layout.block_threads,
                    cache.layout.grid_blocks),
+        "unit_workgroups": int(cache.layout.unit_workgroups),
         "tokens_seen": cache.tokens_seen,
         "prefill": prefill,
     }

@@ -51,8 +51,7 @@ SWEEP = [
     ("bf16", 64, 16, 8, 130, 300, 2, 2, 4),
     ("bf16", 32, 8, 2, 77, 200, 1, 5, 0),
     ("bf16", 128, 2, 1, 640, 900, 1, 9, 2),     # more units than one XCD round
-    ("bf16", 64, 8, 8, 48, 120, 8, 40, 1),      # 2560 (unit, KV head) pairs: more than fit on the device at
-                                                # once, so a multi-step launch walks several pairs per block
+    ("bf16", 64, 8, 8, 48, 120, 8, 40, 1),      # 320 units: a workgroup per unit (see the tests further down)
 ]
 
 
@@ -210,6 +209,100 @@ def test_split_finisher_handles_every_chunk(dtype, d, H, H_kv, k, T, L, B, split
         assert all(s["mismatches"] == 0 for s in stats)
 
 
+# ---- a workgroup per unit --------------------------------------------------------------------
+UNIT_SWEEP = [
+    # dtype, d, H, H_kv, k, T, L, B
+    ("f32", 32, 4, 4, 37, 150, 2, 3),
+    ("f32", 128, 8, 1, 257, 420, 1, 2),         # one wide group
+    ("f32", 128, 4, 2, 1, 40, 1, 1),            # capacity 1
+    ("bf16", 128, 32, 8, 300, 520, 1, 3),
+    ("bf16", 128, 8, 8, 1025, 1300, 1, 2),
+    ("bf16", 64, 16, 2, 130, 300, 2, 2),        # wide bf16 groups: matrix-core logit pass
+    ("bf16", 32, 8, 2, 77, 200, 1, 5),
+]
+
+
+@pytest.mark.parametrize("dtype,d,H,H_kv,k,T,L,B", UNIT_SWEEP)
+def test_unit_workgroups_shape_sweep(dtype, d, H, H_kv, k, T, L, B, monkeypatch):
+    """With many units a workgroup takes a whole unit and goes through its KV heads in turn (scores
+    and victim never leave the workgroup).  TOVA_UNIT_MODE=1 chooses that form for any number of
+    units, so that it can be checked on the same small shapes as the other one."""
+    monkeypatch.setenv("TOVA_UNIT_MODE", "1")
+    spec = StreamSpec(f"unit_{dtype}_d{d}_h{H}_{H_kv}_k{k}", L=L, B=B, H=H, H_kv=H_kv, d=d, dtype=dtype,
+                      k=k, T=T, sink="first", n_sinks=2)
+    units = [(l, b) for l in range(L) for b in range(B)][:4]
+    stats, res = _run(spec, seed=500 + k, units=units, n_splits=1, workers=4)   # (one chunk per KV head is a precondition)
+    assert res["unit_workgroups"] == 1
+    if dtype == "f32":
+        assert all(s["mismatches"] == 0 for s in stats)
+
+
+def test_unit_workgroups_are_the_default_for_many_units():
+    """256 units or more: chosen without being asked; several units per workgroup and step."""
+    spec = StreamSpec("unit_default", L=8, B=80, H=8, H_kv=4, d=64, dtype="bf16", k=40, T=130, sink="first",
+                      n_sinks=1)
+    units = [(0, 0), (3, 41), (7, 79)]
+    stats, res = _run(spec, seed=77, units=units, workers=3)
+    assert res["unit_workgroups"] == 1 and res["layout"][3] == spec.L * spec.B
+
+
+def test_many_pairs_walk_without_unit_workgroups(monkeypatch):
+    """The other form with more (unit, KV head) pairs than fit on the device at once: a multi-step
+    launch then walks several pairs per workgroup (TOVA_UNIT_MODE=0 keeps it from taking units)."""
+    monkeypatch.setenv("TOVA_UNIT_MODE", "0")
+    spec = StreamSpec("pairs_walk", L=8, B=40, H=8, H_kv=8, d=64, dtype="bf16", k=48, T=120, sink="first",
+                      n_sinks=2)
+    units = [(0, 0), (4, 13), (7, 39)]
+    stats, res = _run(spec, seed=148, units=units, n_splits=1, workers=3)
+    assert res["unit_workgroups"] == 0 and res["layout"][3] == spec.L * spec.B * spec.H_kv
+
+
+@pytest.mark.parametrize("variant", ["pinned", "per_head"])
+def test_unit_workgroups_variants(variant, monkeypatch):
+    """TOVA+i and TOVA-head (App. A) in the workgroup-per-unit form."""
+    monkeypatch.setenv("TOVA_UNIT_MODE", "1")
+    k, H, H_kv = 60, 8, 4
+    spec = StreamSpec(f"unit_{variant}", L=2, B=3, H=H, H_kv=H_kv, d=64, dtype="bf16", k=k, T=k + 200)
+    if variant == "pinned":
+        units = [(0, 0), (1, 2)]
+        res = parity.run_gpu(spec, 33, units, n_splits=1, n_pinned=3)
+        assert res["unit_workgroups"] == 1
+        parity.check_global_invariants(spec, res)
+        assert (res["slot_token"][:, :, :3] == torch.arange(3).numpy()).all()
+        assert (res["evicted"][k:] >= 3).all()
+        parity.check_units(spec, 33, units, res, workers=2, n_pinned=3)
+    else:
+        view = spec.replace(B=spec.B * H_kv, H=H // H_kv, H_kv=1)
+        units = [(0, 0), (0, H_kv - 1), (1, view.B - 1)]
+        res = parity.run_gpu(spec, 43, units, n_splits=1, per_head=True)
+        assert res["unit_workgroups"] == 1
+        parity.check_global_invariants(view, res)
+        parity.check_units(view, 43, units, res, workers=3)
+
+
+def test_unit_workgroups_multi_step_matches_per_step(monkeypatch):
+    """One launch for all full-occupancy steps against one launch per step, both in the
+    workgroup-per-unit form: bit-identical results."""
+    from paper_2401_06104_amd import TovaCache
+    from workloads import Stream
+    monkeypatch.setenv("TOVA_UNIT_MODE", "1")
+    spec = spec_for("c3_mistral_gqa", B=24, k=200, T=200 + 150)
+    outs = []
+    for mode in ("1", "0"):
+        monkeypatch.setenv("TOVA_MULTI_STEP", mode)
+        cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype, n_splits=1)
+        assert cache.layout.unit_workgroups == 1
+        c = Stream(spec, 13, device="cuda:0").chunk(0, spec.T)
+        out = torch.empty_like(c["q"])
+        ev = torch.empty(spec.T, spec.L, spec.B, dtype=torch.int32, device="cuda:0")
+        cache.decode_steps(c["q"], c["k"], c["v"], out, ev)
+        torch.cuda.synchronize()
+        outs.append((out.cpu(), ev.cpu(), cache.slot_token.cpu(), cache.occupancy.cpu(), cache.K.cpu(), cache.V.cpu()))
+        cache.destroy()
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
 # ---- multi-step launches --------------------------------------------------------------------
 def test_multi_step_launch_matches_per_step_launches(monkeypatch):
     """tova_decode_steps runs all full-occupancy steps of a call in one launch when it can; the
@@ -242,6 +335,7 @@ def test_multi_step_wait_runs_out_cleanly(monkeypatch):
     from workloads import Stream
     monkeypatch.setenv("TOVA_MULTI_STEP", "1")
     monkeypatch.setenv("TOVA_MULTI_STEP_SPIN", "0")
+    monkeypatch.setenv("TOVA_UNIT_MODE", "0")        # (a workgroup per unit never waits)
     spec = spec_for("c3_mistral_gqa", B=16, k=128, T=128 + 40)
     cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype, n_splits=1)
     c = Stream(spec, 12, device="cuda:0").chunk(0, spec.T)

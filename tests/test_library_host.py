@@ -90,7 +90,11 @@ def test_launch_plan(c, expect_S):
     R, S, k = lay.rows_per_split, lay.n_splits, c.capacity_k
     assert R * S >= k and R * (S - 1) < k                   # chunks cover the slots, none is dead
     pairs = c.n_layers * c.batch * c.n_kv_heads
-    assert lay.grid_blocks == (pairs + 7) // 8 * 8 * S
+    units = c.n_layers * c.batch
+    if S == 1 and units >= 256:      # a workgroup per unit once the units alone fill the device
+        assert lay.unit_workgroups == 1 and lay.grid_blocks == units
+    else:
+        assert lay.unit_workgroups == 0 and lay.grid_blocks == (pairs + 7) // 8 * 8 * S
     assert lay.block_threads in (256, 512)
     G = c.n_q_heads // c.n_kv_heads
     assert lay.lds_bytes >= 4 * (R + 1) * G and lay.lds_bytes <= 64 * 1024
