@@ -122,20 +122,26 @@ int tova_decode_step(tova_cache_t* cache, const void* q, const void* k_new, cons
 /* n_steps consecutive decode steps with inputs resident in device memory:
  * the arrays of tova_decode_step with a leading [n_steps] dimension
  * (evicted: [n_steps][L][B], may be NULL).  Same results as n_steps calls.
- * Once the cache is full, and if every workgroup of a step fits on the device at the same time
- * with one chunk per KV head, the remaining steps run in ONE launch: each workgroup stays with
- * its (sequence, KV head) for all steps, so sequences advance independently of one another and
- * the only wait in the kernel is a workgroup's wait for the victim of its own sequence's current
- * step.  That wait is bounded; should it ever run out, the kernel sets the int32 at
- * error_flag_offset of state_mem and stops early (check it after synchronising the stream when
- * results matter; tova_cache_init clears it).  The environment variable TOVA_MULTI_STEP=0 keeps
- * one launch per step. */
+ * Once the cache is full the remaining steps of a call run in ONE launch.
+ *  - With L * B >= 256 units and one chunk per KV head (layout: unit_workgroups != 0) a workgroup
+ *    owns whole units: it goes through a unit's KV heads in turn, keeps the head-summed scores in
+ *    on-chip memory, picks the victim and stores the new rows itself.  Workgroups never wait for
+ *    one another; any number of them may run.
+ *  - Otherwise a workgroup stays with its (sequence, KV head[, chunk]) items for all steps;
+ *    sequences advance independently of one another and the only wait in the kernel is a
+ *    workgroup's wait for the victim of its own sequence's previous step.  That wait is bounded;
+ *    should it ever run out, the kernel sets the int32 at error_flag_offset of state_mem and
+ *    stops early (check it after synchronising the stream when results matter; tova_cache_init
+ *    clears it).
+ * The environment variable TOVA_MULTI_STEP=0 keeps one launch per step; TOVA_UNIT_MODE=0 / 1
+ * (read by tova_cache_init / tova_cache_layout) overrides the choice between the two forms. */
 int tova_decode_steps(tova_cache_t* cache, int32_t n_steps, const void* q, const void* k_new,
                       const void* v_new, void* out, int32_t* evicted, void* hip_stream);
 
 /* How tova_decode_steps launches once the cache is full (decided in tova_cache_init, which asks
  * the device how many workgroups fit): *blocks = 0 -> one launch per step; otherwise the number
- * of workgroups of the single launch that runs all remaining steps of a call.  HOST out pointer. */
+ * of workgroups of the single launch that runs all remaining steps of a call (with
+ * unit_workgroups: of every launch).  HOST out pointer. */
 int tova_cache_multi_step_blocks(const tova_cache_t* cache, int32_t* blocks);
 
 /* Number of tokens the cache has seen since tova_cache_init (HOST out pointer). */

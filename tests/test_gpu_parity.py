@@ -148,8 +148,8 @@ def test_c3_mistral_gqa_full():
 
 
 def test_c4_llama7b_stack_full_shape():
-    """Config 4 at its real shape (32 layers x 64 sequences, k=4096: 128 GiB of cache, 65,536
-    workgroups per step).  The 4096 fill steps are replaced by laying the first 4096 tokens down
+    """Config 4 at its real shape (32 layers x 64 sequences, k=4096: 128 GiB of cache, 2,048 units
+    of 32 KV heads each, a workgroup per unit).  The 4096 fill steps are replaced by laying the first 4096 tokens down
     directly (what the no-op branch produces); then 48 decode steps at full occupancy.  Three
     sampled units are followed by the oracle; all 2048 units are checked for consistency."""
     free, _ = torch.cuda.mem_get_info()
@@ -162,7 +162,7 @@ def test_c4_llama7b_stack_full_shape():
     parity.check_global_invariants(spec, res)
     for s in parity.check_units(spec, 4, units, res, workers=3):
         print(f"[parity]   {s}", flush=True)
-    assert res["layout"][0] == 1 and res["layout"][3] == 65536
+    assert res["layout"][0] == 1 and res["unit_workgroups"] == 1 and res["layout"][3] == 2048
 
 
 def test_c5_yi_long_full_stream():
