@@ -30,7 +30,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # Bytes that left L2 per decode step of the step kernel on this workload, from rocprofv3 --pmc FETCH_SIZE
 # and WRITE_SIZE runs of this script (512 steps per launch), each scaled by what the same counter reads
 # for a 1 GiB copy kernel (summary: profiles/tova_step_kernel_c3_mistral_gqa.txt).  Not measured live.
-PROFILED_TRAFFIC_BYTES_PER_STEP = 274.4e6
+PROFILED_TRAFFIC_BYTES_PER_STEP = 274.6e6
+# ... and of the 32-layer variant (workgroup-per-unit form), profiles/tova_step_kernel_unit_c3_mistral_gqa_x32.txt
+PROFILED_TRAFFIC_BYTES_PER_STEP_X32 = 8648.8e6
 
 
 def algorithmic_bytes_per_step(spec) -> int:
@@ -108,7 +110,7 @@ def gpu_leg(spec, seed, steps, warmup, device, chunk=256, prefill=False):
     lay = cache.layout
     multi = cache.multi_step_blocks
     plan = dict(multi_step_blocks=multi, n_splits=lay.n_splits, rows_per_split=lay.rows_per_split, block_threads=lay.block_threads,
-                grid_blocks=lay.grid_blocks, lds_bytes=lay.lds_bytes)
+                grid_blocks=lay.grid_blocks, lds_bytes=lay.lds_bytes, unit_workgroups=int(lay.unit_workgroups))
     cache.destroy()
     return dict(wall_s=wall, event_ms=ev_ms, plan=plan, sane=ok,
                 new_token_dropped_frac=float((ev_host == spec.k).float().mean()))
@@ -203,9 +205,11 @@ def main():
                    "sequence_steps_per_s": 1e3 / ms_per_step * spec.L * spec.B},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": PROFILED_TRAFFIC_BYTES_PER_STEP * steps_per_launch if spec.L == 1 else None,
-                     "kernel": "tova_step_kernel<bf16, d=128, G=4, multi-step>" if steps_per_launch > 1
-                               else "tova_step_kernel<bf16, d=128, G=4, per-step>",
+                     "traffic": (PROFILED_TRAFFIC_BYTES_PER_STEP * steps_per_launch if spec.L == 1 else
+                                 PROFILED_TRAFFIC_BYTES_PER_STEP_X32 * steps_per_launch if spec.L == 32 else None),
+                     "kernel": "tova_step_kernel<bf16, d=128, G=4, " +
+                               ("workgroup per unit, " if g["plan"]["unit_workgroups"] else "") +
+                               ("multi-step>" if steps_per_launch > 1 else "per-step>"),
                      "steps_per_launch": steps_per_launch, "algorithmic_bytes_per_step": abytes,
                      "algorithmic_bytes_per_launch": abytes * steps_per_launch,
                      "avg_launch_us": ms_per_step * 1e3 * steps_per_launch},
@@ -219,7 +223,7 @@ def main():
         g32 = gpu_leg(s32, args.seed, 192, 8, "cuda:0", chunk=32)
         ms32 = g32["event_ms"] / 192
         ab32 = algorithmic_bytes_per_step(s32)
-        result["hbm_resident_variant"] = {"workload": "same layer shape x 32 layers (8 GiB cache)", "steps": 192,
+        result["hbm_resident_variant"] = {"workload": "same layer shape x 32 layers (8 GiB cache; 2048 units, a workgroup per unit)", "steps": 192,
                                           "ms_per_step": ms32, "achieved_GBps": ab32 / (ms32 * 1e-3) / 1e9,
                                           "frac": ab32 / (ms32 * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                           "sequence_steps_per_s": 1e3 / ms32 * 32 * 64, "sane": g32["sane"]}
