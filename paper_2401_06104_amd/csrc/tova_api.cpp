@@ -19,7 +19,8 @@ constexpr int kUnitModeUnits = 256;    // from one unit per CU on, a workgroup t
 constexpr size_t kMinBytesPerSplit = 256 * 1024;  // K+V bytes of a chunk below which splitting only adds
                                                   // hand-offs (each costs ~1 us of memory round trip)
 constexpr int kSmallFloats = 512;      // must match the kernel's fixed LDS area
-constexpr int kMaxLdsBytes = 64 * 1024;
+constexpr int kMaxLdsBytes = 64 * 1024;       // per workgroup when several share a CU
+constexpr int kMaxLdsBytesUnit = 152 * 1024;  // a workgroup per unit may have a CU's LDS (160 KB) to itself
 
 thread_local char g_hip_msg[256] = {0};
 
@@ -71,8 +72,43 @@ int resolve(const tova_config_t* c, Resolved* r) {
   }
   r->scale = c->softmax_scale > 0.f ? c->softmax_scale : (float)(1.0 / std::sqrt((double)r->D));
 
-  // ---- split count: enough workgroups to fill 256 CUs, chunks that fit LDS ----
   const int k = r->k;
+  int nt_env = 0;
+  if (const char* e = std::getenv("TOVA_BLOCK_THREADS")) {  // tuning aid: 64..512, multiple of 64
+    int v = std::atoi(e);
+    if (v >= 64 && v <= 512 && v % 64 == 0) nt_env = v;
+  }
+
+  // ---- a workgroup per unit ----
+  // With at least one unit per CU a workgroup takes a whole unit and goes through its KV heads one
+  // after the other: the head-summed scores stay in LDS (a [k + 1] row behind the big area) and no
+  // workgroup ever needs another one's results.  It needs one chunk per KV head, i.e. LDS for the
+  // logits of all k + 1 candidates of a KV head's G query heads; for that it may take most of a
+  // CU's LDS (one workgroup per CU is enough to stream at full rate in this form).
+  r->unit_mode = 0;
+  {
+    int want = (r->units >= kUnitModeUnits);
+    if (const char* e = std::getenv("TOVA_UNIT_MODE")) want = (std::atoi(e) != 0);  // tuning aid / test hook
+    if (want && c->n_splits <= 1) {
+      const long long e_fl = ((long long)(k + 1) * G + 3) / 4 * 4;
+      const long long s_fl = ((long long)k + 1 + 3) / 4 * 4;
+      int nt = nt_env ? nt_env : ((k >= 512 && G < 8) ? 512 : 256);
+      long long red_fl = (long long)(nt / 64) * G * r->D;
+      long long st = e_fl > red_fl ? e_fl : red_fl;
+      if ((kSmallFloats + st + s_fl) * 4 > kMaxLdsBytes && !nt_env) {  // alone on its CU: all the threads a block may have
+        nt = 512;
+        red_fl = (long long)(nt / 64) * G * r->D;
+        st = e_fl > red_fl ? e_fl : red_fl;
+      }
+      if ((kSmallFloats + st + s_fl) * 4 <= kMaxLdsBytesUnit) {
+        r->unit_mode = 1;
+        r->S = 1; r->R = k; r->NT = nt; r->st_off = (int)st;
+        r->lds = (int)((kSmallFloats + st + s_fl) * 4);
+      }
+    }
+  }
+
+  // ---- split count: enough workgroups to fill 256 CUs, chunks that fit LDS ----
   int S = c->n_splits;
   if (S <= 0) {
     int target = kTargetBlocks;
@@ -87,18 +123,13 @@ int resolve(const tova_config_t* c, Resolved* r) {
     if (S > smax) S = smax;
   }
   if (S > k) S = k;
-  int nt_env = 0;
-  if (const char* e = std::getenv("TOVA_BLOCK_THREADS")) {  // tuning aid: 64..512, multiple of 64
-    int v = std::atoi(e);
-    if (v >= 64 && v <= 512 && v % 64 == 0) nt_env = v;
-  }
   const int big_cap = kMaxLdsBytes / 4 - kSmallFloats;  // floats available for the big LDS area
   // LDS: logits / exp values of R slots + the new token; the cross-wave reduction area reuses that
   // memory after the PV pass; with several chunks per KV head a small area behind both holds all
   // chunks' softmax statistics and the finisher's merge weights.
-  int R = (k + S - 1) / S, NT;
-  long long big, st_off;
-  for (;;) {
+  int R = (k + S - 1) / S, NT = 0;
+  long long big = 0, st_off = 0;
+  for (; !r->unit_mode;) {
     S = (k + R - 1) / R;  // no dead chunks
     const long long e_fl = ((long long)(R + 1) * G + 3) / 4 * 4;
     bool ok = false;
@@ -116,22 +147,12 @@ int resolve(const tova_config_t* c, Resolved* r) {
     if (R == 1) return TOVA_ENOSUP;
     R -= (R >= 8) ? R / 8 : 1;  // smaller chunks until the chunk fits
   }
-  r->S = S; r->R = R; r->NT = NT; r->st_off = (int)st_off;
+  if (!r->unit_mode) {
+    r->S = S; r->R = R; r->NT = NT; r->st_off = (int)st_off;
+    r->lds = (int)((kSmallFloats + big) * 4);
+  }
+  S = r->S;
   r->kp = (int)round_up((size_t)k + 1, 64);
-  // With at least as many units as workgroups that fill the device, a workgroup takes a whole unit
-  // and goes through its KV heads one after the other: the head-summed scores stay in LDS (a
-  // [k + 1] row behind the big area) and no workgroup ever needs another one's results.
-  r->unit_mode = (S == 1 && r->units >= kUnitModeUnits);
-  if (const char* e = std::getenv("TOVA_UNIT_MODE")) {  // tuning aid / test hook: 0 = never, 1 = whenever possible
-    const int v = std::atoi(e);
-    r->unit_mode = (v != 0) && S == 1;
-  }
-  if (r->unit_mode) {
-    const long long s_fl = ((long long)k + 1 + 3) / 4 * 4;
-    if (big + s_fl <= big_cap) big += s_fl;
-    else r->unit_mode = 0;
-  }
-  r->lds = (int)((kSmallFloats + big) * 4);
   r->grid = r->unit_mode ? r->units : (r->pairs + 7) / 8 * 8 * S;
   // A chunk looks this many more times (about a microsecond apart) for its siblings' statistics
   // before it leaves its score rows to the pair's finisher.  Only worth it when all workgroups of

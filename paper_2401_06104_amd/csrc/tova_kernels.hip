@@ -1162,8 +1162,14 @@ __global__ void tova_fill_i32_kernel(int32_t* dst, int32_t value, size_t count) 
 
 template <typename T, int D, int G>
 hipError_t launch_one(const StepParams& p, const LaunchPlan& lp, hipStream_t stream) {
-  if (p.unit_mode)
+  if (p.unit_mode) {
+    if (lp.lds_bytes > 64 * 1024) {  // more dynamic LDS than the default limit: say so (a workgroup per CU)
+      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tova_step_kernel<T, D, G, true, true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, lp.lds_bytes);
+      if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL((tova_step_kernel<T, D, G, true, true>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes, stream, p);
+  }
   else if (p.persistent)
     hipLaunchKernelGGL((tova_step_kernel<T, D, G, true>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes, stream, p);
   else

@@ -237,6 +237,20 @@ def test_unit_workgroups_shape_sweep(dtype, d, H, H_kv, k, T, L, B, monkeypatch)
         assert all(s["mismatches"] == 0 for s in stats)
 
 
+def test_unit_workgroups_wide_groups_large_capacity(monkeypatch):
+    """Config 5's shape per unit (8 query heads per KV head, k=4096) with a workgroup per unit: the
+    logits of a KV head's 8 x 4097 candidates need 131 KB of LDS, so a workgroup takes a CU's LDS to
+    itself.  The first 4096 tokens are laid down directly; 60 evicting steps follow."""
+    monkeypatch.setenv("TOVA_UNIT_MODE", "1")
+    spec = spec_for("c5_yi_long", L=3, T=4096 + 60)
+    units = [(0, 0), (2, 0)]
+    res = parity.run_gpu(spec, 55, units, chunk_steps=32, prefill=True)
+    assert res["unit_workgroups"] == 1 and res["layout"][0] == 1
+    parity.check_global_invariants(spec, res)
+    for s in parity.check_units(spec, 55, units, res, workers=2):
+        print(f"[parity]   {s}", flush=True)
+
+
 def test_unit_workgroups_are_the_default_for_many_units():
     """256 units or more: chosen without being asked; several units per workgroup and step."""
     spec = StreamSpec("unit_default", L=8, B=80, H=8, H_kv=4, d=64, dtype="bf16", k=40, T=130, sink="first",
