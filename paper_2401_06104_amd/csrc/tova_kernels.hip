@@ -4,34 +4,35 @@
 // (Sec. 3.2: append the new row, attend; Sec. 4 / App. B Alg. 1: average the
 // attention weights over heads, argmin, drop that row).
 //
-// Work decomposition.  A workgroup owns one (unit, KV head, slot chunk): it
-// streams its chunk of K once and its chunk of V once, 16 bytes per lane,
-// rows laid across LPR = d / (16 / sizeof(elem)) adjacent lanes so that every
-// wave-level load covers whole, contiguous rows.  The G = H / H_kv query
-// heads that share the KV head are all served from the same streamed row
-// (grouped-query attention reads K/V once, not G times).
+// Work decomposition.  Two forms, chosen by the host:
+//  * a workgroup per (unit, KV head, slot chunk): it streams its chunk of K once and its chunk of
+//    V once; the head-group partials of the score vector and (with several chunks) the chunks'
+//    softmax statistics and PV partials are handed between workgroups through device memory;
+//  * a workgroup per unit (many units): it goes through the unit's KV heads in turn and keeps the
+//    head-summed scores in LDS, so nothing is handed to anybody.
+// In both, rows are read 16 bytes per lane and laid across adjacent lanes so that every wave-level
+// load covers whole, contiguous rows, and the G = H / H_kv query heads that share a KV head are
+// all served from the same streamed row (grouped-query attention reads K/V once, not G times).
 //
-//   phase 1  logits   l[i][g] = scale * q_g . K[i]      -> LDS
-//   phase 2  softmax  m_g, e[i][g] = exp(l - m_g), Z_g  (chunk-local)
+//   phase 1  logits   l[i][g] = scale * q_g . K[i]      -> LDS   (vector ALU; matrix cores for
+//                                                                 bf16 groups of 8 heads and more)
+//   phase 2  softmax  m_g, e[i][g] = exp(l - m_g), Z_g  (chunk-local), score contributions
 //   phase 3  PV       acc_g = sum_i e[i][g] * V[i]
-//   phase 4  combine  (a) per (unit, KV head): merge the chunks' (m, Z, acc)
-//                         -> out; head-group partial of the score vector
-//                     (b) per unit: sum the partials over KV heads in fixed
-//                         order, argmin with lowest-index tie break, overwrite
-//                         the victim's slot with the new row, log `evicted`.
-//            Both levels use the "last workgroup to arrive does the merge"
-//            pattern: results are written to scratch with agent-scope
-//            (write-through) stores and an atomic counter elects the finisher.
-//            Nothing ever waits on another workgroup, so every wave reaches
-//            its exit whatever the scheduling order.
+//   phase 4  combine  (a) per (unit, KV head): merge the chunks' (m, Z, acc) -> out
+//                     (b) per unit: sum the score partials over KV heads in fixed order, argmin
+//                         with lowest-index tie break, put the new row into the victim's slot,
+//                         log `evicted`.
 //
-// The score needs every head's *global* softmax normaliser, so when the slots
-// of a KV head are split over several workgroups the chunk-local e values go
-// to scratch (fp32, G per candidate) and are rescaled by the finisher.
-// With a single chunk (S == 1) they never leave LDS.
+// Hand-offs between workgroups use "the last one to arrive does the merge": results are written
+// with agent-scope (write-through) stores, an atomic counter elects the finisher, the finisher
+// reads with agent-scope (cache-bypassing) loads.  Per-step launches never wait for another
+// workgroup.  The bounded exceptions: a chunk looks a limited number of times for its siblings'
+// softmax statistics (and leaves its score rows to the finisher if they are not there), and in a
+// multi-step launch a workgroup waits, with a limit and an error flag, for the victim of its own
+// unit's previous step.  Every wave reaches its exit whatever the scheduling order.
 //
-// The path is bound by HBM bandwidth (2*k*d*sizeof(elem) bytes per KV head
-// and step against 4*G*k*d flops): no matrix cores are used.
+// The path is bound by HBM bandwidth (2*k*d*sizeof(elem) bytes per KV head and step against
+// 4*G*k*d flops).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 

@@ -237,6 +237,25 @@ def test_unit_workgroups_shape_sweep(dtype, d, H, H_kv, k, T, L, B, monkeypatch)
         assert all(s["mismatches"] == 0 for s in stats)
 
 
+def test_unit_workgroups_single_step_entry_point(monkeypatch):
+    """tova_decode_step (one launch per token) in the workgroup-per-unit form, victims not logged
+    for part of the stream (evicted = NULL is allowed)."""
+    from paper_2401_06104_amd import TovaCache
+    from workloads import Stream
+    monkeypatch.setenv("TOVA_UNIT_MODE", "1")
+    spec = StreamSpec("unit_single", L=2, B=2, H=4, H_kv=2, d=32, dtype="f32", k=19, T=90, sink="first", n_sinks=1)
+    stats, res = _run(spec, seed=61, units=[(0, 0), (1, 1)], n_splits=1, single_step_calls=True, workers=2)
+    assert res["unit_workgroups"] == 1 and all(s["mismatches"] == 0 for s in stats)
+    # the same stream with evicted = NULL: same cache contents at the end
+    cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype="f32", n_splits=1)
+    c = Stream(spec, 61, device="cuda:0").chunk(0, spec.T)
+    out = torch.empty_like(c["q"])
+    cache.decode_steps(c["q"], c["k"], c["v"], out, None)
+    torch.cuda.synchronize()
+    assert (cache.slot_token.cpu().numpy() == res["slot_token"]).all()
+    cache.destroy()
+
+
 def test_unit_workgroups_wide_groups_large_capacity(monkeypatch):
     """Config 5's shape per unit (8 query heads per KV head, k=4096) with a workgroup per unit: the
     logits of a KV head's 8 x 4097 candidates need 131 KB of LDS, so a workgroup takes a CU's LDS to
