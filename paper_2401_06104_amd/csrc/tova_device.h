@@ -1,0 +1,296 @@
+// Device-side helpers shared by the kernels of this library (included by the .hip files only):
+// element types, cross-lane reductions, block reductions, cross-workgroup hand-off primitives and
+// the row geometry of the streaming passes.  Everything lives in an unnamed namespace inside
+// tova: each translation unit gets its own copy.
+#ifndef TOVA_DEVICE_H
+#define TOVA_DEVICE_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tova {
+namespace {
+
+// ---------------------------------------------------------------- elements
+struct alignas(16) V16 {
+  uint32_t w[4];
+};
+
+struct bf16_t {
+  uint16_t x;
+};
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <typename T>
+struct Elem;
+
+template <>
+struct Elem<float> {
+  static constexpr int VEC = 4;
+  static __device__ __forceinline__ void unpack(const V16& p, float (&f)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(p.w[i]);
+  }
+  // acc + sum of the 4 products of two 16-byte chunks
+  static __device__ __forceinline__ float dot(const V16& a, const V16& b, float acc) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc = fmaf(__uint_as_float(a.w[i]), __uint_as_float(b.w[i]), acc);
+    return acc;
+  }
+  static __device__ __forceinline__ void store(float* dst, float v) { *dst = v; }
+};
+
+template <>
+struct Elem<bf16_t> {
+  static constexpr int VEC = 8;
+  static __device__ __forceinline__ void unpack(const V16& p, float (&f)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(p.w[i] << 16);
+      f[2 * i + 1] = __uint_as_float(p.w[i] & 0xffff0000u);
+    }
+  }
+  // acc + sum of the 8 products of two 16-byte chunks: v_dot2_f32_bf16 takes the packed
+  // pairs as they are (bf16 products are exact in fp32, the accumulation is fp32)
+  static __device__ __forceinline__ float dot(const V16& a, const V16& b, float acc) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w[i]),
+                                            __builtin_bit_cast(bf16x2_t, b.w[i]), acc, false);
+    return acc;
+  }
+  // round to nearest even, NaN kept quiet
+  static __device__ __forceinline__ void store(bf16_t* dst, float v) {
+    uint32_t u = __float_as_uint(v);
+    uint16_t r;
+    if ((u & 0x7fffffffu) > 0x7f800000u) {
+      r = 0x7fc0;
+    } else {
+      u += 0x7fffu + ((u >> 16) & 1u);
+      r = (uint16_t)(u >> 16);
+    }
+    dst->x = r;
+  }
+};
+
+// ------------------------------------------------------- cross-lane helpers
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+
+// Lane l <-> lane l ^ 16 and l ^ 32 exchanges without the LDS crossbar.  The gfx950 permlane
+// swaps exchange, between two registers a and b, the odd rows of 16 lanes of a with the even
+// rows of b (a' = [a0 b0 a2 b2], b' = [a1 b1 a3 b3]), resp. the upper half of a with the lower
+// half of b; swapping a value with a copy of itself therefore leaves both partners of every
+// lane in a' and b'.  Written as inline asm with both registers as in/out operands: the
+// two-result builtin form returned its first result twice with the ROCm 7.2 compiler.  The
+// s_nop pads cover the VALU -> permlane read/write wait states the compiler cannot see.
+__device__ __forceinline__ void swap_rows16(unsigned& a, unsigned& b) {
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ void swap_rows32(unsigned& a, unsigned& b) {
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+template <bool IS_MAX>
+__device__ __forceinline__ float combine(float a, float b) {
+  return IS_MAX ? fmaxf(a, b) : a + b;
+}
+template <bool IS_MAX>
+__device__ __forceinline__ float fold_rows16(float x) {  // x[l] op x[l ^ 16]
+  unsigned a = __builtin_bit_cast(unsigned, x), b = a;
+  swap_rows16(a, b);
+  return combine<IS_MAX>(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
+}
+template <bool IS_MAX>
+__device__ __forceinline__ float fold_rows32(float x) {  // x[l] op x[l ^ 32]
+  unsigned a = __builtin_bit_cast(unsigned, x), b = a;
+  swap_rows32(a, b);
+  return combine<IS_MAX>(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
+}
+
+// Reduction over each group of LPR adjacent lanes whose lanes hold partials of the SAME
+// quantity; every lane of the group gets the total.  quad_perm[1,0,3,2], quad_perm[2,3,0,1],
+// row_half_mirror, row_mirror (the mirrors are valid because after the first two steps all
+// lanes of a quad agree), then the row swaps.
+template <int LPR, bool IS_MAX = false>
+__device__ __forceinline__ float group_reduce(float x) {
+  if (LPR >= 2) x = combine<IS_MAX>(x, dpp_mov<0xB1>(x));
+  if (LPR >= 4) x = combine<IS_MAX>(x, dpp_mov<0x4E>(x));
+  if (LPR >= 8) x = combine<IS_MAX>(x, dpp_mov<0x141>(x));
+  if (LPR >= 16) x = combine<IS_MAX>(x, dpp_mov<0x140>(x));
+  if (LPR >= 32) x = fold_rows16<IS_MAX>(x);
+  if (LPR >= 64) x = fold_rows32<IS_MAX>(x);
+  return x;
+}
+template <int LPR>
+__device__ __forceinline__ float group_sum(float x) {
+  return group_reduce<LPR, false>(x);
+}
+
+// Sum over the 64 / LV lanes that hold the same column chunk (lanes l, l + LV, l + 2 LV, ...),
+// for lanes that hold DIFFERENT columns: row rotations inside a row of 16, then the row swaps.
+template <int LV>
+__device__ __forceinline__ float column_sum(float x) {
+  if (LV <= 8) x += dpp_mov<0x128>(x);   // row_ror:8
+  if (LV <= 4) x += dpp_mov<0x124>(x);   // row_ror:4
+  if (LV <= 16) x = fold_rows16<false>(x);
+  if (LV <= 32) x = fold_rows32<false>(x);
+  return x;
+}
+
+// Small fixed LDS area in front of the big dynamic one (floats).
+constexpr int kSmallFloats = 512;
+constexpr int kMaxWaves = 16;
+
+// Block-wide max / sum of G per-thread values with ONE barrier: every wave reduces its lanes
+// (DPP + row swaps), lane 0 posts the wave's result, and after the barrier every thread
+// combines the nw posted values in wave order (so the result does not depend on timing).
+// `red` holds kMaxWaves * G floats and must not be in use by a previous reduction.
+template <int G, bool IS_MAX>
+__device__ __forceinline__ void block_reduce(float (&v)[G], float* red, int lane, int wave, int nw) {
+#pragma unroll
+  for (int g = 0; g < G; ++g) v[g] = group_reduce<64, IS_MAX>(v[g]);
+  if (lane == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) red[wave * G + g] = v[g];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float a = red[g];
+    for (int w = 1; w < nw; ++w) a = combine<IS_MAX>(a, red[w * G + g]);
+    v[g] = a;
+  }
+}
+
+// Cross-workgroup hand-off.  A full agent-scope release fence writes back the whole L2 of
+// the XCD and an acquire fence invalidates it; issued by every wave of every workgroup that
+// costs far more than the step's entire K/V stream.  Instead, everything one workgroup hands
+// to another is written with agent-scope (write-through) stores and read with agent-scope
+// (cache-bypassing) loads, so no cache maintenance is needed at all: the producer only has
+// to wait until its stores have completed before it bumps the arrival counter.
+__device__ __forceinline__ void st_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent_i(int32_t* p, int32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int32_t ld_agent_i(const int32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent_u64(unsigned long long* p, unsigned long long v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long ld_agent_u64(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_agent2(const float* p) {  // p is 8-byte aligned
+  unsigned long long r = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((uint32_t)r), __uint_as_float((uint32_t)(r >> 32)));
+}
+
+// Arrival on a counter.  All threads of the block call it after writing their results with
+// st_agent; it adds `add` to the counter once the block's stores have completed and returns the
+// counter's previous value to every thread.  The caller decides from that value whether it is
+// the last one, in which case it may read what the others wrote (ld_agent) and must reset the
+// counter (reset_counter) for the next step.  Nobody waits for anybody.
+__device__ __forceinline__ int arrive(int32_t* counter, int add, int* flag_lds, int tid) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // keep the stores above this point
+  __builtin_amdgcn_s_waitcnt(0);                          // ... and wait until they have completed
+  __syncthreads();
+  if (tid == 0)
+    flag_lds[1] = __hip_atomic_fetch_add(counter, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  return flag_lds[1];
+}
+__device__ __forceinline__ void reset_counter(int32_t* counter, int tid) {
+  if (tid == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Unit finisher: per-thread argmin over the head-summed scores of the k+1 candidates.
+// sgu[h * kp + j] is KV head h's partial for candidate j.  A thread owns candidate pairs
+// (2m, 2m+1), m = tid + i * nt, sums the H_kv partials in head order and keeps the lowest
+// (ascending j, strict <, so the lowest index wins ties; candidates below n_pinned are kept out:
+// TOVA+i, App. A).  The loads bypass the caches, so
+// JB * HB of them are issued before the first is used.
+template <int JB, int HB>
+__device__ __forceinline__ void scan_scores(const float* sgu, int H_kv, int kp, int k, int n_pinned, int tid,
+                                            int nt, float& best, int& bj) {
+  const int npair2 = (k + 2) / 2;  // candidate pairs covering 0..k
+  for (int m0 = tid; m0 < npair2; m0 += nt * JB) {
+    float s0[JB], s1[JB];
+#pragma unroll
+    for (int b = 0; b < JB; ++b) s0[b] = s1[b] = 0.f;
+    for (int h0 = 0; h0 < H_kv; h0 += HB) {
+      float2 raw[JB][HB];
+#pragma unroll
+      for (int b = 0; b < JB; ++b) {
+        const int mm = m0 + b * nt;
+#pragma unroll
+        for (int u = 0; u < HB; ++u) {
+          raw[b][u] = make_float2(0.f, 0.f);
+          if (mm < npair2 && h0 + u < H_kv) raw[b][u] = ld_agent2(sgu + (size_t)(h0 + u) * kp + 2 * mm);
+        }
+      }
+#pragma unroll
+      for (int b = 0; b < JB; ++b)
+#pragma unroll
+        for (int u = 0; u < HB; ++u) {
+          s0[b] += raw[b][u].x;
+          s1[b] += raw[b][u].y;
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < JB; ++b) {
+      const int j0 = 2 * (m0 + b * nt);
+      if (j0 >= n_pinned && j0 <= k && s0[b] < best) {
+        best = s0[b];
+        bj = j0;
+      }
+      if (j0 + 1 >= n_pinned && j0 + 1 <= k && s1[b] < best) {
+        best = s1[b];
+        bj = j0 + 1;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ kernel
+// Row geometry.  A row of d elements is CH = d / VEC 16-byte chunks.
+//  * logit pass: LK = CH / CK adjacent lanes share a row, each holding CK chunks
+//    (chunk c * LK + lane), so a wave-level load still covers whole contiguous
+//    rows while the cross-lane sum per (row, head) needs only log2(LK) DPP steps;
+//  * PV pass: one chunk per lane (LV = CH lanes per row), no cross-lane work in
+//    the loop, G * VEC accumulators per lane.
+template <typename T, int D, int G>
+struct Geo {
+  static constexpr int VEC = Elem<T>::VEC;
+  static constexpr int CH = D / VEC;
+  static constexpr int CK = (CH >= 8) ? 2 : 1;
+  static constexpr int LK = CH / CK;
+  static constexpr int RK = 64 / LK;  // rows per wave pass, logit pass
+  static constexpr int UK = (G >= 8) ? 1 : 2;  // passes per register buffer (two buffers in flight);
+                                               // fewer for wide groups, whose q fragments fill the registers
+  // Wide bf16 groups run the logit pass on the matrix cores (see the kernel): q.K^T for 16 rows x
+  // up to 16 heads per v_mfma_f32_16x16x32_bf16, which takes the register file and the VALU out
+  // of the picture (8 heads of q fragments alone are 64 VGPRs on the vector path).
+  static constexpr bool MFMA_K = (sizeof(T) == 2) && (G >= 8) && (G <= 16) && (D % 32 == 0);
+  static constexpr int LV = CH;
+  static constexpr int RV = 64 / LV;  // rows per wave pass, PV pass
+  static constexpr int UV = (G >= 8) ? 2 : 4;
+  static_assert(D % VEC == 0 && CH <= 64 && (CH & (CH - 1)) == 0, "row geometry");
+};
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+}  // namespace
+}  // namespace tova
+#endif  // TOVA_DEVICE_H
