@@ -9,7 +9,9 @@ What is pinned and what is not:
   * attend / select / update (the per-step arithmetic and the victim rule) are
     pinned by the CPU tests against textbook full attention when the cache
     never fills, brute-force recomputation from the raw stream on tiny inputs,
-    the ordered-list formulation of the paper's appendix algorithm, closed
+    the ordered-list formulation of the paper's appendix algorithm, the mask
+    formulation over a whole prompt (which also defines what a multi-token call
+    must produce), closed
     forms (capacity 1, identical keys, a dominating key) and invariants.
   * the absolute victim sequences on the large synthetic configurations are
     "parity unpinned" by the paper itself (it prints no worked numeric
@@ -18,3 +20,4 @@ What is pinned and what is not:
 """
 from .tova_oracle import TovaOracle, TovaHeadOracle, run_stream  # noqa: F401
 from .tova_literal import tova_policy, LiteralTova  # noqa: F401
+from .tova_masked import tova_masked_prompt  # noqa: F401

@@ -260,5 +260,30 @@ def pin_gqa_grouping(Oracle):
     assert ev == [-1, -1, -1, 1]
 
 
+# P10 -- a whole prompt under the mask formulation (appendix on the language-modelling runs: the
+# policy folded into the attention mask, K and V never moved) gives what the single-token steps
+# give: same outputs, same token removed at every position, same final multi-state.  It is also
+# the definition of what a multi-token call must produce.
+def pin_mask_formulation(Oracle):
+    from oracle.tova_masked import tova_masked_prompt
+    rng = np.random.default_rng(23)
+    for (T, H, H_kv, d, k) in [(40, 4, 4, 8, 5), (60, 8, 2, 16, 12), (25, 6, 1, 4, 1), (30, 4, 2, 8, 40)]:
+        q, kk, vv = _stream(rng, T, H, H_kv, d)
+        out_m, mask, dropped = tova_masked_prompt(q, kk, vv, k)
+        orc = Oracle(k, H, H_kv, d)
+        for t in range(T):
+            held_before = set(int(x) for x in orc.slot_token[: orc.n])
+            r = orc.step(q[t], kk[t], vv[t])
+            assert set(np.flatnonzero(mask[t])) == held_before | {t}
+            np.testing.assert_allclose(r.out, out_m[t], rtol=1e-11, atol=1e-13)
+            if r.evicted < 0:
+                assert dropped[t] == -1
+            elif r.evicted == k:
+                assert dropped[t] == t
+            else:
+                assert dropped[t] in held_before and dropped[t] not in set(int(x) for x in orc.slot_token[: orc.n])
+        assert int(mask.sum(axis=1).max()) <= k + 1          # never more than the multi-state plus the newcomer
+
+
 ALL_PINS = [pin_full_attention, pin_occupancy, pin_brute_force, pin_one_leaves, pin_simplex_hull,
-            pin_v_independence_and_permutation, pin_closed_forms, pin_gqa_grouping]
+            pin_v_independence_and_permutation, pin_closed_forms, pin_gqa_grouping, pin_mask_formulation]
