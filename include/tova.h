@@ -89,6 +89,8 @@ typedef struct {
   int32_t unit_workgroups;  /* nonzero: a workgroup handles a whole (layer, sequence) unit, its KV
                                heads in turn (chosen when L * B alone fills the device); grid_blocks
                                is then L * B, walked by at most a device-filling number of workgroups */
+  int32_t prefill_group;    /* tokens of a prompt that share one pass over the cache in tova_prefill
+                               (0: it goes token by token)                                         */
 } tova_layout_t;
 
 /* Sizes of the three caller-owned DEVICE buffers.  kv_bytes is exactly
@@ -137,6 +139,22 @@ int tova_decode_step(tova_cache_t* cache, const void* q, const void* k_new, cons
  * (read by tova_cache_init / tova_cache_layout) overrides the choice between the two forms. */
 int tova_decode_steps(tova_cache_t* cache, int32_t n_steps, const void* q, const void* k_new,
                       const void* v_new, void* out, int32_t* evicted, void* hip_stream);
+
+/* A prompt: n_tokens consecutive tokens that are all known in advance (num_q > 1 in the terms of
+ * App. B).  Arguments and results are those of tova_decode_steps -- every token attends over what
+ * the multi-state holds after the tokens before it, and is followed by the policy, exactly as if
+ * it had been given alone; this is the mask formulation the paper uses to score whole texts --
+ * but because the queries are known together, groups of 2 to 8 tokens share one pass over the
+ * cache (K and V are read once per group instead of once per token).  A later token of a group is
+ * corrected for what the earlier ones removed, and the victim is found among the few candidates
+ * whose score bounds allow it, from scores recomputed exactly; outputs and victims agree with
+ * tova_decode_steps to rounding (different summation order).  Grouping needs the
+ * workgroup-per-unit form (layout: unit_workgroups), a full cache and 1, 2 or 4 query heads per
+ * KV head; whatever does not meet that (the fill phase, a remainder shorter than a group, other
+ * shapes) is processed token by token through tova_decode_steps.  TOVA_PREFILL_GROUP=0 in the
+ * environment turns grouping off. */
+int tova_prefill(tova_cache_t* cache, int32_t n_tokens, const void* q, const void* k_new,
+                 const void* v_new, void* out, int32_t* evicted, void* hip_stream);
 
 /* How tova_decode_steps launches once the cache is full (decided in tova_cache_init, which asks
  * the device how many workgroups fit): *blocks = 0 -> one launch per step; otherwise the number

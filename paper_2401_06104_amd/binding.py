@@ -36,7 +36,7 @@ class TovaLayout(ctypes.Structure):
     _fields_ = [("k_offset", c_size_t), ("v_offset", c_size_t), ("occupancy_offset", c_size_t),
                 ("slot_token_offset", c_size_t), ("error_flag_offset", c_size_t), ("n_splits", c_int32), ("rows_per_split", c_int32),
                 ("block_threads", c_int32), ("grid_blocks", c_int32), ("lds_bytes", c_int32),
-                ("unit_workgroups", c_int32)]
+                ("unit_workgroups", c_int32), ("prefill_group", c_int32)]
 
 
 def library_path() -> str:
@@ -60,6 +60,7 @@ def load_library() -> ctypes.CDLL:
     lib.tova_decode_step.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.tova_decode_steps.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                       c_void_p, c_void_p]
+    lib.tova_prefill.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.tova_cache_tokens_seen.argtypes = [c_void_p, POINTER(c_int64)]
     lib.tova_cache_multi_step_blocks.argtypes = [c_void_p, POINTER(c_int32)]
     lib.tova_cache_set_tokens_seen.argtypes = [c_void_p, c_int64]
@@ -67,7 +68,7 @@ def load_library() -> ctypes.CDLL:
     lib.tova_strerror.argtypes = [c_int]
     lib.tova_strerror.restype = c_char_p
     for name in ("tova_cache_bytes", "tova_cache_layout", "tova_cache_init", "tova_decode_step",
-                 "tova_decode_steps", "tova_cache_tokens_seen", "tova_cache_set_tokens_seen",
+                 "tova_decode_steps", "tova_prefill", "tova_cache_tokens_seen", "tova_cache_set_tokens_seen",
                  "tova_cache_multi_step_blocks",
                  "tova_cache_destroy"):
         getattr(lib, name).restype = c_int
@@ -221,6 +222,20 @@ class TovaCache:
                                         out.data_ptr(), ev, _stream_handle(stream))
         if rc != TOVA_OK:
             raise TovaError(rc, "tova_decode_steps")
+
+    def prefill(self, q, k_new, v_new, out, evicted=None, stream=None):
+        """A prompt of T tokens known in advance: same arguments and results as decode_steps."""
+        c = self.cfg
+        T = q.shape[0]
+        self._check("q", q, (T, c.n_layers, c.batch, c.n_q_heads, c.head_dim))
+        self._check("k_new", k_new, (T, c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        self._check("v_new", v_new, (T, c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        self._check("out", out, (T, c.n_layers, c.batch, c.n_q_heads, c.head_dim))
+        ev = self._evicted_ptr(evicted, (T, *self.state_shape))
+        rc = self.lib.tova_prefill(self._h, T, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
+                                   out.data_ptr(), ev, _stream_handle(stream))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_prefill")
 
     def _evicted_ptr(self, evicted, shape):
         if evicted is None:

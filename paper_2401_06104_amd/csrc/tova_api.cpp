@@ -16,6 +16,7 @@ namespace {
 constexpr size_t kAlign = 256;
 constexpr int kTargetBlocks = 512;     // two workgroups per CU on 256 CUs
 constexpr int kUnitModeUnits = 256;    // from one unit per CU on, a workgroup takes a whole unit
+constexpr int kPrefillMaxGrid = 1024;  // workgroups of the multi-token kernel (each has a scratch area of its own)
 constexpr size_t kMinBytesPerSplit = 256 * 1024;  // K+V bytes of a chunk below which splitting only adds
                                                   // hand-offs (each costs ~1 us of memory round trip)
 constexpr int kSmallFloats = 512;      // must match the kernel's fixed LDS area
@@ -31,6 +32,8 @@ struct Resolved {
   int n_pinned, per_head;
   int units, pairs, S, R, kp, NT, grid, lds, st_off, spin_limit, force_slow, persist_spin, multi_step, multi_grid, spin_env;
   int unit_mode;  // one workgroup per unit instead of one per (unit, KV head, chunk)
+  int pf_C, pf_NT, pf_lds, pf_e_floats, pf_ncp;  // multi-token kernel: tokens per group (0 = not available) and its LDS plan
+  size_t uscr_off;
   float scale;
   size_t kv_bytes, state_bytes, scratch_bytes;
   size_t v_off;                                   // in kv_mem
@@ -104,6 +107,28 @@ int resolve(const tova_config_t* c, Resolved* r) {
         r->unit_mode = 1;
         r->S = 1; r->R = k; r->NT = nt; r->st_off = (int)st;
         r->lds = (int)((kSmallFloats + st + s_fl) * 4);
+      }
+    }
+  }
+
+  // ---- groups of C prompt tokens per pass over the cache (workgroup-per-unit form only) ----
+  // C * G (token, head) combinations share a streamed row; the vector passes hold at most 8.
+  r->pf_C = 0;
+  if (r->unit_mode) {
+    const int cands[3] = {8, 4, 2};
+    for (int ci = 0; ci < 3 && !r->pf_C; ++ci) {
+      const int C = cands[ci], GE = G * C;
+      const bool built = (G == 1 && (C == 4 || C == 8)) || (G == 2 && (C == 2 || C == 4)) || (G == 4 && C == 2);
+      if (!built) continue;
+      const int nt = nt_env ? nt_env : (k >= 512 ? 512 : 256);
+      const long long NC = (long long)k + C, ncp = (NC + 3) / 4 * 4;
+      long long e_fl = NC * GE;
+      if ((long long)(nt / 64) * GE * r->D > e_fl) e_fl = (long long)(nt / 64) * GE * r->D;
+      if ((long long)r->H * r->D + NC > e_fl) e_fl = (long long)r->H * r->D + NC;
+      e_fl = (e_fl + 3) / 4 * 4;
+      const long long tot = kSmallFloats + e_fl + C * ncp + 2LL * r->H * C + r->H + (long long)C * r->H;
+      if (tot * 4 <= kMaxLdsBytesUnit) {
+        r->pf_C = C; r->pf_NT = nt; r->pf_lds = (int)(tot * 4); r->pf_e_floats = (int)e_fl; r->pf_ncp = (int)ncp;
       }
     }
   }
@@ -197,6 +222,11 @@ int resolve(const tova_config_t* c, Resolved* r) {
     r->stats_off = off; off += round_up((size_t)r->pairs * S * G * 2 * 4, kAlign);
     r->accp_off = off; off += 2 * round_up((size_t)r->pairs * S * G * r->D * 4, kAlign);  // two parity copies
   }
+  r->uscr_off = off;
+  if (r->pf_C) {
+    const size_t blocks = (size_t)(r->units < kPrefillMaxGrid ? r->units : kPrefillMaxGrid);
+    off += round_up(blocks * r->H * r->pf_C * r->D * 4, kAlign);
+  }
   r->scratch_bytes = off;
   return TOVA_OK;
 }
@@ -247,6 +277,7 @@ int tova_cache_layout(const tova_config_t* cfg, tova_layout_t* layout) {
   layout->grid_blocks = r.grid;
   layout->lds_bytes = r.lds;
   layout->unit_workgroups = r.unit_mode;
+  layout->prefill_group = r.pf_C;
   return TOVA_OK;
 }
 
@@ -308,6 +339,60 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
     return hip_fail(e, "tova_cache_init");
   }
   *out = c;
+  return TOVA_OK;
+}
+
+int tova_prefill(tova_cache_t* c, int32_t n_tokens, const void* q, const void* k_new, const void* v_new,
+                 void* out, int32_t* evicted, void* hip_stream) {
+  if (!c || n_tokens < 0) return TOVA_EINVAL;
+  if (n_tokens == 0) return TOVA_OK;
+  if (!q || !k_new || !v_new || !out) return TOVA_EINVAL;
+  if (!aligned(q, 16) || !aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(out, 16) || !aligned(evicted, 4))
+    return TOVA_EINVAL;
+  const Resolved& r = c->r;
+  if (c->t + n_tokens > 0x7fffffffLL) return TOVA_ENOSUP;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const size_t q_step = (size_t)r.units * r.H * r.D * r.esize;
+  const size_t kv_step = (size_t)r.pairs * r.D * r.esize;
+  int C = r.pf_C;
+  if (const char* e = std::getenv("TOVA_PREFILL_GROUP")) {  // test hook: 0 = token by token
+    if (std::atoi(e) == 0) C = 0;
+  }
+  for (int32_t i = 0; i < n_tokens;) {
+    const void* qi = static_cast<const char*>(q) + (size_t)i * q_step;
+    const void* ki = static_cast<const char*>(k_new) + (size_t)i * kv_step;
+    const void* vi = static_cast<const char*>(v_new) + (size_t)i * kv_step;
+    void* oi = static_cast<char*>(out) + (size_t)i * q_step;
+    int32_t* ei = evicted ? evicted + (size_t)i * r.units : nullptr;
+    int32_t m = n_tokens - i;
+    if (c->t < r.k) {
+      // while the multi-state fills nothing is removed: token by token (App. B: early return)
+      if (m > r.k - c->t) m = (int32_t)(r.k - c->t);
+    } else if (C >= 2 && m >= C) {
+      const int32_t n_chunks = m / C;
+      m = n_chunks * C;
+      tova::PrefillParams p;
+      p.q = qi; p.k_new = ki; p.v_new = vi; p.out = oi; p.evicted = ei;
+      p.K = c->kv; p.V = c->kv + r.v_off;
+      p.slot_token = reinterpret_cast<int32_t*>(c->state + r.slot_off);
+      p.uscr = reinterpret_cast<float*>(c->scratch + r.uscr_off);
+      p.q_stride = (int64_t)(q_step / r.esize); p.kv_stride = (int64_t)(kv_step / r.esize);
+      p.n_chunks = n_chunks; p.units = r.units; p.H = r.H; p.H_kv = r.H_kv; p.k = r.k;
+      p.n_pinned = r.n_pinned; p.t = (int32_t)c->t; p.e_floats = r.pf_e_floats; p.ncp = r.pf_ncp; p.scale = r.scale;
+      int grid = r.multi_grid > 0 ? r.multi_grid : r.units;
+      if (grid > kPrefillMaxGrid) grid = kPrefillMaxGrid;
+      if (grid > r.units) grid = r.units;
+      const tova::LaunchPlan lp{grid, r.pf_NT, r.pf_lds};
+      const hipError_t e = tova::launch_prefill(r.bf16, r.D, r.G, C, p, lp, s);
+      if (e != hipSuccess) return hip_fail(e, "tova_prefill launch");
+      c->t += m;
+      i += m;
+      continue;
+    }
+    const int rc = tova_decode_steps(c, m, qi, ki, vi, oi, ei, hip_stream);
+    if (rc != TOVA_OK) return rc;
+    i += m;
+  }
   return TOVA_OK;
 }
 

@@ -52,12 +52,36 @@ struct StepParams {
   float scale;
 };
 
+// Arguments of one launch of the multi-token kernel (groups of C tokens of a prompt, cache full,
+// one workgroup per unit).
+struct PrefillParams {
+  const void* q;       // [n_chunks * C][units][H][d]   first token of the launch
+  const void* k_new;   // [n_chunks * C][units][H_kv][d]
+  const void* v_new;
+  void* out;           // like q
+  int32_t* evicted;    // [n_chunks * C][units] or null
+  void* K;             // [units][H_kv][k][d]
+  void* V;
+  int32_t* slot_token; // [units][k]
+  float* uscr;         // [grid][H][C][d] fp32: unmasked PV sums of the unit a workgroup is at
+  int64_t q_stride, kv_stride;  // elements between consecutive tokens of q / out and of k_new / v_new
+  int32_t n_chunks;    // groups of C tokens in this launch
+  int32_t units, H, H_kv, k;
+  int32_t n_pinned;
+  int32_t t;           // index of the first token of the launch
+  int32_t e_floats;    // floats of the first big LDS area (logits / reduction / resolution buffers)
+  int32_t ncp;         // k + C rounded up to a multiple of 4: stride of the tentative score rows
+  float scale;
+};
+
 struct LaunchPlan {
   int32_t grid, block, lds_bytes;
 };
 
 hipError_t launch_step(int dtype_is_bf16, int D, int G, const StepParams& p, const LaunchPlan& lp,
                        hipStream_t stream);
+hipError_t launch_prefill(int dtype_is_bf16, int D, int G, int C, const PrefillParams& p, const LaunchPlan& lp,
+                          hipStream_t stream);
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_t stream);
 // how many blocks of the step kernel (given instantiation, block size, dynamic LDS) fit on the
 // current device at once; 0 if the query fails

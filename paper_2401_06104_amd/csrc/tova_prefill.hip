@@ -1,0 +1,512 @@
+// Multi-token steps for gfx950 (MI355X): C consecutive tokens of a prompt per pass over the cache.
+//
+// What it computes is fixed by the single-token step (Sec. 3.2, Sec. 4, App. B Alg. 1): token
+// t + i of a group attends over what the bounded multi-state holds after tokens t .. t + i - 1
+// have been processed (plus itself), and the policy then removes one row -- the mask formulation
+// of the paper's language-modelling runs, where all positions of a text are scored at once with a
+// mask derived row by row from the layer's own attention weights.  A prompt is known in advance,
+// so the queries of C tokens can share one stream of K and one of V; what one token changes for
+// the next is small and is applied as a correction:
+//
+//   candidates        the k cached rows and the group's own C tokens (candidate k + i); token i
+//                     may see candidate k + i' only for i' <= i
+//   pass A            per KV head, K and V streamed ONCE for all C tokens: logits, maxima m and
+//                     sums Z over all causally allowed candidates, the unmasked PV sums U, and the
+//                     "tentative" scores T_i[c] = sum_heads w_i[c] / Z_i   (w = 2^(l - m))
+//   resolution        token by token (i = 0 .. C-1), with E_i = candidates removed by tokens < i:
+//                     Z'_i = Z_i - sum_{e in E_i} w_i[e]          (a few dot products)
+//                     exact score s_i[c] = sum_heads w_i[c] / Z'_i lies in [T_i[c], T_i[c] f_max]
+//                     with f = Z / Z' >= 1 per head, so only candidates whose lower bound does not
+//                     exceed the smallest upper bound can be the argmin; their scores are
+//                     recomputed exactly from their K rows and the argmin is taken among them
+//                     (lowest slot index on ties, the token itself last)
+//                     out_i = (U_i - sum_{e in E_i} w_i[e] V[e]) / Z'_i
+//   commit            tokens that still hold a slot at the end are stored there.
+//
+// One workgroup per (layer, sequence) unit, KV heads in turn (the form of the single-token kernel
+// for many units): nothing is exchanged between workgroups.  Cache full, one chunk per KV head.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tova_internal.h"
+
+#include "tova_device.h"
+
+namespace tova {
+namespace {
+
+template <typename T>
+__device__ __forceinline__ float elem_f32(const T* p, int idx);
+template <>
+__device__ __forceinline__ float elem_f32<float>(const float* p, int idx) {
+  return p[idx];
+}
+template <>
+__device__ __forceinline__ float elem_f32<bf16_t>(const bf16_t* p, int idx) {
+  return __uint_as_float((uint32_t)p[idx].x << 16);
+}
+
+constexpr float kBoundSlack = 1e-4f;  // rounding of the streamed sums against the recomputed ones: ~1e-6
+
+template <typename T, int D, int G, int C>
+__global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel(const PrefillParams p) {
+  using E = Elem<T>;
+  constexpr int GE = G * C;  // (token, query head) combinations served by one streamed row
+  using Ge = Geo<T, D, GE>;
+  constexpr int VEC = Ge::VEC, CK = Ge::CK, LK = Ge::LK, RK = Ge::RK, UK = Ge::UK;
+  constexpr int LV = Ge::LV, RV = Ge::RV, UV = Ge::UV;
+  constexpr int ROW16 = D * (int)sizeof(T) / 16;
+  constexpr int EPL = (D + 63) / 64;  // elements of a row per lane in the exact recomputation
+  static_assert(GE <= 8 && C <= 8, "register budget of the vector passes");
+
+  extern __shared__ float4 smem4[];
+  float* small = reinterpret_cast<float*>(smem4);
+  float* big = small + kSmallFloats;
+  const int nt = blockDim.x;
+  const int nw = nt >> 6;
+  const int k = p.k, NC = p.k + C, H = p.H, ncp = p.ncp;
+  float* e_lds = big;               // [NC][GE] logits, then exp values; reduction area; resolution buffers
+  float* t_lds = big + p.e_floats;  // [C][ncp] tentative scores
+  float* mst = t_lds + C * ncp;     // [H][C] maxima (log2 domain)
+  float* zst = mst + H * C;         // [H][C] sums over all causally allowed candidates
+  float* zcs = zst + H * C;         // [H]    corrected sums of the token being resolved
+  float* wev = zcs + H;             // [C][H] that token's weights of the candidates removed before it
+  int* pos = reinterpret_cast<int*>(small + 384);  // [C] slot a group token holds (-1: none)
+  int* vict = pos + 8;                             // [C] candidate removed at step i
+  int* misc = vict + 8;                            // [0] contender count
+  const float scale2 = p.scale * kLog2e;
+  float* const ublk = p.uscr + (size_t)blockIdx.x * H * C * D;  // [H][C][D] unmasked PV sums of the unit at hand
+
+  for (int ch = 0; ch < p.n_chunks; ++ch) {
+  for (int unit = blockIdx.x; unit < p.units; unit += gridDim.x) {
+  const int pair0 = unit * p.H_kv;
+  const size_t tok_q = (size_t)ch * C * p.q_stride;    // element offset of the group's first token in q / out
+  const size_t tok_kv = (size_t)ch * C * p.kv_stride;  // ... in k_new / v_new
+
+  // ================= pass A: one stream of K and V per KV head for all C tokens =================
+  for (int kvh = 0; kvh < p.H_kv; ++kvh) {
+  // (a fresh opaque copy of the thread index per KV head: otherwise the lane arithmetic of the
+  // body is hoisted out of the loops and kept in registers across them)
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int pair = pair0 + kvh;
+  const T* Kb = reinterpret_cast<const T*>(p.K) + (size_t)pair * k * D;
+  const T* Vb = reinterpret_cast<const T*>(p.V) + (size_t)pair * k * D;
+  const T* knew0 = reinterpret_cast<const T*>(p.k_new) + tok_kv + (size_t)pair * D;
+  const T* vnew0 = reinterpret_cast<const T*>(p.v_new) + tok_kv + (size_t)pair * D;
+  const T* qb0 = reinterpret_cast<const T*>(p.q) + tok_q + ((size_t)unit * H + (size_t)kvh * G) * D;
+
+  // ---- logits (log2 domain) of all (token, head) combinations against every candidate
+  float m[GE], Z[GE];
+#pragma unroll
+  for (int ge = 0; ge < GE; ++ge) m[ge] = -INFINITY;
+  {
+    const int lk = lane % LK;
+    const int rk = lane / LK;
+    V16 qf[GE][CK];
+#pragma unroll
+    for (int ge = 0; ge < GE; ++ge) {
+      const T* qg = qb0 + (size_t)(ge / G) * p.q_stride + (ge % G) * D;
+#pragma unroll
+      for (int c = 0; c < CK; ++c) qf[ge][c] = *reinterpret_cast<const V16*>(qg + (c * LK + lk) * VEC);
+    }
+    auto load_tile = [&](V16(&dst)[UK][CK], int base) {
+#pragma unroll
+      for (int u = 0; u < UK; ++u) {
+        const int j = base + u * RK + rk;
+#pragma unroll
+        for (int c = 0; c < CK; ++c) dst[u][c] = V16{{0u, 0u, 0u, 0u}};
+        if (j < k) {
+          const T* row = Kb + (size_t)j * D;
+#pragma unroll
+          for (int c = 0; c < CK; ++c) dst[u][c] = *reinterpret_cast<const V16*>(row + (c * LK + lk) * VEC);
+        }
+      }
+    };
+    auto logits_of = [&](const V16(&row)[CK], float(&l2)[GE]) {
+#pragma unroll
+      for (int ge = 0; ge < GE; ++ge) {
+        float a = 0.f;
+#pragma unroll
+        for (int c = 0; c < CK; ++c) a = E::dot(row[c], qf[ge][c], a);
+        l2[ge] = group_sum<LK>(a) * scale2;
+      }
+    };
+    auto compute_tile = [&](const V16(&src)[UK][CK], int base) {
+#pragma unroll
+      for (int u = 0; u < UK; ++u) {
+        const int j = base + u * RK + rk;
+        float l2[GE];
+        logits_of(src[u], l2);
+        if (j < k) {
+#pragma unroll
+          for (int ge = 0; ge < GE; ++ge) m[ge] = fmaxf(m[ge], l2[ge]);
+          if (lk == 0) {
+#pragma unroll
+            for (int ge = 0; ge < GE; ++ge) e_lds[j * GE + ge] = l2[ge];
+          }
+        }
+      }
+    };
+    constexpr int TILE = RK * UK;
+    const int stride = nw * TILE;
+    int base = wave * TILE;
+    V16 bufA[UK][CK], bufB[UK][CK];
+    load_tile(bufA, base);
+    if (wave == nw - 1) {  // the group's own tokens as candidates k .. k + C - 1 (wave-uniform)
+      for (int i2 = 0; i2 < C; ++i2) {
+        V16 kn[CK];
+#pragma unroll
+        for (int c = 0; c < CK; ++c)
+          kn[c] = *reinterpret_cast<const V16*>(knew0 + (size_t)i2 * p.kv_stride + (c * LK + lk) * VEC);
+        float l2[GE];
+        logits_of(kn, l2);
+#pragma unroll
+        for (int ge = 0; ge < GE; ++ge) {
+          if (ge / G < i2) l2[ge] = -INFINITY;  // a token does not see a later one
+          m[ge] = fmaxf(m[ge], l2[ge]);
+        }
+        if (lane == 0) {
+#pragma unroll
+          for (int ge = 0; ge < GE; ++ge) e_lds[(k + i2) * GE + ge] = l2[ge];
+        }
+      }
+    }
+    while (base < k) {
+      load_tile(bufB, base + stride);
+      compute_tile(bufA, base);
+      base += stride;
+      if (base >= k) break;
+      load_tile(bufA, base + stride);
+      compute_tile(bufB, base);
+      base += stride;
+    }
+  }
+
+  // the first V tile is requested before the softmax barriers
+  const int lv = lane % LV;
+  const int rv = lane / LV;
+  constexpr int TILEV = RV * UV;
+  const int stridev = nw * TILEV;
+  auto load_vtile = [&](V16(&dst)[UV], int base) {
+#pragma unroll
+    for (int u = 0; u < UV; ++u) {
+      const int j = base + u * RV + rv;
+      dst[u] = V16{{0u, 0u, 0u, 0u}};
+      if (j < k) dst[u] = *reinterpret_cast<const V16*>(Vb + (size_t)j * D + lv * VEC);
+    }
+  };
+  V16 vA[UV], vB[UV];
+  int basev = wave * TILEV;
+  load_vtile(vA, basev);
+
+  // ---- maxima, exp values, sums over all causally allowed candidates
+  block_reduce<GE, true>(m, small, lane, wave, nw);
+#pragma unroll
+  for (int ge = 0; ge < GE; ++ge) Z[ge] = 0.f;
+  for (int c = tid; c < NC; c += nt) {
+#pragma unroll
+    for (int ge = 0; ge < GE; ++ge) {
+      const float e = __builtin_amdgcn_exp2f(e_lds[c * GE + ge] - m[ge]);  // (masked: 2^-inf = 0)
+      e_lds[c * GE + ge] = e;
+      Z[ge] += e;
+    }
+  }
+  block_reduce<GE, false>(Z, small + kMaxWaves * GE, lane, wave, nw);
+
+  // ---- tentative scores (heads in order; entry c is always this thread's) and the statistics
+  {
+    float rz[GE];
+#pragma unroll
+    for (int ge = 0; ge < GE; ++ge) rz[ge] = 1.0f / Z[ge];
+    for (int c = tid; c < NC; c += nt) {
+#pragma unroll
+      for (int i = 0; i < C; ++i) {
+        float a = 0.f;
+#pragma unroll
+        for (int g = 0; g < G; ++g) a = fmaf(e_lds[c * GE + i * G + g], rz[i * G + g], a);
+        t_lds[i * ncp + c] = (kvh == 0) ? a : t_lds[i * ncp + c] + a;
+      }
+    }
+#pragma unroll
+    for (int ge = 0; ge < GE; ++ge) {
+      if (tid == ge) {
+        const int hq = kvh * G + ge % G;
+        mst[hq * C + ge / G] = m[ge];
+        zst[hq * C + ge / G] = Z[ge];
+      }
+    }
+  }
+
+  // ---- unmasked PV sums: U_(i,g) = sum over allowed candidates of w V
+  float acc[GE][VEC];
+#pragma unroll
+  for (int ge = 0; ge < GE; ++ge)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[ge][v] = 0.f;
+  auto accumulate = [&](const V16& row, const float(&w)[GE]) {
+    float vf[VEC];
+    E::unpack(row, vf);
+#pragma unroll
+    for (int ge = 0; ge < GE; ++ge)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[ge][v] = fmaf(w[ge], vf[v], acc[ge][v]);
+  };
+  auto compute_vtile = [&](const V16(&src)[UV], int base) {
+#pragma unroll
+    for (int u = 0; u < UV; ++u) {
+      const int j = base + u * RV + rv;
+      float w[GE];
+#pragma unroll
+      for (int ge = 0; ge < GE; ++ge) w[ge] = (j < k) ? e_lds[j * GE + ge] : 0.f;
+      accumulate(src[u], w);
+    }
+  };
+  if (wave == nw - 1) {  // the group's own value rows
+    for (int i2 = 0; i2 < C; ++i2) {
+      const V16 vn = *reinterpret_cast<const V16*>(vnew0 + (size_t)i2 * p.kv_stride + lv * VEC);
+      float w[GE];
+#pragma unroll
+      for (int ge = 0; ge < GE; ++ge) w[ge] = (rv == 0) ? e_lds[(k + i2) * GE + ge] : 0.f;
+      accumulate(vn, w);
+    }
+  }
+  while (basev < k) {
+    load_vtile(vB, basev + stridev);
+    compute_vtile(vA, basev);
+    basev += stridev;
+    if (basev >= k) break;
+    load_vtile(vA, basev + stridev);
+    compute_vtile(vB, basev);
+    basev += stridev;
+  }
+  float* red = big;  // [nw][GE * D]
+#pragma unroll
+  for (int ge = 0; ge < GE; ++ge)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[ge][v] = column_sum<LV>(acc[ge][v]);
+  __syncthreads();  // everyone is done reading the exp values; the reduction area reuses them
+  if (rv == 0) {
+#pragma unroll
+    for (int ge = 0; ge < GE; ++ge)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) red[(wave * GE + ge) * D + lv * VEC + v] = acc[ge][v];
+  }
+  __syncthreads();
+  for (int x = tid; x < GE * D; x += nt) {
+    float a = red[x];
+    for (int w = 1; w < nw; ++w) a += red[w * GE * D + x];
+    const int ge = x / D;
+    ublk[((size_t)(kvh * G + ge % G) * C + ge / G) * D + (x - ge * D)] = a;
+  }
+  __syncthreads();  // the reduction area is free for the next KV head
+  }  // KV heads
+
+  // ================= resolution: token by token =================
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0);  // the U sums are in memory before other waves read them
+  if (tid < C) pos[tid] = -1;
+  __syncthreads();
+  float* qs = e_lds;                                       // [H][D] the token's queries in fp32
+  int* cont = reinterpret_cast<int*>(e_lds + (size_t)H * D);  // candidates that may be the argmin
+  int32_t* const evp = p.evicted ? p.evicted + (size_t)ch * C * p.units : nullptr;
+
+  // w of candidate `cand` for every query head of token i, handed to `sink(hq, w)` by all lanes
+  // of the calling wave (a wave per candidate; lanes split the row's elements)
+  auto weights_of = [&](int i, int cand, auto&& sink) {
+    for (int h = 0; h < p.H_kv; ++h) {
+      const T* row = (cand < k) ? reinterpret_cast<const T*>(p.K) + ((size_t)(pair0 + h) * k + cand) * D
+                                : reinterpret_cast<const T*>(p.k_new) + tok_kv + (size_t)(cand - k) * p.kv_stride +
+                                      (size_t)(pair0 + h) * D;
+      float kx[EPL];
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) kx[e] = (lane + 64 * e < D) ? elem_f32<T>(row, lane + 64 * e) : 0.f;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const int hq = h * G + g;
+        float part = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e)
+          if (lane + 64 * e < D) part = fmaf(kx[e], qs[hq * D + lane + 64 * e], part);
+        const float l2 = group_reduce<64, false>(part) * scale2;
+        sink(hq, __builtin_amdgcn_exp2f(l2 - mst[hq * C + i]));
+      }
+    }
+  };
+  // slot index a candidate stands for when scores tie (the token at hand counts as index k)
+  auto position = [&](int i, int cand) { return cand < k ? cand : (cand == k + i ? k : pos[cand - k]); };
+
+  for (int i = 0; i < C; ++i) {
+    const T* qi = reinterpret_cast<const T*>(p.q) + tok_q + (size_t)i * p.q_stride + (size_t)unit * H * D;
+    for (int x = tid; x < H * D; x += nt) qs[x] = elem_f32<T>(qi, x);
+    __syncthreads();
+    // (a) what the candidates removed by the group's earlier tokens weigh for this token
+    for (int e = wave; e < i; e += nw)
+      weights_of(i, vict[e], [&](int hq, float w) {
+        if (lane == 0) wev[e * H + hq] = w;
+      });
+    __syncthreads();
+    // (b) corrected sums; f = Z / Z' >= 1 per head, f_max its largest value (1 is used as the lower end)
+    float fr[1] = {1.0f};
+    for (int hq = tid; hq < H; hq += nt) {
+      const float zf = zst[hq * C + i];
+      float d = 0.f;
+      for (int e = 0; e < i; ++e) d += wev[e * H + hq];
+      const float zc = zf - d;
+      zcs[hq] = zc;
+      fr[0] = fmaxf(fr[0], zf / zc);
+    }
+    block_reduce<1, true>(fr, small, lane, wave, nw);
+    const float f_max = fr[0];
+    // (c) the smallest upper bound, then the candidates whose lower bound does not exceed it
+    const float* Ti = t_lds + i * ncp;
+    auto alive = [&](int c) {
+      if (c < p.n_pinned) return false;  // TOVA+i (App. A): the first tokens hold slots 0 .. n_pinned-1
+      for (int e = 0; e < i; ++e)
+        if (vict[e] == c) return false;
+      return true;
+    };
+    float lo[1] = {-INFINITY};  // -(min T)
+    for (int c = tid; c <= k + i; c += nt)
+      if (alive(c)) lo[0] = fmaxf(lo[0], -Ti[c]);
+    if (tid == 0) misc[0] = 0;
+    block_reduce<1, true>(lo, small + 64, lane, wave, nw);
+    const float bound = -lo[0] * f_max * (1.0f + kBoundSlack);
+    for (int c = tid; c <= k + i; c += nt)
+      if (alive(c) && Ti[c] * (1.0f - kBoundSlack) <= bound) cont[atomicAdd(&misc[0], 1)] = c;
+    __syncthreads();
+    const int ncont = misc[0];
+    // (d) exact scores of those (a wave per candidate), argmin by (score, slot index)
+    float best = INFINITY;
+    int bpos = 0x7fffffff, bcand = k + i;
+    for (int x = wave; x < ncont; x += nw) {
+      const int cand = cont[x];
+      float s = 0.f, a = 0.f;
+      weights_of(i, cand, [&](int hq, float w) {
+        a = fmaf(w, 1.0f / zcs[hq], a);
+        if (hq % G == G - 1) {  // KV-head partials added in head order, as the single-token kernels do
+          s += a;
+          a = 0.f;
+        }
+      });
+      const int pc = position(i, cand);
+      if (s < best || (s == best && pc < bpos)) {
+        best = s;
+        bpos = pc;
+        bcand = cand;
+      }
+    }
+    float* bv = small + 256;
+    int* bi = reinterpret_cast<int*>(small + 256 + kMaxWaves);
+    int* bc = bi + kMaxWaves;
+    if (lane == 0) {
+      bv[wave] = best;
+      bi[wave] = bpos;
+      bc[wave] = bcand;
+    }
+    __syncthreads();
+    best = bv[0];
+    bpos = bi[0];
+    bcand = bc[0];
+    for (int w = 1; w < nw; ++w) {
+      if (bv[w] < best || (bv[w] == best && bi[w] < bpos)) {
+        best = bv[w];
+        bpos = bi[w];
+        bcand = bc[w];
+      }
+    }
+    __syncthreads();  // (everyone has read pos / vict of the earlier tokens)
+    // (e) the token takes its victim's slot (or is dropped itself)
+    if (tid == 0) {
+      vict[i] = bcand;
+      if (bcand != k + i) {
+        pos[i] = bpos;
+        if (bcand >= k) pos[bcand - k] = -1;
+      }
+      if (evp) evp[(size_t)i * p.units + unit] = bpos;  // (bpos == k: the token itself)
+    }
+    // (f) the token's output: the removed candidates' share taken out of the unmasked sums
+    T* outi = reinterpret_cast<T*>(p.out) + tok_q + (size_t)i * p.q_stride + (size_t)unit * H * D;
+    for (int x = tid; x < H * D; x += nt) {
+      const int hq = x / D, dd = x - hq * D;
+      float a = ublk[((size_t)hq * C + i) * D + dd];
+      for (int e = 0; e < i; ++e) {
+        const int cand = vict[e];
+        const T* vrow = (cand < k) ? reinterpret_cast<const T*>(p.V) + ((size_t)(pair0 + hq / G) * k + cand) * D
+                                   : reinterpret_cast<const T*>(p.v_new) + tok_kv + (size_t)(cand - k) * p.kv_stride +
+                                         (size_t)(pair0 + hq / G) * D;
+        a = fmaf(-wev[e * H + hq], elem_f32<T>(vrow, dd), a);
+      }
+      E::store(outi + x, a / zcs[hq]);
+    }
+    __syncthreads();
+  }
+
+  // ================= commit: the tokens that still hold a slot =================
+  for (int i = 0; i < C; ++i) {
+    const int ps = pos[i];
+    if (ps < 0) continue;  // block-uniform
+    const T* kn = reinterpret_cast<const T*>(p.k_new) + tok_kv + (size_t)i * p.kv_stride + (size_t)pair0 * D;
+    const T* vn = reinterpret_cast<const T*>(p.v_new) + tok_kv + (size_t)i * p.kv_stride + (size_t)pair0 * D;
+    T* Ku = reinterpret_cast<T*>(p.K) + ((size_t)pair0 * k + ps) * D;
+    T* Vu = reinterpret_cast<T*>(p.V) + ((size_t)pair0 * k + ps) * D;
+    for (int x = tid; x < p.H_kv * ROW16; x += nt) {
+      const int h = x / ROW16, c16 = x - h * ROW16;
+      reinterpret_cast<V16*>(Ku + (size_t)h * k * D)[c16] = reinterpret_cast<const V16*>(kn)[x];
+      reinterpret_cast<V16*>(Vu + (size_t)h * k * D)[c16] = reinterpret_cast<const V16*>(vn)[x];
+    }
+    if (tid == 0) p.slot_token[(size_t)unit * k + ps] = p.t + ch * C + i;
+  }
+  // the rows must have landed before other waves of this block read them in the unit's next group
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  }  // units
+  }  // groups
+}
+
+template <typename T, int D>
+hipError_t launch_gc(int G, int C, const PrefillParams& p, const LaunchPlan& lp, hipStream_t s) {
+#define TOVA_PREFILL_CASE(g, c)                                                                              \
+  if (G == g && C == c) {                                                                                    \
+    if (lp.lds_bytes > 64 * 1024) {                                                                          \
+      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tova_prefill_kernel<T, D, g, c>), \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, lp.lds_bytes);   \
+      if (e != hipSuccess) return e;                                                                         \
+    }                                                                                                        \
+    hipLaunchKernelGGL((tova_prefill_kernel<T, D, g, c>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes, s, p); \
+    return hipGetLastError();                                                                                \
+  }
+  TOVA_PREFILL_CASE(1, 4)
+  TOVA_PREFILL_CASE(1, 8)
+  TOVA_PREFILL_CASE(2, 2)
+  TOVA_PREFILL_CASE(2, 4)
+  TOVA_PREFILL_CASE(4, 2)
+#undef TOVA_PREFILL_CASE
+  return hipErrorInvalidValue;
+}
+
+template <typename T>
+hipError_t launch_dgc(int D, int G, int C, const PrefillParams& p, const LaunchPlan& lp, hipStream_t s) {
+  switch (D) {
+    case 32: return launch_gc<T, 32>(G, C, p, lp, s);
+    case 64: return launch_gc<T, 64>(G, C, p, lp, s);
+    case 128: return launch_gc<T, 128>(G, C, p, lp, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_prefill(int dtype_is_bf16, int D, int G, int C, const PrefillParams& p, const LaunchPlan& lp,
+                          hipStream_t stream) {
+  return dtype_is_bf16 ? launch_dgc<bf16_t>(D, G, C, p, lp, stream) : launch_dgc<float>(D, G, C, p, lp, stream);
+}
+
+}  // namespace tova

@@ -27,7 +27,7 @@ GAP_EXEMPT = 1e-6
 
 def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: int = 256,
             single_step_calls: bool = False, device="cuda:0", prefill: bool = False, keep=None,
-            progress: bool = False, n_pinned: int = 0, per_head: bool = False):
+            progress: bool = False, n_pinned: int = 0, per_head: bool = False, use_prefill: bool = False):
     """units: list of (layer, seq) whose outputs are kept.  Returns a dict of CPU arrays.
 
     prefill=True skips the fill phase: the first k tokens are laid down directly (slot j holds
@@ -70,6 +70,8 @@ def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: 
         if single_step_calls:
             for i in range(t1 - t0):
                 cache.decode_step(c["q"][i], c["k"][i], c["v"][i], out[i], evicted[t0 + i])
+        elif use_prefill:          # the tokens of a chunk handed over as a prompt (tova_prefill)
+            cache.prefill(c["q"], c["k"], c["v"], out, evicted[t0:t1])
         else:
             cache.decode_steps(c["q"], c["k"], c["v"], out, evicted[t0:t1])
         for (a, b) in keep:
@@ -90,6 +92,7 @@ def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: 
         "layout": (cache.layout.n_splits, cache.layout.rows_per_split, cache.layout.block_threads,
                    cache.layout.grid_blocks),
         "unit_workgroups": int(cache.layout.unit_workgroups),
+        "prefill_group": int(cache.layout.prefill_group),
         "tokens_seen": cache.tokens_seen,
         "prefill": prefill,
     }

@@ -336,6 +336,94 @@ def test_unit_workgroups_multi_step_matches_per_step(monkeypatch):
         assert torch.equal(a, b)
 
 
+# ---- prompts: groups of tokens per pass over the cache (tova_prefill) -------------------------
+PREFILL_SWEEP = [
+    # dtype, d, H, H_kv, k, T, L, B, tokens per call, expected group
+    ("f32", 32, 4, 4, 37, 150, 2, 3, 50, 8),
+    ("f32", 64, 8, 4, 100, 260, 1, 2, 37, 4),         # calls that are no multiple of the group
+    ("f32", 128, 4, 2, 1, 40, 1, 1, 40, 4),            # capacity 1
+    ("f32", 128, 8, 2, 64, 200, 1, 2, 64, 2),
+    ("bf16", 128, 32, 8, 300, 520, 1, 3, 128, 2),
+    ("bf16", 128, 8, 8, 1025, 1300, 1, 2, 256, 8),
+    ("bf16", 64, 8, 4, 130, 300, 2, 2, 33, 4),
+    ("bf16", 32, 8, 2, 77, 200, 1, 5, 200, 2),
+]
+
+
+@pytest.mark.parametrize("dtype,d,H,H_kv,k,T,L,B,call,group", PREFILL_SWEEP)
+def test_prefill_groups_shape_sweep(dtype, d, H, H_kv, k, T, L, B, call, group, monkeypatch):
+    """tova_prefill: the tokens of a call are a prompt; groups of them share one pass over K and V.
+    Same bar as the single-token path: outputs within tolerance of the oracle's sequential steps,
+    victims equal except at near-ties."""
+    monkeypatch.setenv("TOVA_UNIT_MODE", "1")
+    spec = StreamSpec(f"prefill_{dtype}_d{d}_h{H}_{H_kv}_k{k}", L=L, B=B, H=H, H_kv=H_kv, d=d, dtype=dtype,
+                      k=k, T=T, sink="first", n_sinks=2)
+    units = [(l, b) for l in range(L) for b in range(B)][:4]
+    print(f"[parity] {spec.name} prefill calls of {call} tokens", flush=True)
+    res = parity.run_gpu(spec, 700 + k, units, n_splits=1, chunk_steps=call, use_prefill=True)
+    assert res["unit_workgroups"] == 1 and res["prefill_group"] == group
+    parity.check_global_invariants(spec, res)
+    stats = parity.check_units(spec, 700 + k, units, res, workers=4)
+    for s in stats:
+        print(f"[parity]   {s}", flush=True)
+    if dtype == "f32":
+        assert all(s["mismatches"] == 0 for s in stats)
+
+
+def test_prefill_identical_keys_evict_slot_zero(monkeypatch):
+    """Exact ties inside a group: with all keys equal every candidate scores the same for every
+    token, so each token must take slot 0 from its predecessor (lowest slot index, the token
+    itself last) -- the bounds leave every candidate in and the exact scores must tie bit for bit."""
+    from paper_2401_06104_amd import TovaCache
+    monkeypatch.setenv("TOVA_UNIT_MODE", "1")
+    L, B, H, H_kv, d, k, T = 1, 2, 4, 2, 64, 10, 58
+    g = torch.Generator().manual_seed(3)
+    q = torch.randn(T, L, B, H, d, generator=g).cuda()
+    kk = torch.randn(1, 1, 1, 1, d, generator=g).expand(T, L, B, H_kv, d).contiguous().cuda()
+    vv = torch.randn(T, L, B, H_kv, d, generator=g).cuda()
+    cache = TovaCache(L, B, k, H, H_kv, d, dtype="f32", n_splits=1)
+    assert cache.layout.prefill_group == 4
+    out = torch.empty_like(q)
+    ev = torch.empty(T, L, B, dtype=torch.int32, device="cuda:0")
+    cache.prefill(q, kk, vv, out, ev)
+    torch.cuda.synchronize()
+    assert (ev[:k] == -1).all() and (ev[k:] == 0).all()
+    st = cache.slot_token.cpu()
+    assert (st[..., 0] == T - 1).all() and (st[..., 1:] == torch.arange(1, k)).all()
+    # uniform attention over the k + 1 candidates: the output is their mean value
+    t = T - 1
+    held = torch.cat([vv[1:k, 0, 0], vv[t - 1:t + 1, 0, 0]]).mean(dim=0)       # tokens 1..k-1, t-1 (slot 0), t
+    torch.testing.assert_close(out[t, 0, 0, 0], held[0], rtol=1e-5, atol=1e-6)
+    cache.destroy()
+
+
+def test_prefill_matches_decode_steps_state(monkeypatch):
+    """The same prompt through tova_prefill and through tova_decode_steps: same victims and final
+    state on a well-separated stream, outputs equal to rounding; and grouping can be turned off."""
+    from paper_2401_06104_amd import TovaCache
+    from workloads import Stream
+    monkeypatch.setenv("TOVA_UNIT_MODE", "1")
+    spec = StreamSpec("prefill_vs_steps", L=2, B=2, H=4, H_kv=4, d=32, dtype="f32", k=16, T=120, sink="first", n_sinks=1)
+    runs = []
+    for how in ("prefill", "steps", "prefill_ungrouped"):
+        if how == "prefill_ungrouped":
+            monkeypatch.setenv("TOVA_PREFILL_GROUP", "0")
+        cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype="f32", n_splits=1)
+        c = Stream(spec, 21, device="cuda:0").chunk(0, spec.T)
+        out = torch.empty_like(c["q"])
+        ev = torch.empty(spec.T, spec.L, spec.B, dtype=torch.int32, device="cuda:0")
+        (cache.decode_steps if how == "steps" else cache.prefill)(c["q"], c["k"], c["v"], out, ev)
+        torch.cuda.synchronize()
+        runs.append((out.cpu(), ev.cpu(), cache.slot_token.cpu(), cache.K.cpu(), cache.V.cpu(), cache.tokens_seen))
+        cache.destroy()
+    for other in runs[1:]:
+        torch.testing.assert_close(runs[0][0], other[0], rtol=1e-5, atol=1e-5)   # (elements near zero: absolute)
+        for a, b in zip(runs[0][1:5], other[1:5]):
+            assert torch.equal(a, b)
+        assert runs[0][5] == other[5] == spec.T
+    assert torch.equal(runs[1][0], runs[2][0])            # ungrouped prefill IS the single-token path
+
+
 # ---- multi-step launches --------------------------------------------------------------------
 def test_multi_step_launch_matches_per_step_launches(monkeypatch):
     """tova_decode_steps runs all full-occupancy steps of a call in one launch when it can; the
