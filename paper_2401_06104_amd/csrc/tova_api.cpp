@@ -33,6 +33,7 @@ struct Resolved {
   int units, pairs, S, R, kp, NT, grid, lds, st_off, spin_limit, force_slow, persist_spin, multi_step, multi_grid, spin_env;
   int unit_mode;  // one workgroup per unit instead of one per (unit, KV head, chunk)
   int pf_C, pf_NT, pf_lds, pf_e_floats, pf_ncp;  // multi-token kernel: tokens per group (0 = not available) and its LDS plan
+  int pf_grid;                                   // ... its workgroups (decided in tova_cache_init)
   size_t uscr_off;
   float scale;
   size_t kv_bytes, state_bytes, scratch_bytes;
@@ -120,7 +121,8 @@ int resolve(const tova_config_t* c, Resolved* r) {
       const int C = cands[ci], GE = G * C;
       const bool built = (G == 1 && (C == 4 || C == 8)) || (G == 2 && (C == 2 || C == 4)) || (G == 4 && C == 2);
       if (!built) continue;
-      const int nt = nt_env ? nt_env : (k >= 512 ? 512 : 256);
+      // eight combinations need ~150 VGPRs (three waves per SIMD): small workgroups, three to a CU
+      const int nt = nt_env ? nt_env : ((k >= 512 && GE < 8) ? 512 : 256);
       const long long NC = (long long)k + C, ncp = (NC + 3) / 4 * 4;
       long long e_fl = NC * GE;
       if ((long long)(nt / 64) * GE * r->D > e_fl) e_fl = (long long)(nt / 64) * GE * r->D;
@@ -334,6 +336,25 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
     c->r.multi_grid = want < cap ? want : cap;   // never more blocks than fit at once
     if (c->r.multi_grid < 8) c->r.multi_step = 0;
   }
+  c->r.pf_grid = 0;
+  if (r.pf_C) {
+    // workgroups of the multi-token kernel: as many per CU as its LDS and registers allow (measured:
+    // 256-thread workgroups, three per CU, for eight combinations; else two of 512), never more than
+    // have a scratch area
+    const int cus = tova::device_cus();
+    int per_cu = (160 * 1024) / r.pf_lds;
+    const int cap_cu = (r.G * r.pf_C >= 8) ? 3 : 2;
+    if (per_cu > cap_cu) per_cu = cap_cu;
+    if (per_cu < 1) per_cu = 1;
+    int g = cus > 0 ? cus * per_cu : r.units;
+    if (const char* ev = std::getenv("TOVA_UNIT_GRID")) {  // tuning aid
+      const int v = std::atoi(ev);
+      if (v >= 1) g = v;
+    }
+    if (g > kPrefillMaxGrid) g = kPrefillMaxGrid;
+    if (g > r.units) g = r.units;
+    c->r.pf_grid = g;
+  }
   if (e != hipSuccess) {
     delete c;
     return hip_fail(e, "tova_cache_init");
@@ -379,10 +400,7 @@ int tova_prefill(tova_cache_t* c, int32_t n_tokens, const void* q, const void* k
       p.q_stride = (int64_t)(q_step / r.esize); p.kv_stride = (int64_t)(kv_step / r.esize);
       p.n_chunks = n_chunks; p.units = r.units; p.H = r.H; p.H_kv = r.H_kv; p.k = r.k;
       p.n_pinned = r.n_pinned; p.t = (int32_t)c->t; p.e_floats = r.pf_e_floats; p.ncp = r.pf_ncp; p.scale = r.scale;
-      int grid = r.multi_grid > 0 ? r.multi_grid : r.units;
-      if (grid > kPrefillMaxGrid) grid = kPrefillMaxGrid;
-      if (grid > r.units) grid = r.units;
-      const tova::LaunchPlan lp{grid, r.pf_NT, r.pf_lds};
+      const tova::LaunchPlan lp{r.pf_grid, r.pf_NT, r.pf_lds};
       const hipError_t e = tova::launch_prefill(r.bf16, r.D, r.G, C, p, lp, s);
       if (e != hipSuccess) return hip_fail(e, "tova_prefill launch");
       c->t += m;

@@ -102,7 +102,82 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
   float m[GE], Z[GE];
 #pragma unroll
   for (int ge = 0; ge < GE; ++ge) m[ge] = -INFINITY;
-  {
+  if constexpr (Ge::MFMA_K) {
+    // Matrix-core logit pass (bf16, 8 combinations): v_mfma_f32_16x16x32_bf16 contracts 32 elements
+    // of d for 16 candidate rows (A: lane l holds row l % 16, eight consecutive elements) against 16
+    // (token, head) columns (B: lane l holds column l % 16, the same eight elements; columns >= GE
+    // are zero).  MFMA kk takes the 16-byte chunk kk * 4 + l / 16 of a row; result register r of
+    // lane l is the logit of row (l / 16) * 4 + r for column l % 16.
+    constexpr int KK = D / 32;
+    constexpr int UM = 2;  // 16-row tiles per register buffer
+    const int r16 = lane & 15, c4 = lane >> 4;
+    V16 qm[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      qm[kk] = V16{{0u, 0u, 0u, 0u}};
+      if (r16 < GE)
+        qm[kk] = *reinterpret_cast<const V16*>(qb0 + (size_t)(r16 / G) * p.q_stride + (r16 % G) * D + (kk * 4 + c4) * 8);
+    }
+    float mh = -INFINITY;  // running maximum of column r16 over the rows this lane sees
+    auto load_tile = [&](V16(&dst)[UM][KK], int base) {
+#pragma unroll
+      for (int u = 0; u < UM; ++u) {
+        const int j = base + u * 16 + r16;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) dst[u][kk] = V16{{0u, 0u, 0u, 0u}};
+        if (j < k) {
+          const T* row = Kb + (size_t)j * D;
+#pragma unroll
+          for (int kk = 0; kk < KK; ++kk) dst[u][kk] = *reinterpret_cast<const V16*>(row + (kk * 4 + c4) * 8);
+        }
+      }
+    };
+    // rows row0 .. row0 + 15 of the candidate list; `own`: they are the group's own tokens 0 .. 15
+    auto logits16 = [&](const V16(&a)[KK], int row0, int nvalid, bool own) {
+      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[kk]),
+                                                      __builtin_bit_cast(bf16x8_t, qm[kk]), acc, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int j = row0 + c4 * 4 + r;
+        float l2 = acc[r] * scale2;
+        if (own && r16 / G < c4 * 4 + r) l2 = -INFINITY;  // a token does not see a later one
+        if (r16 < GE && j < nvalid) {
+          mh = fmaxf(mh, l2);
+          e_lds[j * GE + r16] = l2;
+        }
+      }
+    };
+    constexpr int TILE = 16 * UM;
+    const int stride = nw * TILE;
+    int base = wave * TILE;
+    V16 bufA[UM][KK], bufB[UM][KK];
+    load_tile(bufA, base);
+    if (wave == nw - 1) {  // the group's own tokens as rows 0 .. C-1 of an otherwise empty tile
+      V16 kn[KK];
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        kn[kk] = V16{{0u, 0u, 0u, 0u}};
+        if (r16 < C) kn[kk] = *reinterpret_cast<const V16*>(knew0 + (size_t)r16 * p.kv_stride + (kk * 4 + c4) * 8);
+      }
+      logits16(kn, k, k + C, true);
+    }
+    while (base < k) {
+      load_tile(bufB, base + stride);
+#pragma unroll
+      for (int u = 0; u < UM; ++u) logits16(bufA[u], base + u * 16, k, false);
+      base += stride;
+      if (base >= k) break;
+      load_tile(bufA, base + stride);
+#pragma unroll
+      for (int u = 0; u < UM; ++u) logits16(bufB[u], base + u * 16, k, false);
+      base += stride;
+    }
+#pragma unroll
+    for (int ge = 0; ge < GE; ++ge) m[ge] = (ge == r16) ? mh : -INFINITY;
+  } else {
     const int lk = lane % LK;
     const int rk = lane / LK;
     V16 qf[GE][CK];
@@ -320,22 +395,33 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
   // w of candidate `cand` for every query head of token i, handed to `sink(hq, w)` by all lanes
   // of the calling wave (a wave per candidate; lanes split the row's elements)
   auto weights_of = [&](int i, int cand, auto&& sink) {
-    for (int h = 0; h < p.H_kv; ++h) {
-      const T* row = (cand < k) ? reinterpret_cast<const T*>(p.K) + ((size_t)(pair0 + h) * k + cand) * D
-                                : reinterpret_cast<const T*>(p.k_new) + tok_kv + (size_t)(cand - k) * p.kv_stride +
-                                      (size_t)(pair0 + h) * D;
-      float kx[EPL];
+    constexpr int HB = 8;  // KV heads whose rows are requested together (the loads are what takes time here)
+    for (int h0 = 0; h0 < p.H_kv; h0 += HB) {
+      float kx[HB][EPL];
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) kx[e] = (lane + 64 * e < D) ? elem_f32<T>(row, lane + 64 * e) : 0.f;
+      for (int hb = 0; hb < HB; ++hb) {
+        const int h = min(h0 + hb, p.H_kv - 1);
+        const T* row = (cand < k) ? reinterpret_cast<const T*>(p.K) + ((size_t)(pair0 + h) * k + cand) * D
+                                  : reinterpret_cast<const T*>(p.k_new) + tok_kv + (size_t)(cand - k) * p.kv_stride +
+                                        (size_t)(pair0 + h) * D;
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const int hq = h * G + g;
-        float part = 0.f;
+        for (int e = 0; e < EPL; ++e) kx[hb][e] = (lane + 64 * e < D) ? elem_f32<T>(row, lane + 64 * e) : 0.f;
+      }
 #pragma unroll
-        for (int e = 0; e < EPL; ++e)
-          if (lane + 64 * e < D) part = fmaf(kx[e], qs[hq * D + lane + 64 * e], part);
-        const float l2 = group_reduce<64, false>(part) * scale2;
-        sink(hq, __builtin_amdgcn_exp2f(l2 - mst[hq * C + i]));
+      for (int hb = 0; hb < HB; ++hb) {
+        const int h = h0 + hb;
+        if (h < p.H_kv) {  // wave-uniform
+#pragma unroll
+          for (int g = 0; g < G; ++g) {
+            const int hq = h * G + g;
+            float part = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e)
+              if (lane + 64 * e < D) part = fmaf(kx[hb][e], qs[hq * D + lane + 64 * e], part);
+            const float l2 = group_reduce<64, false>(part) * scale2;
+            sink(hq, __builtin_amdgcn_exp2f(l2 - mst[hq * C + i]));
+          }
+        }
       }
     }
   };

@@ -370,6 +370,20 @@ def test_prefill_groups_shape_sweep(dtype, d, H, H_kv, k, T, L, B, call, group, 
         assert all(s["mismatches"] == 0 for s in stats)
 
 
+def test_prefill_groups_config4_shape(monkeypatch):
+    """Config 4's shape per unit (32 heads, no grouping, k=4096, boosted keys): groups of 4 tokens,
+    134 KB of LDS per workgroup.  The first 4096 tokens are laid down directly; a 50-token prompt
+    follows (12 groups and a remainder of 2 tokens that goes through the single-token path)."""
+    monkeypatch.setenv("TOVA_UNIT_MODE", "1")
+    spec = spec_for("c4_llama7b_stack", L=2, B=2, T=4096 + 50)
+    units = [(0, 1), (1, 0)]
+    res = parity.run_gpu(spec, 44, units, n_splits=1, chunk_steps=50, prefill=True, use_prefill=True)
+    assert res["unit_workgroups"] == 1 and res["prefill_group"] == 4
+    parity.check_global_invariants(spec, res)
+    for s in parity.check_units(spec, 44, units, res, workers=2):
+        print(f"[parity]   {s}", flush=True)
+
+
 def test_prefill_identical_keys_evict_slot_zero(monkeypatch):
     """Exact ties inside a group: with all keys equal every candidate scores the same for every
     token, so each token must take slot 0 from its predecessor (lowest slot index, the token
