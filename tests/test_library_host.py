@@ -70,6 +70,7 @@ def test_validation_errors():
     assert not h.value
     assert lib.tova_decode_step(None, None, None, None, None, None, None) == TOVA_EINVAL
     assert lib.tova_decode_steps(None, 3, None, None, None, None, None, None) == TOVA_EINVAL
+    assert lib.tova_prefill(None, 3, None, None, None, None, None, None) == TOVA_EINVAL
     assert lib.tova_cache_destroy(None) == TOVA_EINVAL
     assert lib.tova_cache_tokens_seen(None, None) == TOVA_EINVAL
     assert lib.tova_cache_set_tokens_seen(None, 0) == TOVA_EINVAL
@@ -104,6 +105,18 @@ def test_launch_plan(c, expect_S):
     assert st >= lay.slot_token_offset + 4 * c.n_layers * c.batch * k
     assert lay.slot_token_offset + 4 * c.n_layers * c.batch * k <= lay.error_flag_offset <= st - 4
     assert lay.slot_token_offset >= 4 * c.n_layers * c.batch
+
+
+@pytest.mark.parametrize("c,unit,group", [
+    (cfg(L=32, B=64, k=4096, H=32, Hkv=32, d=128, dt=TOVA_BF16), 1, 4),   # config 4: 4 tokens' logits fill a CU's LDS
+    (cfg(L=32, B=64, k=1024, H=32, Hkv=8, d=128, dt=TOVA_BF16), 1, 2),    # 4 heads per KV head: 2 tokens = 8 combinations
+    (cfg(L=8, B=64, k=1024, H=32, Hkv=32, d=128, dt=TOVA_BF16), 1, 8),
+    (cfg(L=32, B=16, k=4096, H=32, Hkv=4, d=128, dt=TOVA_BF16), 1, 0),    # 8 heads per KV head: no room for a second token
+    (cfg(B=64, k=1024, H=32, Hkv=8, d=128, dt=TOVA_BF16), 0, 0),          # 64 units: the hand-off form, token by token
+])
+def test_prompt_groups_in_the_plan(c, unit, group):
+    lay = tova_cache_layout(c)
+    assert lay.unit_workgroups == unit and lay.prefill_group == group
 
 
 def test_forced_splits_are_normalised():
