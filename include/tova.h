@@ -148,11 +148,12 @@ int tova_decode_steps(tova_cache_t* cache, int32_t n_steps, const void* q, const
  * cache (K and V are read once per group instead of once per token).  A later token of a group is
  * corrected for what the earlier ones removed, and the victim is found among the few candidates
  * whose score bounds allow it, from scores recomputed exactly; outputs and victims agree with
- * tova_decode_steps to rounding (different summation order).  Grouping needs the
- * workgroup-per-unit form (layout: unit_workgroups), a full cache and 1, 2 or 4 query heads per
- * KV head; whatever does not meet that (the fill phase, a remainder shorter than a group, other
- * shapes) is processed token by token through tova_decode_steps.  TOVA_PREFILL_GROUP=0 in the
- * environment turns grouping off. */
+ * tova_decode_steps to rounding (different summation order).  While the cache still has room the
+ * groups simply append their tokens.  Grouping needs the workgroup-per-unit form (layout:
+ * unit_workgroups) and 1, 2 or 4 query heads per KV head; whatever does not meet that (a
+ * remainder shorter than a group, the last rows before the cache is full, other shapes) is
+ * processed token by token through tova_decode_steps.  TOVA_PREFILL_GROUP=0 in the environment
+ * turns grouping off. */
 int tova_prefill(tova_cache_t* cache, int32_t n_tokens, const void* q, const void* k_new,
                  const void* v_new, void* out, int32_t* evicted, void* hip_stream);
 

@@ -386,17 +386,19 @@ int tova_prefill(tova_cache_t* c, int32_t n_tokens, const void* q, const void* k
     void* oi = static_cast<char*>(out) + (size_t)i * q_step;
     int32_t* ei = evicted ? evicted + (size_t)i * r.units : nullptr;
     int32_t m = n_tokens - i;
-    if (c->t < r.k) {
-      // while the multi-state fills nothing is removed: token by token (App. B: early return)
-      if (m > r.k - c->t) m = (int32_t)(r.k - c->t);
-    } else if (C >= 2 && m >= C) {
+    const bool filling = c->t < r.k;
+    if (filling && m > r.k - c->t) m = (int32_t)(r.k - c->t);  // (App. B: nothing is removed while there is room)
+    if (C >= 2 && m >= C) {
       const int32_t n_chunks = m / C;
       m = n_chunks * C;
       tova::PrefillParams p;
       p.q = qi; p.k_new = ki; p.v_new = vi; p.out = oi; p.evicted = ei;
       p.K = c->kv; p.V = c->kv + r.v_off;
+      p.occupancy = reinterpret_cast<int32_t*>(c->state + r.occ_off);
       p.slot_token = reinterpret_cast<int32_t*>(c->state + r.slot_off);
       p.uscr = reinterpret_cast<float*>(c->scratch + r.uscr_off);
+      p.filling = filling ? 1 : 0;
+      p.n0 = (int32_t)(filling ? c->t : r.k);
       p.q_stride = (int64_t)(q_step / r.esize); p.kv_stride = (int64_t)(kv_step / r.esize);
       p.n_chunks = n_chunks; p.units = r.units; p.H = r.H; p.H_kv = r.H_kv; p.k = r.k;
       p.n_pinned = r.n_pinned; p.t = (int32_t)c->t; p.e_floats = r.pf_e_floats; p.ncp = r.pf_ncp; p.scale = r.scale;

@@ -52,8 +52,8 @@ struct StepParams {
   float scale;
 };
 
-// Arguments of one launch of the multi-token kernel (groups of C tokens of a prompt, cache full,
-// one workgroup per unit).
+// Arguments of one launch of the multi-token kernel (groups of C tokens of a prompt, one
+// workgroup per unit; either the cache is full, or it is filling and has room for every group).
 struct PrefillParams {
   const void* q;       // [n_chunks * C][units][H][d]   first token of the launch
   const void* k_new;   // [n_chunks * C][units][H_kv][d]
@@ -62,8 +62,12 @@ struct PrefillParams {
   int32_t* evicted;    // [n_chunks * C][units] or null
   void* K;             // [units][H_kv][k][d]
   void* V;
+  int32_t* occupancy;  // [units]
   int32_t* slot_token; // [units][k]
   float* uscr;         // [grid][H][C][d] fp32: unmasked PV sums of the unit a workgroup is at
+  int32_t filling;     // the multi-state is not full and stays within capacity during this launch:
+                       // groups only append their tokens (n0 = rows cached when the launch starts)
+  int32_t n0;
   int64_t q_stride, kv_stride;  // elements between consecutive tokens of q / out and of k_new / v_new
   int32_t n_chunks;    // groups of C tokens in this launch
   int32_t units, H, H_kv, k;

@@ -23,8 +23,12 @@
 //                     out_i = (U_i - sum_{e in E_i} w_i[e] V[e]) / Z'_i
 //   commit            tokens that still hold a slot at the end are stored there.
 //
+// While the multi-state still has room (App. B: nothing is removed while num_kv <= cache_max_size)
+// a group is plain causal attention over the cached rows and its own tokens: pass A, out = U / Z,
+// and the tokens take the next free slots.
+//
 // One workgroup per (layer, sequence) unit, KV heads in turn (the form of the single-token kernel
-// for many units): nothing is exchanged between workgroups.  Cache full, one chunk per KV head.
+// for many units): nothing is exchanged between workgroups.  One chunk per KV head.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -64,7 +68,7 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
   float* big = small + kSmallFloats;
   const int nt = blockDim.x;
   const int nw = nt >> 6;
-  const int k = p.k, NC = p.k + C, H = p.H, ncp = p.ncp;
+  const int k = p.k, H = p.H, ncp = p.ncp;
   float* e_lds = big;               // [NC][GE] logits, then exp values; reduction area; resolution buffers
   float* t_lds = big + p.e_floats;  // [C][ncp] tentative scores
   float* mst = t_lds + C * ncp;     // [H][C] maxima (log2 domain)
@@ -80,6 +84,10 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
   for (int ch = 0; ch < p.n_chunks; ++ch) {
   for (int unit = blockIdx.x; unit < p.units; unit += gridDim.x) {
   const int pair0 = unit * p.H_kv;
+  // rows cached when the group starts: k once the multi-state is full; while it fills (App. B: nothing
+  // is removed while num_kv <= cache_max_size) the groups simply append their tokens
+  const int n = p.filling ? p.n0 + ch * C : k;
+  const int NC = n + C;  // candidates: the cached rows, then the group's own tokens
   const size_t tok_q = (size_t)ch * C * p.q_stride;    // element offset of the group's first token in q / out
   const size_t tok_kv = (size_t)ch * C * p.kv_stride;  // ... in k_new / v_new
 
@@ -125,7 +133,7 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
         const int j = base + u * 16 + r16;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) dst[u][kk] = V16{{0u, 0u, 0u, 0u}};
-        if (j < k) {
+        if (j < n) {
           const T* row = Kb + (size_t)j * D;
 #pragma unroll
           for (int kk = 0; kk < KK; ++kk) dst[u][kk] = *reinterpret_cast<const V16*>(row + (kk * 4 + c4) * 8);
@@ -162,17 +170,17 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
         kn[kk] = V16{{0u, 0u, 0u, 0u}};
         if (r16 < C) kn[kk] = *reinterpret_cast<const V16*>(knew0 + (size_t)r16 * p.kv_stride + (kk * 4 + c4) * 8);
       }
-      logits16(kn, k, k + C, true);
+      logits16(kn, n, n + C, true);
     }
-    while (base < k) {
+    while (base < n) {
       load_tile(bufB, base + stride);
 #pragma unroll
-      for (int u = 0; u < UM; ++u) logits16(bufA[u], base + u * 16, k, false);
+      for (int u = 0; u < UM; ++u) logits16(bufA[u], base + u * 16, n, false);
       base += stride;
-      if (base >= k) break;
+      if (base >= n) break;
       load_tile(bufA, base + stride);
 #pragma unroll
-      for (int u = 0; u < UM; ++u) logits16(bufB[u], base + u * 16, k, false);
+      for (int u = 0; u < UM; ++u) logits16(bufB[u], base + u * 16, n, false);
       base += stride;
     }
 #pragma unroll
@@ -193,7 +201,7 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
         const int j = base + u * RK + rk;
 #pragma unroll
         for (int c = 0; c < CK; ++c) dst[u][c] = V16{{0u, 0u, 0u, 0u}};
-        if (j < k) {
+        if (j < n) {
           const T* row = Kb + (size_t)j * D;
 #pragma unroll
           for (int c = 0; c < CK; ++c) dst[u][c] = *reinterpret_cast<const V16*>(row + (c * LK + lk) * VEC);
@@ -215,7 +223,7 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
         const int j = base + u * RK + rk;
         float l2[GE];
         logits_of(src[u], l2);
-        if (j < k) {
+        if (j < n) {
 #pragma unroll
           for (int ge = 0; ge < GE; ++ge) m[ge] = fmaxf(m[ge], l2[ge]);
           if (lk == 0) {
@@ -230,7 +238,7 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
     int base = wave * TILE;
     V16 bufA[UK][CK], bufB[UK][CK];
     load_tile(bufA, base);
-    if (wave == nw - 1) {  // the group's own tokens as candidates k .. k + C - 1 (wave-uniform)
+    if (wave == nw - 1) {  // the group's own tokens as candidates n .. n + C - 1 (wave-uniform)
       for (int i2 = 0; i2 < C; ++i2) {
         V16 kn[CK];
 #pragma unroll
@@ -245,15 +253,15 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
         }
         if (lane == 0) {
 #pragma unroll
-          for (int ge = 0; ge < GE; ++ge) e_lds[(k + i2) * GE + ge] = l2[ge];
+          for (int ge = 0; ge < GE; ++ge) e_lds[(n + i2) * GE + ge] = l2[ge];
         }
       }
     }
-    while (base < k) {
+    while (base < n) {
       load_tile(bufB, base + stride);
       compute_tile(bufA, base);
       base += stride;
-      if (base >= k) break;
+      if (base >= n) break;
       load_tile(bufA, base + stride);
       compute_tile(bufB, base);
       base += stride;
@@ -270,7 +278,7 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
     for (int u = 0; u < UV; ++u) {
       const int j = base + u * RV + rv;
       dst[u] = V16{{0u, 0u, 0u, 0u}};
-      if (j < k) dst[u] = *reinterpret_cast<const V16*>(Vb + (size_t)j * D + lv * VEC);
+      if (j < n) dst[u] = *reinterpret_cast<const V16*>(Vb + (size_t)j * D + lv * VEC);
     }
   };
   V16 vA[UV], vB[UV];
@@ -302,7 +310,7 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
         float a = 0.f;
 #pragma unroll
         for (int g = 0; g < G; ++g) a = fmaf(e_lds[c * GE + i * G + g], rz[i * G + g], a);
-        t_lds[i * ncp + c] = (kvh == 0) ? a : t_lds[i * ncp + c] + a;
+        if (!p.filling) t_lds[i * ncp + c] = (kvh == 0) ? a : t_lds[i * ncp + c] + a;
       }
     }
 #pragma unroll
@@ -335,7 +343,7 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
       const int j = base + u * RV + rv;
       float w[GE];
 #pragma unroll
-      for (int ge = 0; ge < GE; ++ge) w[ge] = (j < k) ? e_lds[j * GE + ge] : 0.f;
+      for (int ge = 0; ge < GE; ++ge) w[ge] = (j < n) ? e_lds[j * GE + ge] : 0.f;
       accumulate(src[u], w);
     }
   };
@@ -344,15 +352,15 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
       const V16 vn = *reinterpret_cast<const V16*>(vnew0 + (size_t)i2 * p.kv_stride + lv * VEC);
       float w[GE];
 #pragma unroll
-      for (int ge = 0; ge < GE; ++ge) w[ge] = (rv == 0) ? e_lds[(k + i2) * GE + ge] : 0.f;
+      for (int ge = 0; ge < GE; ++ge) w[ge] = (rv == 0) ? e_lds[(n + i2) * GE + ge] : 0.f;
       accumulate(vn, w);
     }
   }
-  while (basev < k) {
+  while (basev < n) {
     load_vtile(vB, basev + stridev);
     compute_vtile(vA, basev);
     basev += stridev;
-    if (basev >= k) break;
+    if (basev >= n) break;
     load_vtile(vA, basev + stridev);
     compute_vtile(vB, basev);
     basev += stridev;
@@ -428,7 +436,21 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
   // slot index a candidate stands for when scores tie (the token at hand counts as index k)
   auto position = [&](int i, int cand) { return cand < k ? cand : (cand == k + i ? k : pos[cand - k]); };
 
-  for (int i = 0; i < C; ++i) {
+  if (p.filling) {
+    // nothing is removed: out = U / Z, the tokens take the next free slots
+    for (int x = tid; x < C * H * D; x += nt) {
+      const int i = x / (H * D), y = x - i * (H * D), hq = y / D;
+      T* outi = reinterpret_cast<T*>(p.out) + tok_q + (size_t)i * p.q_stride + (size_t)unit * H * D;
+      E::store(outi + y, ublk[((size_t)hq * C + i) * D + (y - hq * D)] / zst[hq * C + i]);
+    }
+    if (tid < C) {
+      pos[tid] = n + tid;
+      if (evp) evp[(size_t)tid * p.units + unit] = -1;
+    }
+    if (tid == 0) p.occupancy[unit] = n + C;
+    __syncthreads();
+  }
+  for (int i = 0; i < C && !p.filling; ++i) {
     const T* qi = reinterpret_cast<const T*>(p.q) + tok_q + (size_t)i * p.q_stride + (size_t)unit * H * D;
     for (int x = tid; x < H * D; x += nt) qs[x] = elem_f32<T>(qi, x);
     __syncthreads();
