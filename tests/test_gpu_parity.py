@@ -384,6 +384,29 @@ def test_prefill_groups_config4_shape(monkeypatch):
         print(f"[parity]   {s}", flush=True)
 
 
+@pytest.mark.parametrize("variant", ["pinned", "per_head"])
+def test_prefill_variants(variant, monkeypatch):
+    """TOVA+i and TOVA-head (App. A) for prompts."""
+    monkeypatch.setenv("TOVA_UNIT_MODE", "1")
+    k, H, H_kv = 60, 8, 4
+    spec = StreamSpec(f"prefill_{variant}", L=2, B=3, H=H, H_kv=H_kv, d=64, dtype="bf16", k=k, T=k + 200)
+    if variant == "pinned":
+        units = [(0, 0), (1, 2)]
+        res = parity.run_gpu(spec, 35, units, n_splits=1, n_pinned=3, chunk_steps=97, use_prefill=True)
+        assert res["prefill_group"] == 4
+        parity.check_global_invariants(spec, res)
+        assert (res["slot_token"][:, :, :3] == torch.arange(3).numpy()).all()
+        assert (res["evicted"][k:] >= 3).all()
+        parity.check_units(spec, 35, units, res, workers=2, n_pinned=3)
+    else:
+        view = spec.replace(B=spec.B * H_kv, H=H // H_kv, H_kv=1)
+        units = [(0, 0), (0, H_kv - 1), (1, view.B - 1)]
+        res = parity.run_gpu(spec, 45, units, n_splits=1, per_head=True, chunk_steps=97, use_prefill=True)
+        assert res["prefill_group"] == 4
+        parity.check_global_invariants(view, res)
+        parity.check_units(view, 45, units, res, workers=3)
+
+
 def test_prefill_identical_keys_evict_slot_zero(monkeypatch):
     """Exact ties inside a group: with all keys equal every candidate scores the same for every
     token, so each token must take slot 0 from its predecessor (lowest slot index, the token
