@@ -217,7 +217,8 @@ int resolve(const tova_config_t* c, Resolved* r) {
   r->slow_off = off; off += round_up((size_t)r->pairs * S * 4, kAlign);
   r->pstate_off = off; off += round_up((size_t)r->units * 8, kAlign);
   r->cnt_bytes = off;
-  r->sg_off = off; off += round_up((size_t)r->pairs * r->kp * 4, kAlign);
+  r->sg_off = off;
+  if (!r->unit_mode) off += round_up((size_t)r->pairs * r->kp * 4, kAlign);  // (a workgroup per unit keeps the scores in LDS)
   r->escr_off = r->stats_off = r->accp_off = off;
   if (S > 1) {
     r->escr_off = off; off += round_up((size_t)r->pairs * r->kp * G * 4, kAlign);
