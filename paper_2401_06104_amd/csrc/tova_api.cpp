@@ -121,14 +121,21 @@ int resolve(const tova_config_t* c, Resolved* r) {
       const int C = cands[ci], GE = G * C;
       const bool built = (G == 1 && (C == 4 || C == 8)) || (G == 2 && (C == 2 || C == 4)) || (G == 4 && C == 2);
       if (!built) continue;
-      // eight combinations need ~150 VGPRs (three waves per SIMD): small workgroups, three to a CU
-      const int nt = nt_env ? nt_env : ((k >= 512 && GE < 8) ? 512 : 256);
+      // eight combinations need ~150 VGPRs (three waves per SIMD): workgroups of 256 threads, up to
+      // three to a CU (measured better than fewer, larger ones) -- unless the LDS leaves room for
+      // one workgroup only, which then has 512 threads
       const long long NC = (long long)k + C, ncp = (NC + 3) / 4 * 4;
-      long long e_fl = NC * GE;
-      if ((long long)(nt / 64) * GE * r->D > e_fl) e_fl = (long long)(nt / 64) * GE * r->D;
-      if ((long long)r->H * r->D + NC > e_fl) e_fl = (long long)r->H * r->D + NC;
-      e_fl = (e_fl + 3) / 4 * 4;
-      const long long tot = kSmallFloats + e_fl + C * ncp + 2LL * r->H * C + r->H + (long long)C * r->H;
+      int nt = 0;
+      long long e_fl = 0, tot = 0;
+      for (int pass = 0; pass < 2; ++pass) {
+        nt = nt_env ? nt_env : (GE < 8 ? (k >= 512 ? 512 : 256) : (pass == 0 ? 256 : 512));
+        e_fl = NC * GE;
+        if ((long long)(nt / 64) * GE * r->D > e_fl) e_fl = (long long)(nt / 64) * GE * r->D;
+        if ((long long)r->H * r->D + NC > e_fl) e_fl = (long long)r->H * r->D + NC;
+        e_fl = (e_fl + 3) / 4 * 4;
+        tot = kSmallFloats + e_fl + C * ncp + 2LL * r->H * C + r->H + (long long)C * r->H;
+        if (nt_env || GE < 8 || (160 * 1024) / (tot * 4) >= 2) break;
+      }
       if (tot * 4 <= kMaxLdsBytesUnit) {
         r->pf_C = C; r->pf_NT = nt; r->pf_lds = (int)(tot * 4); r->pf_e_floats = (int)e_fl; r->pf_ncp = (int)ncp;
       }
