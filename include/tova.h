@@ -150,7 +150,9 @@ int tova_decode_steps(tova_cache_t* cache, int32_t n_steps, const void* q, const
  * whose score bounds allow it, from scores recomputed exactly; outputs and victims agree with
  * tova_decode_steps to rounding (different summation order).  While the cache still has room the
  * groups simply append their tokens.  Grouping needs the workgroup-per-unit form (layout:
- * unit_workgroups) and 1, 2 or 4 query heads per KV head; whatever does not meet that (a
+ * unit_workgroups), 1, 2 or 4 query heads per KV head and a capacity of at least 8 groups (the
+ * corrections stay exact to rounding only while what a group removes is a small part of the
+ * multi-state); whatever does not meet that (a
  * remainder shorter than a group, the last rows before the cache is full, other shapes) is
  * processed token by token through tova_decode_steps.  TOVA_PREFILL_GROUP=0 in the environment
  * turns grouping off. */

@@ -121,6 +121,10 @@ int resolve(const tova_config_t* c, Resolved* r) {
       const int C = cands[ci], GE = G * C;
       const bool built = (G == 1 && (C == 4 || C == 8)) || (G == 2 && (C == 2 || C == 4)) || (G == 4 && C == 2);
       if (!built) continue;
+      // The corrections subtract what the group's earlier tokens removed from sums over everything:
+      // that keeps full precision only while the removed candidates carry a small part of the
+      // weight, i.e. while a group is small against the multi-state.
+      if (k < 8 * C) continue;
       // eight combinations need ~150 VGPRs (three waves per SIMD): workgroups of 256 threads, up to
       // three to a CU (measured better than fewer, larger ones) -- unless the LDS leaves room for
       // one workgroup only, which then has 512 threads

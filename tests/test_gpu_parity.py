@@ -339,9 +339,10 @@ def test_unit_workgroups_multi_step_matches_per_step(monkeypatch):
 # ---- prompts: groups of tokens per pass over the cache (tova_prefill) -------------------------
 PREFILL_SWEEP = [
     # dtype, d, H, H_kv, k, T, L, B, tokens per call, expected group
-    ("f32", 32, 4, 4, 37, 150, 2, 3, 50, 8),
+    ("f32", 32, 4, 4, 37, 150, 2, 3, 50, 4),          # (groups stay below an eighth of the capacity)
+    ("f32", 32, 4, 4, 70, 190, 1, 2, 190, 8),
     ("f32", 64, 8, 4, 100, 260, 1, 2, 37, 4),         # calls that are no multiple of the group
-    ("f32", 128, 4, 2, 1, 40, 1, 1, 40, 4),            # capacity 1
+    ("f32", 128, 4, 2, 1, 40, 1, 1, 40, 0),            # capacity 1: token by token
     ("f32", 128, 8, 2, 64, 200, 1, 2, 64, 2),
     ("bf16", 128, 32, 8, 300, 520, 1, 3, 128, 2),
     ("bf16", 128, 8, 8, 1025, 1300, 1, 2, 256, 8),
@@ -413,7 +414,7 @@ def test_prefill_identical_keys_evict_slot_zero(monkeypatch):
     itself last) -- the bounds leave every candidate in and the exact scores must tie bit for bit."""
     from paper_2401_06104_amd import TovaCache
     monkeypatch.setenv("TOVA_UNIT_MODE", "1")
-    L, B, H, H_kv, d, k, T = 1, 2, 4, 2, 64, 10, 58
+    L, B, H, H_kv, d, k, T = 1, 2, 4, 2, 64, 40, 88
     g = torch.Generator().manual_seed(3)
     q = torch.randn(T, L, B, H, d, generator=g).cuda()
     kk = torch.randn(1, 1, 1, 1, d, generator=g).expand(T, L, B, H_kv, d).contiguous().cuda()
@@ -440,7 +441,7 @@ def test_prefill_matches_decode_steps_state(monkeypatch):
     from paper_2401_06104_amd import TovaCache
     from workloads import Stream
     monkeypatch.setenv("TOVA_UNIT_MODE", "1")
-    spec = StreamSpec("prefill_vs_steps", L=2, B=2, H=4, H_kv=4, d=32, dtype="f32", k=16, T=120, sink="first", n_sinks=1)
+    spec = StreamSpec("prefill_vs_steps", L=2, B=2, H=4, H_kv=4, d=32, dtype="f32", k=40, T=140, sink="first", n_sinks=1)
     runs = []
     for how in ("prefill", "steps", "prefill_ungrouped"):
         if how == "prefill_ungrouped":
@@ -459,6 +460,48 @@ def test_prefill_matches_decode_steps_state(monkeypatch):
             assert torch.equal(a, b)
         assert runs[0][5] == other[5] == spec.T
     assert torch.equal(runs[1][0], runs[2][0])            # ungrouped prefill IS the single-token path
+
+
+def test_prefill_random_shapes_match_decode_steps(monkeypatch):
+    """Eighty random small shapes, the prompt cut into calls at random places: tova_prefill must give
+    tova_decode_steps' victims and final state, and its outputs within the tolerance.  (A difference in
+    the victims would be looked at through the oracle's near-tie rule; none occurs on these streams.)"""
+    import random
+    from paper_2401_06104_amd import TovaCache
+    monkeypatch.setenv("TOVA_UNIT_MODE", "1")
+    rng = random.Random(5)
+    grouped = 0
+    for case in range(80):
+        d = rng.choice([32, 64, 128]); G = rng.choice([1, 2, 4]); H_kv = rng.choice([1, 2, 3, 4]); H = G * H_kv
+        k = rng.choice([1, 5, 16, 21, 33, 40, 64, 77, 130]); T = k + rng.randint(5, 90)
+        L = rng.choice([1, 2]); B = rng.choice([1, 2, 3]); dtype = rng.choice(["f32", "bf16"])
+        pinned = rng.choice([0, 0, 0, 1, 2]) if k > 2 else 0
+        dt = torch.float32 if dtype == "f32" else torch.bfloat16
+        g = torch.Generator().manual_seed(case * 7 + 1)
+        q = torch.randn(T, L, B, H, d, generator=g).to(dt).cuda()
+        kk = torch.randn(T, L, B, H_kv, d, generator=g).to(dt).cuda()
+        vv = torch.randn(T, L, B, H_kv, d, generator=g).to(dt).cuda()
+        runs = []
+        for how in ("steps", "prefill"):
+            cache = TovaCache(L, B, k, H, H_kv, d, dtype=dtype, n_splits=1, n_pinned=pinned)
+            out = torch.empty_like(q)
+            ev = torch.empty(T, L, B, dtype=torch.int32, device="cuda")
+            if how == "steps":
+                cache.decode_steps(q, kk, vv, out, ev)
+            else:
+                cuts = sorted(set([0, T] + [rng.randint(1, T - 1) for _ in range(rng.randint(0, 3))]))
+                for a, b in zip(cuts[:-1], cuts[1:]):
+                    cache.prefill(q[a:b], kk[a:b], vv[a:b], out[a:b], ev[a:b])
+                grouped += int(cache.layout.prefill_group > 1)
+            torch.cuda.synchronize()
+            runs.append((out.float().cpu(), ev.cpu(), cache.slot_token.cpu().clone()))
+            cache.destroy()
+        what = f"case {case}: d={d} G={G} H_kv={H_kv} k={k} T={T} L={L} B={B} {dtype} pinned={pinned}"
+        assert torch.equal(runs[0][1], runs[1][1]), "victims differ, " + what
+        assert torch.equal(runs[0][2], runs[1][2]), "final state differs, " + what
+        err = ((runs[0][0] - runs[1][0]).abs().amax(dim=-1) / runs[0][0].abs().amax(dim=-1).clamp_min(1e-30)).max().item()
+        assert err <= 2 * parity.OUT_TOL[dtype], f"outputs differ by {err:.2e}, " + what     # (each is within OUT_TOL of the oracle)
+    assert grouped >= 40
 
 
 # ---- multi-step launches --------------------------------------------------------------------
