@@ -270,6 +270,49 @@ def test_unit_workgroups_wide_groups_large_capacity(monkeypatch):
         print(f"[parity]   {s}", flush=True)
 
 
+def test_unit_workgroups_random_shapes_match_the_hand_off_form(monkeypatch):
+    """Sixty random small shapes through both forms (automatic split count in the hand-off form):
+    the victims and the final state must be identical and the outputs equal to rounding -- bit for
+    bit when the hand-off form also runs one chunk per KV head (same arithmetic, same head order)."""
+    import random
+    from paper_2401_06104_amd import TovaCache
+    rng = random.Random(9)
+    for case in range(60):
+        d = rng.choice([32, 64, 128]); G = rng.choice([1, 2, 4, 8]); H_kv = rng.choice([1, 2, 3, 4]); H = G * H_kv
+        k = rng.choice([1, 2, 7, 16, 33, 64, 100, 257]); T = k + rng.randint(5, 70)
+        L = rng.choice([1, 2]); B = rng.choice([1, 2, 5]); dtype = rng.choice(["f32", "bf16"])
+        splits = rng.choice([1, 1, 0, 3])
+        pinned = rng.choice([0, 0, 1]) if k > 2 else 0
+        dt = torch.float32 if dtype == "f32" else torch.bfloat16
+        g = torch.Generator().manual_seed(case * 11 + 3)
+        q = torch.randn(T, L, B, H, d, generator=g).to(dt).cuda()
+        kk = torch.randn(T, L, B, H_kv, d, generator=g).to(dt).cuda()
+        vv = torch.randn(T, L, B, H_kv, d, generator=g).to(dt).cuda()
+        runs = []
+        for unit_form in (True, False):
+            monkeypatch.setenv("TOVA_UNIT_MODE", "1" if unit_form else "0")
+            cache = TovaCache(L, B, k, H, H_kv, d, dtype=dtype, n_splits=1 if unit_form else splits, n_pinned=pinned)
+            assert bool(cache.layout.unit_workgroups) == unit_form
+            out = torch.empty_like(q)
+            ev = torch.empty(T, L, B, dtype=torch.int32, device="cuda")
+            cut = rng.randint(1, T - 1)
+            cache.decode_steps(q[:cut], kk[:cut], vv[:cut], out[:cut], ev[:cut])
+            cache.decode_steps(q[cut:], kk[cut:], vv[cut:], out[cut:], ev[cut:])
+            torch.cuda.synchronize()
+            one_chunk = cache.layout.n_splits == 1
+            runs.append((out.cpu(), ev.cpu(), cache.slot_token.cpu().clone(), cache.K.cpu().clone(), one_chunk))
+            cache.destroy()
+        what = f"case {case}: d={d} G={G} H_kv={H_kv} k={k} T={T} L={L} B={B} {dtype} splits={splits} pinned={pinned}"
+        assert torch.equal(runs[0][1], runs[1][1]), "victims differ, " + what
+        assert torch.equal(runs[0][2], runs[1][2]) and torch.equal(runs[0][3], runs[1][3]), "final state differs, " + what
+        if runs[1][4]:
+            assert torch.equal(runs[0][0], runs[1][0]), "outputs differ, " + what
+        else:
+            a, b = runs[0][0].float(), runs[1][0].float()
+            err = ((a - b).abs().amax(dim=-1) / a.abs().amax(dim=-1).clamp_min(1e-30)).max().item()
+            assert err <= 2 * parity.OUT_TOL[dtype], f"outputs differ by {err:.2e}, " + what
+
+
 def test_unit_workgroups_are_the_default_for_many_units():
     """256 units or more: chosen without being asked; several units per workgroup and step."""
     spec = StreamSpec("unit_default", L=8, B=80, H=8, H_kv=4, d=64, dtype="bf16", k=40, T=130, sink="first",
