@@ -291,6 +291,273 @@ struct Geo {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
+// ------------------------------------------------------------------ streaming passes
+// Both kernels stream a KV head's rows twice per token (group): once through the logit pass (K),
+// once through the PV pass (V).  A row serves NH "columns": the query heads of the KV head, or
+// (token, head) combinations of a group of prompt tokens.  Besides the `nrows` cached rows there
+// are `n_own` rows of the caller's own (the incoming token, or the group's tokens), which the
+// block's last wave takes (`own_here`, wave-uniform).
+//
+//   qp(h)        -> const T*  query vector of column h
+//   ownp(r)      -> const T*  key (value) row of own candidate r
+//   masked(h, r) -> bool      column h must not see own candidate r
+//
+// logit_pass writes the log2-domain logits l2[j][h] = scale2 * q_h . K[j] to e_lds[j * NH + h]
+// (own candidate r is row nrows + r) and leaves per-lane running maxima in m (to be block-reduced).
+
+template <typename T, int D, int NH, typename QPtr, typename OwnPtr, typename Mask>
+__device__ __forceinline__ void logit_pass(const T* Kb, int nrows, int n_own, bool own_here, QPtr&& qp,
+                                           OwnPtr&& ownp, Mask&& masked, float scale2, int lane, int wave,
+                                           int nw, float* e_lds, float (&m)[NH]) {
+  using E = Elem<T>;
+  using Ge = Geo<T, D, NH>;
+  constexpr int VEC = Ge::VEC, CK = Ge::CK, LK = Ge::LK, RK = Ge::RK, UK = Ge::UK;
+#pragma unroll
+  for (int h = 0; h < NH; ++h) m[h] = -INFINITY;
+  if constexpr (Ge::MFMA_K) {
+    // Matrix cores.  One v_mfma_f32_16x16x32_bf16 contracts 32 elements of d for 16 rows (A: lane l
+    // holds row l % 16, eight consecutive elements) against 16 columns (B: lane l holds column
+    // l % 16, the same eight elements; columns >= NH are zero); D / 32 of them cover a row.  Which
+    // eight elements a lane holds is free as long as A and B agree: MFMA kk takes the 16-byte
+    // chunk kk * 4 + l / 16, so the four lanes of a row load 64 contiguous bytes.  Result register
+    // r of lane l is the logit of row (l / 16) * 4 + r for column l % 16.
+    constexpr int KK = D / 32;
+    constexpr int UM = 2;  // 16-row tiles per register buffer
+    const int r16 = lane & 15, c4 = lane >> 4;
+    V16 qm[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      qm[kk] = V16{{0u, 0u, 0u, 0u}};
+      if (r16 < NH) qm[kk] = *reinterpret_cast<const V16*>(qp(r16) + (kk * 4 + c4) * 8);
+    }
+    float mh = -INFINITY;  // running maximum of column r16 over the rows this lane sees
+    auto load_tile = [&](V16(&dst)[UM][KK], int base) {
+#pragma unroll
+      for (int u = 0; u < UM; ++u) {
+        const int j = base + u * 16 + r16;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) dst[u][kk] = V16{{0u, 0u, 0u, 0u}};
+        if (j < nrows) {
+          const T* row = Kb + (size_t)j * D;
+#pragma unroll
+          for (int kk = 0; kk < KK; ++kk) dst[u][kk] = *reinterpret_cast<const V16*>(row + (kk * 4 + c4) * 8);
+        }
+      }
+    };
+    // rows row0 .. row0 + 15 of the candidate list; `own`: they are own candidates 0 .. 15
+    auto logits16 = [&](const V16(&a)[KK], int row0, int nvalid, bool own) {
+      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[kk]),
+                                                      __builtin_bit_cast(bf16x8_t, qm[kk]), acc, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int j = row0 + c4 * 4 + r;
+        float l2 = acc[r] * scale2;
+        if (own && masked(r16, c4 * 4 + r)) l2 = -INFINITY;
+        if (r16 < NH && j < nvalid) {
+          mh = fmaxf(mh, l2);
+          e_lds[j * NH + r16] = l2;
+        }
+      }
+    };
+    constexpr int TILE = 16 * UM;
+    const int stride = nw * TILE;
+    int base = wave * TILE;
+    V16 bufA[UM][KK], bufB[UM][KK];
+    V16 kn[KK];
+    if (own_here) {  // the own candidates as rows 0 .. n_own - 1 of an otherwise empty tile
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        kn[kk] = V16{{0u, 0u, 0u, 0u}};
+        if (r16 < n_own) kn[kk] = *reinterpret_cast<const V16*>(ownp(r16) + (kk * 4 + c4) * 8);
+      }
+    }
+    load_tile(bufA, base);
+    if (own_here) logits16(kn, nrows, nrows + n_own, true);
+    while (base < nrows) {  // two register buffers: the next tile is in flight while this one is used
+      load_tile(bufB, base + stride);
+#pragma unroll
+      for (int u = 0; u < UM; ++u) logits16(bufA[u], base + u * 16, nrows, false);
+      base += stride;
+      if (base >= nrows) break;
+      load_tile(bufA, base + stride);
+#pragma unroll
+      for (int u = 0; u < UM; ++u) logits16(bufB[u], base + u * 16, nrows, false);
+      base += stride;
+    }
+#pragma unroll
+    for (int h = 0; h < NH; ++h) m[h] = (h == r16) ? mh : -INFINITY;
+  } else {
+    // Vector ALUs.  LK adjacent lanes share a row, each holding CK 16-byte chunks of it (chunk
+    // c * LK + lane), so a wave-level load covers whole contiguous rows and the cross-lane sum per
+    // (row, column) needs log2(LK) DPP steps.
+    const int lk = lane % LK;  // position inside the row
+    const int rk = lane / LK;  // which of the RK rows of a wave pass
+    V16 qf[NH][CK];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+      const T* qh = qp(h);
+#pragma unroll
+      for (int c = 0; c < CK; ++c) qf[h][c] = *reinterpret_cast<const V16*>(qh + (c * LK + lk) * VEC);
+    }
+    auto load_tile = [&](V16(&dst)[UK][CK], int base) {
+#pragma unroll
+      for (int u = 0; u < UK; ++u) {
+        const int j = base + u * RK + rk;
+#pragma unroll
+        for (int c = 0; c < CK; ++c) dst[u][c] = V16{{0u, 0u, 0u, 0u}};
+        if (j < nrows) {
+          const T* row = Kb + (size_t)j * D;
+#pragma unroll
+          for (int c = 0; c < CK; ++c) dst[u][c] = *reinterpret_cast<const V16*>(row + (c * LK + lk) * VEC);
+        }
+      }
+    };
+    auto logits_of = [&](const V16(&row)[CK], float(&l2)[NH]) {
+#pragma unroll
+      for (int h = 0; h < NH; ++h) {
+        float a = 0.f;
+#pragma unroll
+        for (int c = 0; c < CK; ++c) a = E::dot(row[c], qf[h][c], a);
+        l2[h] = group_sum<LK>(a) * scale2;
+      }
+    };
+    auto compute_tile = [&](const V16(&src)[UK][CK], int base) {
+#pragma unroll
+      for (int u = 0; u < UK; ++u) {
+        const int j = base + u * RK + rk;
+        float l2[NH];
+        logits_of(src[u], l2);
+        if (j < nrows) {
+#pragma unroll
+          for (int h = 0; h < NH; ++h) m[h] = fmaxf(m[h], l2[h]);  // running max, per lane
+          if (lk == 0) {
+#pragma unroll
+            for (int h = 0; h < NH; ++h) e_lds[j * NH + h] = l2[h];
+          }
+        }
+      }
+    };
+    constexpr int TILE = RK * UK;  // rows per wave per buffer
+    const int stride = nw * TILE;
+    int base = wave * TILE;
+    V16 bufA[UK][CK], bufB[UK][CK];
+    load_tile(bufA, base);
+    if (own_here) {
+      for (int r = 0; r < n_own; ++r) {
+        V16 kn[CK];
+        const T* kr = ownp(r);
+#pragma unroll
+        for (int c = 0; c < CK; ++c) kn[c] = *reinterpret_cast<const V16*>(kr + (c * LK + lk) * VEC);
+        float l2[NH];
+        logits_of(kn, l2);
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+          if (masked(h, r)) l2[h] = -INFINITY;
+          m[h] = fmaxf(m[h], l2[h]);
+        }
+        if (lane == 0) {
+#pragma unroll
+          for (int h = 0; h < NH; ++h) e_lds[(nrows + r) * NH + h] = l2[h];
+        }
+      }
+    }
+    while (base < nrows) {  // two register buffers: the next tile is in flight while this one is used
+      load_tile(bufB, base + stride);
+      compute_tile(bufA, base);
+      base += stride;
+      if (base >= nrows) break;
+      load_tile(bufA, base + stride);
+      compute_tile(bufB, base);
+      base += stride;
+    }
+  }
+}
+
+// PV pass: acc[h][v] += sum_j w[j][col0 + h] * V[j][...] over the cached rows and the own candidates,
+// weights read from e_lds (stride NHT columns per candidate).  One 16-byte chunk of a row per lane
+// (LV lanes per row, RV rows per wave-level load); the caller requests the first tile early with
+// pv_first_tile (so that the V stream is in flight during the softmax barriers) and combines the RV
+// row groups and the waves afterwards.
+template <typename T, int D, int NH, int UVN>
+__device__ __forceinline__ void pv_first_tile(V16 (&vA)[UVN], const T* Vb, int nrows, int lane, int wave) {
+  using Ge = Geo<T, D, NH>;
+  constexpr int VEC = Ge::VEC, LV = Ge::LV, RV = Ge::RV, UV = Ge::UV;
+  static_assert(UVN == UV, "tile shape");
+  const int lv = lane % LV, rv = lane / LV;
+  const int base = wave * RV * UV;
+#pragma unroll
+  for (int u = 0; u < UV; ++u) {
+    const int j = base + u * RV + rv;
+    vA[u] = V16{{0u, 0u, 0u, 0u}};
+    if (j < nrows) vA[u] = *reinterpret_cast<const V16*>(Vb + (size_t)j * D + lv * VEC);
+  }
+}
+template <typename T, int D, int NH, typename OwnPtr, int UVN, int VECN>
+__device__ __forceinline__ void pv_pass(const T* Vb, int nrows, int n_own, bool own_here, OwnPtr&& ownp,
+                                        const float* e_lds, int NHT, int col0, int lane, int wave, int nw,
+                                        V16 (&vA)[UVN], float (&acc)[NH][VECN]) {
+  using E = Elem<T>;
+  using Ge = Geo<T, D, NH>;
+  constexpr int VEC = Ge::VEC, LV = Ge::LV, RV = Ge::RV, UV = Ge::UV;
+  static_assert(UVN == UV && VECN == VEC, "tile shape");
+  const int lv = lane % LV, rv = lane / LV;
+  constexpr int TILEV = RV * UV;
+  const int stridev = nw * TILEV;
+  auto load_vtile = [&](V16(&dst)[UV], int base) {
+#pragma unroll
+    for (int u = 0; u < UV; ++u) {
+      const int j = base + u * RV + rv;
+      dst[u] = V16{{0u, 0u, 0u, 0u}};
+      if (j < nrows) dst[u] = *reinterpret_cast<const V16*>(Vb + (size_t)j * D + lv * VEC);
+    }
+  };
+  auto accumulate = [&](const V16& row, const float(&w)[NH]) {
+    float vf[VEC];
+    E::unpack(row, vf);
+#pragma unroll
+    for (int h = 0; h < NH; ++h)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[h][v] = fmaf(w[h], vf[v], acc[h][v]);
+  };
+  auto compute_vtile = [&](const V16(&src)[UV], int base) {
+#pragma unroll
+    for (int u = 0; u < UV; ++u) {
+      const int j = base + u * RV + rv;
+      float w[NH];
+#pragma unroll
+      for (int h = 0; h < NH; ++h) w[h] = (j < nrows) ? e_lds[j * NHT + col0 + h] : 0.f;
+      accumulate(src[u], w);
+    }
+  };
+#pragma unroll
+  for (int h = 0; h < NH; ++h)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[h][v] = 0.f;
+  if (own_here) {  // the own candidates' value rows (first row group of the wave only)
+    for (int r = 0; r < n_own; ++r) {
+      const V16 vn = *reinterpret_cast<const V16*>(ownp(r) + lv * VEC);
+      float w[NH];
+#pragma unroll
+      for (int h = 0; h < NH; ++h) w[h] = (rv == 0) ? e_lds[(nrows + r) * NHT + col0 + h] : 0.f;
+      accumulate(vn, w);
+    }
+  }
+  V16 vB[UV];
+  int basev = wave * TILEV;
+  while (basev < nrows) {
+    load_vtile(vB, basev + stridev);
+    compute_vtile(vA, basev);
+    basev += stridev;
+    if (basev >= nrows) break;
+    load_vtile(vA, basev + stridev);
+    compute_vtile(vB, basev);
+    basev += stridev;
+  }
+}
+
 }  // namespace
 }  // namespace tova
 #endif  // TOVA_DEVICE_H

@@ -57,8 +57,7 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
   using E = Elem<T>;
   constexpr int GE = G * C;  // (token, query head) combinations served by one streamed row
   using Ge = Geo<T, D, GE>;
-  constexpr int VEC = Ge::VEC, CK = Ge::CK, LK = Ge::LK, RK = Ge::RK, UK = Ge::UK;
-  constexpr int LV = Ge::LV, RV = Ge::RV, UV = Ge::UV;
+  constexpr int VEC = Ge::VEC, LV = Ge::LV, UV = Ge::UV;
   constexpr int ROW16 = D * (int)sizeof(T) / 16;
   constexpr int EPL = (D + 63) / 64;  // elements of a row per lane in the exact recomputation
   static_assert(GE <= 8 && C <= 8, "register budget of the vector passes");
@@ -106,184 +105,20 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
   const T* vnew0 = reinterpret_cast<const T*>(p.v_new) + tok_kv + (size_t)pair * D;
   const T* qb0 = reinterpret_cast<const T*>(p.q) + tok_q + ((size_t)unit * H + (size_t)kvh * G) * D;
 
-  // ---- logits (log2 domain) of all (token, head) combinations against every candidate
+  // ---- logits (log2 domain) of all (token, head) combinations against every candidate: the n
+  //      cached rows, then the group's own tokens (a token does not see a later one)
   float m[GE], Z[GE];
-#pragma unroll
-  for (int ge = 0; ge < GE; ++ge) m[ge] = -INFINITY;
-  if constexpr (Ge::MFMA_K) {
-    // Matrix-core logit pass (bf16, 8 combinations): v_mfma_f32_16x16x32_bf16 contracts 32 elements
-    // of d for 16 candidate rows (A: lane l holds row l % 16, eight consecutive elements) against 16
-    // (token, head) columns (B: lane l holds column l % 16, the same eight elements; columns >= GE
-    // are zero).  MFMA kk takes the 16-byte chunk kk * 4 + l / 16 of a row; result register r of
-    // lane l is the logit of row (l / 16) * 4 + r for column l % 16.
-    constexpr int KK = D / 32;
-    constexpr int UM = 2;  // 16-row tiles per register buffer
-    const int r16 = lane & 15, c4 = lane >> 4;
-    V16 qm[KK];
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      qm[kk] = V16{{0u, 0u, 0u, 0u}};
-      if (r16 < GE)
-        qm[kk] = *reinterpret_cast<const V16*>(qb0 + (size_t)(r16 / G) * p.q_stride + (r16 % G) * D + (kk * 4 + c4) * 8);
-    }
-    float mh = -INFINITY;  // running maximum of column r16 over the rows this lane sees
-    auto load_tile = [&](V16(&dst)[UM][KK], int base) {
-#pragma unroll
-      for (int u = 0; u < UM; ++u) {
-        const int j = base + u * 16 + r16;
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) dst[u][kk] = V16{{0u, 0u, 0u, 0u}};
-        if (j < n) {
-          const T* row = Kb + (size_t)j * D;
-#pragma unroll
-          for (int kk = 0; kk < KK; ++kk) dst[u][kk] = *reinterpret_cast<const V16*>(row + (kk * 4 + c4) * 8);
-        }
-      }
-    };
-    // rows row0 .. row0 + 15 of the candidate list; `own`: they are the group's own tokens 0 .. 15
-    auto logits16 = [&](const V16(&a)[KK], int row0, int nvalid, bool own) {
-      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[kk]),
-                                                      __builtin_bit_cast(bf16x8_t, qm[kk]), acc, 0, 0, 0);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int j = row0 + c4 * 4 + r;
-        float l2 = acc[r] * scale2;
-        if (own && r16 / G < c4 * 4 + r) l2 = -INFINITY;  // a token does not see a later one
-        if (r16 < GE && j < nvalid) {
-          mh = fmaxf(mh, l2);
-          e_lds[j * GE + r16] = l2;
-        }
-      }
-    };
-    constexpr int TILE = 16 * UM;
-    const int stride = nw * TILE;
-    int base = wave * TILE;
-    V16 bufA[UM][KK], bufB[UM][KK];
-    load_tile(bufA, base);
-    if (wave == nw - 1) {  // the group's own tokens as rows 0 .. C-1 of an otherwise empty tile
-      V16 kn[KK];
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        kn[kk] = V16{{0u, 0u, 0u, 0u}};
-        if (r16 < C) kn[kk] = *reinterpret_cast<const V16*>(knew0 + (size_t)r16 * p.kv_stride + (kk * 4 + c4) * 8);
-      }
-      logits16(kn, n, n + C, true);
-    }
-    while (base < n) {
-      load_tile(bufB, base + stride);
-#pragma unroll
-      for (int u = 0; u < UM; ++u) logits16(bufA[u], base + u * 16, n, false);
-      base += stride;
-      if (base >= n) break;
-      load_tile(bufA, base + stride);
-#pragma unroll
-      for (int u = 0; u < UM; ++u) logits16(bufB[u], base + u * 16, n, false);
-      base += stride;
-    }
-#pragma unroll
-    for (int ge = 0; ge < GE; ++ge) m[ge] = (ge == r16) ? mh : -INFINITY;
-  } else {
-    const int lk = lane % LK;
-    const int rk = lane / LK;
-    V16 qf[GE][CK];
-#pragma unroll
-    for (int ge = 0; ge < GE; ++ge) {
-      const T* qg = qb0 + (size_t)(ge / G) * p.q_stride + (ge % G) * D;
-#pragma unroll
-      for (int c = 0; c < CK; ++c) qf[ge][c] = *reinterpret_cast<const V16*>(qg + (c * LK + lk) * VEC);
-    }
-    auto load_tile = [&](V16(&dst)[UK][CK], int base) {
-#pragma unroll
-      for (int u = 0; u < UK; ++u) {
-        const int j = base + u * RK + rk;
-#pragma unroll
-        for (int c = 0; c < CK; ++c) dst[u][c] = V16{{0u, 0u, 0u, 0u}};
-        if (j < n) {
-          const T* row = Kb + (size_t)j * D;
-#pragma unroll
-          for (int c = 0; c < CK; ++c) dst[u][c] = *reinterpret_cast<const V16*>(row + (c * LK + lk) * VEC);
-        }
-      }
-    };
-    auto logits_of = [&](const V16(&row)[CK], float(&l2)[GE]) {
-#pragma unroll
-      for (int ge = 0; ge < GE; ++ge) {
-        float a = 0.f;
-#pragma unroll
-        for (int c = 0; c < CK; ++c) a = E::dot(row[c], qf[ge][c], a);
-        l2[ge] = group_sum<LK>(a) * scale2;
-      }
-    };
-    auto compute_tile = [&](const V16(&src)[UK][CK], int base) {
-#pragma unroll
-      for (int u = 0; u < UK; ++u) {
-        const int j = base + u * RK + rk;
-        float l2[GE];
-        logits_of(src[u], l2);
-        if (j < n) {
-#pragma unroll
-          for (int ge = 0; ge < GE; ++ge) m[ge] = fmaxf(m[ge], l2[ge]);
-          if (lk == 0) {
-#pragma unroll
-            for (int ge = 0; ge < GE; ++ge) e_lds[j * GE + ge] = l2[ge];
-          }
-        }
-      }
-    };
-    constexpr int TILE = RK * UK;
-    const int stride = nw * TILE;
-    int base = wave * TILE;
-    V16 bufA[UK][CK], bufB[UK][CK];
-    load_tile(bufA, base);
-    if (wave == nw - 1) {  // the group's own tokens as candidates n .. n + C - 1 (wave-uniform)
-      for (int i2 = 0; i2 < C; ++i2) {
-        V16 kn[CK];
-#pragma unroll
-        for (int c = 0; c < CK; ++c)
-          kn[c] = *reinterpret_cast<const V16*>(knew0 + (size_t)i2 * p.kv_stride + (c * LK + lk) * VEC);
-        float l2[GE];
-        logits_of(kn, l2);
-#pragma unroll
-        for (int ge = 0; ge < GE; ++ge) {
-          if (ge / G < i2) l2[ge] = -INFINITY;  // a token does not see a later one
-          m[ge] = fmaxf(m[ge], l2[ge]);
-        }
-        if (lane == 0) {
-#pragma unroll
-          for (int ge = 0; ge < GE; ++ge) e_lds[(n + i2) * GE + ge] = l2[ge];
-        }
-      }
-    }
-    while (base < n) {
-      load_tile(bufB, base + stride);
-      compute_tile(bufA, base);
-      base += stride;
-      if (base >= n) break;
-      load_tile(bufA, base + stride);
-      compute_tile(bufB, base);
-      base += stride;
-    }
-  }
+  const bool own_here = (wave == nw - 1);  // wave-uniform
+  logit_pass<T, D, GE>(
+      Kb, n, C, own_here, [&](int ge) { return qb0 + (size_t)(ge / G) * p.q_stride + (ge % G) * D; },
+      [&](int r) { return knew0 + (size_t)r * p.kv_stride; }, [&](int ge, int r) { return ge / G < r; }, scale2,
+      lane, wave, nw, e_lds, m);
 
   // the first V tile is requested before the softmax barriers
   const int lv = lane % LV;
   const int rv = lane / LV;
-  constexpr int TILEV = RV * UV;
-  const int stridev = nw * TILEV;
-  auto load_vtile = [&](V16(&dst)[UV], int base) {
-#pragma unroll
-    for (int u = 0; u < UV; ++u) {
-      const int j = base + u * RV + rv;
-      dst[u] = V16{{0u, 0u, 0u, 0u}};
-      if (j < n) dst[u] = *reinterpret_cast<const V16*>(Vb + (size_t)j * D + lv * VEC);
-    }
-  };
-  V16 vA[UV], vB[UV];
-  int basev = wave * TILEV;
-  load_vtile(vA, basev);
+  V16 vA[UV];
+  pv_first_tile<T, D, GE>(vA, Vb, n, lane, wave);
 
   // ---- maxima, exp values, sums over all causally allowed candidates
   block_reduce<GE, true>(m, small, lane, wave, nw);
@@ -325,46 +160,8 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
 
   // ---- unmasked PV sums: U_(i,g) = sum over allowed candidates of w V
   float acc[GE][VEC];
-#pragma unroll
-  for (int ge = 0; ge < GE; ++ge)
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) acc[ge][v] = 0.f;
-  auto accumulate = [&](const V16& row, const float(&w)[GE]) {
-    float vf[VEC];
-    E::unpack(row, vf);
-#pragma unroll
-    for (int ge = 0; ge < GE; ++ge)
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) acc[ge][v] = fmaf(w[ge], vf[v], acc[ge][v]);
-  };
-  auto compute_vtile = [&](const V16(&src)[UV], int base) {
-#pragma unroll
-    for (int u = 0; u < UV; ++u) {
-      const int j = base + u * RV + rv;
-      float w[GE];
-#pragma unroll
-      for (int ge = 0; ge < GE; ++ge) w[ge] = (j < n) ? e_lds[j * GE + ge] : 0.f;
-      accumulate(src[u], w);
-    }
-  };
-  if (wave == nw - 1) {  // the group's own value rows
-    for (int i2 = 0; i2 < C; ++i2) {
-      const V16 vn = *reinterpret_cast<const V16*>(vnew0 + (size_t)i2 * p.kv_stride + lv * VEC);
-      float w[GE];
-#pragma unroll
-      for (int ge = 0; ge < GE; ++ge) w[ge] = (rv == 0) ? e_lds[(n + i2) * GE + ge] : 0.f;
-      accumulate(vn, w);
-    }
-  }
-  while (basev < n) {
-    load_vtile(vB, basev + stridev);
-    compute_vtile(vA, basev);
-    basev += stridev;
-    if (basev >= n) break;
-    load_vtile(vA, basev + stridev);
-    compute_vtile(vB, basev);
-    basev += stridev;
-  }
+  pv_pass<T, D, GE>(Vb, n, C, own_here, [&](int r) { return vnew0 + (size_t)r * p.kv_stride; }, e_lds, GE, 0, lane,
+                    wave, nw, vA, acc);
   float* red = big;  // [nw][GE * D]
 #pragma unroll
   for (int ge = 0; ge < GE; ++ge)
