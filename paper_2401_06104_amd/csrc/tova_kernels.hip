@@ -49,8 +49,7 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
   static_assert(MULTI || !UNIT, "the one-block-per-unit form is built on the multi-step loop");
   using E = Elem<T>;
   using Ge = Geo<T, D, G>;
-  constexpr int VEC = Ge::VEC, CK = Ge::CK, LK = Ge::LK, RK = Ge::RK, UK = Ge::UK;
-  constexpr int LV = Ge::LV, RV = Ge::RV, UV = Ge::UV;
+  constexpr int VEC = Ge::VEC, LV = Ge::LV, UV = Ge::UV;
 
   extern __shared__ float4 smem4[];
   float* small = reinterpret_cast<float*>(smem4);  // kSmallFloats
@@ -175,181 +174,20 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
                 ((size_t)unit * p.H + (size_t)kvh * G) * D;
 
   // ---------------- phase 1: logits ----------------
+  // (vector ALUs, or the matrix cores for wide bf16 groups: see logit_pass; the incoming token is
+  // candidate `ncached` -- App. B: the last column -- and is taken by the block's last wave)
   float m[G], Z[G];  // chunk-local softmax statistics (log2 domain)
-#pragma unroll
-  for (int g = 0; g < G; ++g) m[g] = -INFINITY;
-  if constexpr (Ge::MFMA_K) {
-    // Matrix-core logit pass.  One v_mfma_f32_16x16x32_bf16 contracts 32 elements of d for 16
-    // cached rows (A: lane l holds row l % 16, eight consecutive elements) against 16 heads
-    // (B: lane l holds head l % 16, the same eight elements; heads >= G are zero); D / 32 of them
-    // cover a row.  Which eight elements a lane holds is free as long as A and B agree: MFMA kk
-    // takes the 16-byte chunk kk * 4 + l / 16, so the four lanes of a row load 64 contiguous bytes.
-    // Result register r of lane l is the logit of row (l / 16) * 4 + r for head l % 16.
-    constexpr int KK = D / 32;
-    constexpr int UM = 2;  // 16-row tiles per register buffer
-    const int r16 = lane & 15, c4 = lane >> 4;
-    V16 qm[KK];
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      qm[kk] = V16{{0u, 0u, 0u, 0u}};
-      if (r16 < G) qm[kk] = *reinterpret_cast<const V16*>(qb + r16 * D + (kk * 4 + c4) * 8);
-    }
-    float mh = -INFINITY;  // running maximum of head r16 over the rows this lane sees
-    auto load_tile = [&](V16(&dst)[UM][KK], int base) {
-#pragma unroll
-      for (int u = 0; u < UM; ++u) {
-        const int i = base + u * 16 + r16;
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) dst[u][kk] = V16{{0u, 0u, 0u, 0u}};
-        if (i < ncached) {
-          const T* row = Kb + (size_t)i * D;
-#pragma unroll
-          for (int kk = 0; kk < KK; ++kk) dst[u][kk] = *reinterpret_cast<const V16*>(row + (kk * 4 + c4) * 8);
-        }
-      }
-    };
-    auto logits16 = [&](const V16(&a)[KK], int row0, int nvalid) {  // rows row0 .. row0 + 15
-      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[kk]),
-                                                      __builtin_bit_cast(bf16x8_t, qm[kk]), acc, 0, 0, 0);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int i = row0 + c4 * 4 + r;
-        const float l2 = acc[r] * scale2;
-        if (r16 < G && i < nvalid) {
-          mh = fmaxf(mh, l2);
-          e_lds[i * G + r16] = l2;
-        }
-      }
-    };
-    constexpr int TILE = 16 * UM;
-    const int stride = nw * TILE;
-    int base = wave * TILE;
-    V16 bufA[UM][KK], bufB[UM][KK];
-    const bool new_here = has_new && (wave == nw - 1);  // wave-uniform
-    V16 kn[KK];
-    if (new_here) {  // the incoming token as row 0 of an otherwise empty tile
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        kn[kk] = V16{{0u, 0u, 0u, 0u}};
-        if (r16 == 0) kn[kk] = *reinterpret_cast<const V16*>(knew + (kk * 4 + c4) * 8);
-      }
-    }
-    load_tile(bufA, base);
-    if (new_here) logits16(kn, ncached, ncached + 1);  // candidate `ncached` (App. B: the last column)
-    while (base < ncached) {  // two register buffers: the next tile is in flight while this one is used
-      load_tile(bufB, base + stride);
-#pragma unroll
-      for (int u = 0; u < UM; ++u) logits16(bufA[u], base + u * 16, ncached);
-      base += stride;
-      if (base >= ncached) break;
-      load_tile(bufA, base + stride);
-#pragma unroll
-      for (int u = 0; u < UM; ++u) logits16(bufB[u], base + u * 16, ncached);
-      base += stride;
-    }
-#pragma unroll
-    for (int g = 0; g < G; ++g) m[g] = (g == r16) ? mh : -INFINITY;
-  } else {
-    const int lk = lane % LK;  // position inside the row
-    const int rk = lane / LK;  // which of the RK rows of a wave pass
-    V16 qf[G][CK];
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int c = 0; c < CK; ++c)
-        qf[g][c] = *reinterpret_cast<const V16*>(qb + g * D + (c * LK + lk) * VEC);
-
-    auto load_tile = [&](V16(&dst)[UK][CK], int base) {
-#pragma unroll
-      for (int u = 0; u < UK; ++u) {
-        const int i = base + u * RK + rk;
-#pragma unroll
-        for (int c = 0; c < CK; ++c) dst[u][c] = V16{{0u, 0u, 0u, 0u}};
-        if (i < ncached) {
-          const T* row = Kb + (size_t)i * D;
-#pragma unroll
-          for (int c = 0; c < CK; ++c) dst[u][c] = *reinterpret_cast<const V16*>(row + (c * LK + lk) * VEC);
-        }
-      }
-    };
-    auto logits_of = [&](const V16(&row)[CK], float(&l2)[G]) {
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float a = 0.f;
-#pragma unroll
-        for (int c = 0; c < CK; ++c) a = E::dot(row[c], qf[g][c], a);
-        l2[g] = group_sum<LK>(a) * scale2;
-      }
-    };
-    auto compute_tile = [&](const V16(&src)[UK][CK], int base) {
-#pragma unroll
-      for (int u = 0; u < UK; ++u) {
-        const int i = base + u * RK + rk;
-        float l2[G];
-        logits_of(src[u], l2);
-        if (i < ncached) {
-#pragma unroll
-          for (int g = 0; g < G; ++g) m[g] = fmaxf(m[g], l2[g]);  // running max, per lane
-          if (lk == 0) {
-#pragma unroll
-            for (int g = 0; g < G; ++g) e_lds[i * G + g] = l2[g];
-          }
-        }
-      }
-    };
-
-    constexpr int TILE = RK * UK;  // rows per wave per buffer
-    const int stride = nw * TILE;
-    int base = wave * TILE;
-    V16 bufA[UK][CK], bufB[UK][CK];
-    V16 kn[CK];
-    const bool new_here = has_new && (wave == nw - 1);  // wave-uniform
-    if (new_here) {
-#pragma unroll
-      for (int c = 0; c < CK; ++c) kn[c] = *reinterpret_cast<const V16*>(knew + (c * LK + lk) * VEC);
-    }
-    load_tile(bufA, base);
-    if (new_here) {  // the incoming token is candidate `ncached` (App. B: the last column)
-      float l2[G];
-      logits_of(kn, l2);
-#pragma unroll
-      for (int g = 0; g < G; ++g) m[g] = fmaxf(m[g], l2[g]);
-      if (lane == 0) {
-#pragma unroll
-        for (int g = 0; g < G; ++g) e_lds[ncached * G + g] = l2[g];
-      }
-    }
-    while (base < ncached) {  // two register buffers: the next tile is in flight while this one is used
-      load_tile(bufB, base + stride);
-      compute_tile(bufA, base);
-      base += stride;
-      if (base >= ncached) break;
-      load_tile(bufA, base + stride);
-      compute_tile(bufB, base);
-      base += stride;
-    }
-  }
+  const bool new_here = has_new && (wave == nw - 1);  // wave-uniform
+  logit_pass<T, D, G>(
+      Kb, ncached, 1, new_here, [&](int g) { return qb + g * D; }, [&](int) { return knew; },
+      [](int, int) { return false; }, scale2, lane, wave, nw, e_lds, m);
 
   // The first PV tile is requested now, so that the V stream is already in flight while the
   // block goes through the softmax barriers.
   const int lv = lane % LV;
   const int rv = lane / LV;
-  constexpr int TILEV = RV * UV;
-  const int stridev = nw * TILEV;
-  auto load_vtile = [&](V16(&dst)[UV], int base) {
-#pragma unroll
-    for (int u = 0; u < UV; ++u) {
-      const int i = base + u * RV + rv;
-      dst[u] = V16{{0u, 0u, 0u, 0u}};
-      if (i < ncached) dst[u] = *reinterpret_cast<const V16*>(Vb + (size_t)i * D + lv * VEC);
-    }
-  };
-  V16 vA[UV], vB[UV];
-  int basev = wave * TILEV;
-  load_vtile(vA, basev);
+  V16 vA[UV];
+  pv_first_tile<T, D, G>(vA, Vb, ncached, lane, wave);
 
   // ---------------- phase 2: chunk-local softmax ----------------
   // The barrier inside this reduction is also the one that makes the logits visible.
@@ -461,44 +299,7 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
 
   // ---------------- phase 3: PV ----------------
   float acc[G][VEC];
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) acc[g][v] = 0.f;
-  auto accumulate = [&](const V16& row, const float(&w)[G]) {
-    float vf[VEC];
-    E::unpack(row, vf);
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) acc[g][v] = fmaf(w[g], vf[v], acc[g][v]);
-  };
-  auto compute_vtile = [&](const V16(&src)[UV], int base) {
-#pragma unroll
-    for (int u = 0; u < UV; ++u) {
-      const int i = base + u * RV + rv;
-      float w[G];
-#pragma unroll
-      for (int g = 0; g < G; ++g) w[g] = (i < ncached) ? e_lds[i * G + g] : 0.f;
-      accumulate(src[u], w);
-    }
-  };
-  if (has_new && wave == nw - 1) {  // the incoming token's own value row
-    V16 vn = *reinterpret_cast<const V16*>(vnew + lv * VEC);
-    float w[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) w[g] = (rv == 0) ? e_lds[ncached * G + g] : 0.f;
-    accumulate(vn, w);
-  }
-  while (basev < ncached) {
-    load_vtile(vB, basev + stridev);
-    compute_vtile(vA, basev);
-    basev += stridev;
-    if (basev >= ncached) break;
-    load_vtile(vA, basev + stridev);
-    compute_vtile(vB, basev);
-    basev += stridev;
-  }
+  pv_pass<T, D, G>(Vb, ncached, 1, new_here, [&](int) { return vnew; }, e_lds, G, 0, lane, wave, nw, vA, acc);
   // combine the RV row groups of the wave, then the waves (in wave order)
   float* red = big;  // [nw][G*D]
   if constexpr (LV == 16 && (G * VEC) % 4 == 0) {
