@@ -13,6 +13,11 @@ What is pinned and what is not:
     formulation over a whole prompt (which also defines what a multi-token call
     must produce), closed
     forms (capacity 1, identical keys, a dominating key) and invariants.
+  * the step with re-assigned positions (tova_positions: compressed gaps between retained
+    tokens, rotary embedding at those positions) is pinned by closed forms of the gap rule,
+    complex multiplication for the rotary embedding, ordinary rotary attention when nothing
+    is dropped, a two-dimensional case with closed-form logits, independence of the stream's
+    origin, and brute force from the raw stream on tiny inputs.
   * the absolute victim sequences on the large synthetic configurations are
     "parity unpinned" by the paper itself (it prints no worked numeric
     example); they are trusted only because the routine that produces them
@@ -21,3 +26,4 @@ What is pinned and what is not:
 from .tova_oracle import TovaOracle, TovaHeadOracle, run_stream  # noqa: F401
 from .tova_literal import tova_policy, LiteralTova  # noqa: F401
 from .tova_masked import tova_masked_prompt  # noqa: F401
+from .tova_positions import TovaPositionsOracle, compress_gap, compressed_positions, rope  # noqa: F401
