@@ -159,6 +159,26 @@ int tova_decode_steps(tova_cache_t* cache, int32_t n_steps, const void* q, const
 int tova_prefill(tova_cache_t* cache, int32_t n_tokens, const void* q, const void* k_new,
                  const void* v_new, void* out, int32_t* evicted, void* hip_stream);
 
+/* Decode steps beyond the training length (Sec. 7.2, "Extrapolation with TOVA").  Arguments and
+ * results are those of tova_decode_steps, with one difference in meaning: q, k_new and the cached
+ * keys carry NO positional encoding.  Before each attention the positions of everything the query
+ * attends over are re-assigned -- between two candidates that are adjacent in token order (the
+ * slot -> token map in state_mem gives the order) a gap of g tokens counts as ln(ln(g)), gaps of at
+ * most 10 tokens as they are -- and the rotary embedding is applied inside the kernel at those
+ * positions: element i of a head vector is paired with element i + d/2, the pair turned by
+ * position * rope_base^(-2i/d).  rope_base <= 0 selects 10000; NaN / infinity -> TOVA_EINVAL.
+ * Values are not touched; softmax, outputs, scores, victim and the in-place overwrite (of the
+ * un-rotated rows) are as in tova_decode_steps, the n_pinned / per_head variants included.
+ * The caller keeps one convention per cache: a cache stepped through this entry point holds
+ * un-rotated keys and must not be handed to the others, and vice versa.
+ * One launch covers all n_steps, the fill phase included; a workgroup owns a (layer, sequence)
+ * unit, so with fewer units than compute units part of the device idles.  Needs on-chip memory for
+ * (k + 1) * (4 * max(H / H_kv, 5) + 12) bytes plus 2 KiB within 152 KiB, else TOVA_ENOSUP (k = 4096
+ * fits with up to 4 query heads per KV head, k = 2048 with 8). */
+int tova_decode_steps_repositioned(tova_cache_t* cache, int32_t n_steps, const void* q, const void* k_new,
+                                   const void* v_new, void* out, int32_t* evicted, float rope_base,
+                                   void* hip_stream);
+
 /* How tova_decode_steps launches once the cache is full (decided in tova_cache_init, which asks
  * the device how many workgroups fit): *blocks = 0 -> one launch per step; otherwise the number
  * of workgroups of the single launch that runs all remaining steps of a call (with

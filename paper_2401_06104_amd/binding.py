@@ -61,6 +61,8 @@ def load_library() -> ctypes.CDLL:
     lib.tova_decode_steps.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                       c_void_p, c_void_p]
     lib.tova_prefill.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.tova_decode_steps_repositioned.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+                                                   c_void_p, c_float, c_void_p]
     lib.tova_cache_tokens_seen.argtypes = [c_void_p, POINTER(c_int64)]
     lib.tova_cache_multi_step_blocks.argtypes = [c_void_p, POINTER(c_int32)]
     lib.tova_cache_set_tokens_seen.argtypes = [c_void_p, c_int64]
@@ -236,6 +238,20 @@ class TovaCache:
                                    out.data_ptr(), ev, _stream_handle(stream))
         if rc != TOVA_OK:
             raise TovaError(rc, "tova_prefill")
+
+    def decode_steps_repositioned(self, q, k_new, v_new, out, evicted=None, rope_base=0.0, stream=None):
+        """T steps on a cache of un-rotated keys, positions re-assigned before each attention."""
+        c = self.cfg
+        T = q.shape[0]
+        self._check("q", q, (T, c.n_layers, c.batch, c.n_q_heads, c.head_dim))
+        self._check("k_new", k_new, (T, c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        self._check("v_new", v_new, (T, c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        self._check("out", out, (T, c.n_layers, c.batch, c.n_q_heads, c.head_dim))
+        ev = self._evicted_ptr(evicted, (T, *self.state_shape))
+        rc = self.lib.tova_decode_steps_repositioned(self._h, T, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
+                                                     out.data_ptr(), ev, float(rope_base), _stream_handle(stream))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_decode_steps_repositioned")
 
     def _evicted_ptr(self, evicted, shape):
         if evicted is None:

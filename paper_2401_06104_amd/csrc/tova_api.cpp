@@ -492,6 +492,57 @@ int tova_decode_steps(tova_cache_t* c, int32_t n_steps, const void* q, const voi
   return TOVA_OK;
 }
 
+int tova_decode_steps_repositioned(tova_cache_t* c, int32_t n_steps, const void* q, const void* k_new,
+                                   const void* v_new, void* out, int32_t* evicted, float rope_base,
+                                   void* hip_stream) {
+  if (!c || n_steps < 0) return TOVA_EINVAL;
+  if (!(rope_base == rope_base) || std::isinf(rope_base)) return TOVA_EINVAL;
+  if (n_steps == 0) return TOVA_OK;
+  if (!q || !k_new || !v_new || !out) return TOVA_EINVAL;
+  if (!aligned(q, 16) || !aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(out, 16) ||
+      !aligned(evicted, 4))
+    return TOVA_EINVAL;
+  const Resolved& r = c->r;
+  if (c->t + n_steps > 0x7fffffffLL) return TOVA_ENOSUP;  // token index is kept in 32 bits
+  // LDS of a workgroup: logits of the k + 1 candidates of a KV head's G query heads (the position
+  // scratch, 20 bytes per candidate, and the PV reduction area share that memory), the head-summed
+  // scores, and one double per candidate for the compressed distances
+  const int nt = (r.k >= 512) ? 512 : 256;
+  const long long kp = ((long long)r.k + 1 + 3) / 4 * 4;
+  long long e_fl = kp * r.G;
+  if ((long long)(nt / 64) * r.G * r.D > e_fl) e_fl = (long long)(nt / 64) * r.G * r.D;
+  if (5 * kp > e_fl) e_fl = 5 * kp;
+  const long long lds = (kSmallFloats + e_fl + kp + 2 * kp) * 4;
+  if (lds > kMaxLdsBytesUnit) return TOVA_ENOSUP;
+  const int cus = tova::device_cus();
+  int per_cu = (int)((160 * 1024) / lds);
+  if (per_cu > 2) per_cu = 2;
+  if (per_cu < 1) per_cu = 1;
+  int grid = cus > 0 ? cus * per_cu : r.units;
+  if (grid > r.units) grid = r.units;
+
+  tova::ReposParams p;
+  p.q = q; p.k_new = k_new; p.v_new = v_new; p.out = out; p.evicted = evicted;
+  p.K = c->kv;
+  p.V = c->kv + r.v_off;
+  p.occupancy = reinterpret_cast<int32_t*>(c->state + r.occ_off);
+  p.slot_token = reinterpret_cast<int32_t*>(c->state + r.slot_off);
+  p.q_stride = (int64_t)r.units * r.H * r.D;
+  p.kv_stride = (int64_t)r.pairs * r.D;
+  p.log2_base = std::log2(rope_base > 0.f ? (double)rope_base : 10000.0);
+  p.n0 = (int32_t)(c->t < r.k ? c->t : r.k);
+  p.n_iter = n_steps;
+  p.units = r.units; p.H = r.H; p.H_kv = r.H_kv; p.k = r.k; p.n_pinned = r.n_pinned;
+  p.t = (int32_t)c->t;
+  p.e_floats = (int)e_fl;
+  p.scale = r.scale;
+  const tova::LaunchPlan lp{grid, nt, (int)lds};
+  const hipError_t e = tova::launch_repos(r.bf16, r.D, r.G, p, lp, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_fail(e, "tova_decode_steps_repositioned launch");
+  c->t += n_steps;
+  return TOVA_OK;
+}
+
 int tova_decode_step(tova_cache_t* c, const void* q, const void* k_new, const void* v_new, void* out,
                      int32_t* evicted, void* hip_stream) {
   return tova_decode_steps(c, 1, q, k_new, v_new, out, evicted, hip_stream);

@@ -1,4 +1,5 @@
-// Shared between the host API (tova_api.cpp) and the device code (tova_kernels.hip).
+// Shared between the host API (tova_api.cpp) and the device code (tova_kernels.hip, tova_prefill.hip,
+// tova_repos.hip).
 #ifndef TOVA_INTERNAL_H
 #define TOVA_INTERNAL_H
 
@@ -78,6 +79,29 @@ struct PrefillParams {
   float scale;
 };
 
+// Arguments of one launch of the kernel for decode steps with re-assigned positions (tova_repos.hip):
+// a workgroup per unit, all steps of the call, fill phase included.
+struct ReposParams {
+  const void* q;       // [n_iter][units][H][d]   without positional encoding
+  const void* k_new;   // [n_iter][units][H_kv][d] without positional encoding
+  const void* v_new;
+  void* out;           // like q
+  int32_t* evicted;    // [n_iter][units] or null
+  void* K;             // [units][H_kv][k][d]  keys without positional encoding
+  void* V;
+  int32_t* occupancy;  // [units]
+  int32_t* slot_token; // [units][k]
+  int64_t q_stride, kv_stride;  // elements between consecutive steps of q / out and of k_new / v_new
+  double log2_base;    // log2 of the rotary base
+  int32_t n0;          // rows cached when the launch starts, min(t, k)
+  int32_t n_iter;      // decode steps of this launch
+  int32_t units, H, H_kv, k;
+  int32_t n_pinned;
+  int32_t t;           // index of the first incoming token
+  int32_t e_floats;    // floats of the first big LDS area (logits / PV reduction / position scratch)
+  float scale;
+};
+
 struct LaunchPlan {
   int32_t grid, block, lds_bytes;
 };
@@ -86,6 +110,7 @@ hipError_t launch_step(int dtype_is_bf16, int D, int G, const StepParams& p, con
                        hipStream_t stream);
 hipError_t launch_prefill(int dtype_is_bf16, int D, int G, int C, const PrefillParams& p, const LaunchPlan& lp,
                           hipStream_t stream);
+hipError_t launch_repos(int dtype_is_bf16, int D, int G, const ReposParams& p, const LaunchPlan& lp, hipStream_t stream);
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_t stream);
 // how many blocks of the step kernel (given instantiation, block size, dynamic LDS) fit on the
 // current device at once; 0 if the query fails

@@ -27,13 +27,16 @@ GAP_EXEMPT = 1e-6
 
 def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: int = 256,
             single_step_calls: bool = False, device="cuda:0", prefill: bool = False, keep=None,
-            progress: bool = False, n_pinned: int = 0, per_head: bool = False, use_prefill: bool = False):
+            progress: bool = False, n_pinned: int = 0, per_head: bool = False, use_prefill: bool = False,
+            rope_base=None):
     """units: list of (layer, seq) whose outputs are kept.  Returns a dict of CPU arrays.
 
     prefill=True skips the fill phase: the first k tokens are laid down directly (slot j holds
     token j, which is exactly what k fill steps produce -- App. B's no-op branch) and stepping
     starts at token k through tova_cache_set_tokens_seen.
     keep: list of (t0, t1) step ranges whose outputs are kept (default: all steps).
+    rope_base: not None -> the stream is taken as un-rotated q / k and stepped through
+    tova_decode_steps_repositioned with that rotary base (Sec. 7.2).
     n_pinned / per_head: the TOVA+i / TOVA-head variants (App. A).  With per_head the results come
     back in the equivalent layer-mode view -- B * H_kv sequences of one KV head with G query heads
     each (the stream's flat element order is the same) -- and `units` are (layer, b * H_kv + kvh)."""
@@ -70,6 +73,8 @@ def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: 
         if single_step_calls:
             for i in range(t1 - t0):
                 cache.decode_step(c["q"][i], c["k"][i], c["v"][i], out[i], evicted[t0 + i])
+        elif rope_base is not None:
+            cache.decode_steps_repositioned(c["q"], c["k"], c["v"], out, evicted[t0:t1], rope_base=rope_base)
         elif use_prefill:          # the tokens of a chunk handed over as a prompt (tova_prefill)
             cache.prefill(c["q"], c["k"], c["v"], out, evicted[t0:t1])
         else:
@@ -139,19 +144,24 @@ def _new_stats(unit, steps):
 
 
 def check_unit(spec: StreamSpec, seed: int, unit, gpu_out, gpu_evicted, gpu_slot_token, gpu_K, gpu_V,
-               t_stop=None, prefill=False, out_t0=0, n_pinned=0):
+               t_stop=None, prefill=False, out_t0=0, n_pinned=0, rope_base=None):
     """Steps the oracle over unit=(layer, seq) from the start of the stream (or, with prefill,
     from the state "slot j holds token j") and compares with the GPU's log.
     gpu_out [t, H, d] holds steps out_t0.. ; gpu_evicted [T]; gpu_slot_token [k]; gpu_K / gpu_V
     [H_kv, k, d] are the final cache (compared only when the whole stream is checked).
     Returns a dict of statistics; raises AssertionError on any violation."""
     from oracle.tova_oracle import TovaOracle
+    from oracle.tova_positions import TovaPositionsOracle
 
     l, b = unit
     T = spec.T if t_stop is None else t_stop
     tol = OUT_TOL[spec.dtype]
     st = Stream(spec, seed, device="cpu", layers=[l], seqs=[b])
-    orc = TovaOracle(spec.k, spec.H, spec.H_kv, spec.d, pinned=n_pinned)
+    if rope_base is None:
+        orc = TovaOracle(spec.k, spec.H, spec.H_kv, spec.d, pinned=n_pinned)
+    else:      # (rope_base <= 0 asks the library for its default, 10000)
+        orc = TovaPositionsOracle(spec.k, spec.H, spec.H_kv, spec.d, pinned=n_pinned,
+                                  base=rope_base if rope_base > 0 else 10000.0)
     stats = _new_stats(unit, T)
     kk_all, vv_all = [], []
     for t0 in range(0, T, 512):
@@ -246,7 +256,8 @@ def _check_unit_star(args):
     return check_unit(*args)
 
 
-def check_units(spec, seed, units, res, workers: int = 1, t_stop=None, out=None, out_t0=None, n_pinned=0):
+def check_units(spec, seed, units, res, workers: int = 1, t_stop=None, out=None, out_t0=None, n_pinned=0,
+                rope_base=None):
     """Checks every sampled unit; with workers > 1 in spawned CPU-only processes."""
     jobs = []
     out = res["out"] if out is None else out
@@ -254,7 +265,7 @@ def check_units(spec, seed, units, res, workers: int = 1, t_stop=None, out=None,
     for ui, (l, b) in enumerate(units):
         jobs.append((spec, seed, (l, b), out[:, ui], res["evicted"][:, l, b],
                      res["slot_token"][l, b], res["K"][ui], res["V"][ui], t_stop, res.get("prefill", False),
-                     out_t0, n_pinned))
+                     out_t0, n_pinned, rope_base))
     if workers <= 1 or len(jobs) == 1:
         return [check_unit(*j) for j in jobs]
     import multiprocessing as mp

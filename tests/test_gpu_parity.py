@@ -590,6 +590,88 @@ def test_multi_step_wait_runs_out_cleanly(monkeypatch):
     cache.destroy()
 
 
+# ---- decode steps with re-assigned positions (Sec. 7.2) --------------------------------------
+REPOS_SWEEP = [
+    # dtype, d, H, H_kv, k, T, L, B, rope_base, pinned
+    ("f32", 32, 4, 4, 37, 300, 2, 3, 10000.0, 0),
+    ("f32", 64, 8, 4, 100, 500, 1, 2, 0.0, 0),           # base <= 0: the default, 10000
+    ("f32", 128, 8, 1, 257, 700, 1, 2, 500.0, 0),         # one wide group
+    ("f32", 128, 4, 2, 1, 60, 1, 1, 10000.0, 0),          # capacity 1
+    ("f32", 64, 4, 4, 600, 1300, 1, 1, 10000.0, 0),       # gap sums over several candidates per thread
+    ("bf16", 128, 32, 8, 300, 900, 1, 3, 10000.0, 0),
+    ("bf16", 128, 32, 32, 512, 1500, 1, 2, 10000.0, 0),   # the paper's setting: a multi-state of 512, every head its own KV head
+    ("bf16", 64, 16, 2, 130, 500, 2, 2, 10000.0, 0),      # eight query heads per KV head
+    ("bf16", 32, 8, 2, 77, 400, 1, 5, 100.0, 4),          # first tokens pinned
+    ("bf16", 64, 2, 2, 2100, 2600, 1, 1, 10000.0, 0),     # more than four candidates per thread in the rank count
+    ("bf16", 32, 2, 2, 20, 120, 10, 60, 10000.0, 0),      # 600 units: workgroups walk several units per step
+]
+
+
+@pytest.mark.parametrize("dtype,d,H,H_kv,k,T,L,B,base,pinned", REPOS_SWEEP)
+def test_repositioned_steps_shape_sweep(dtype, d, H, H_kv, k, T, L, B, base, pinned):
+    """tova_decode_steps_repositioned against the oracle that re-assigns the positions of the
+    retained tokens (compressed gaps) and applies the rotary embedding before every attention; the
+    streams are taken as un-rotated q / k.  T goes far enough beyond k for long gaps to form."""
+    spec = StreamSpec(f"repos_{dtype}_d{d}_h{H}_{H_kv}_k{k}", L=L, B=B, H=H, H_kv=H_kv, d=d, dtype=dtype,
+                      k=k, T=T, sink="first", n_sinks=2)
+    units = sorted({(0, 0), (L - 1, B - 1), (L // 2, B // 2)})
+    print(f"[parity] {spec.name} L={L} B={B} T={T} base={base} pinned={pinned} units={units}", flush=True)
+    res = parity.run_gpu(spec, 900 + k, units, n_pinned=pinned, rope_base=base, chunk_steps=200)
+    parity.check_global_invariants(spec, res)
+    if pinned:
+        assert (res["slot_token"][:, :, :pinned] == torch.arange(pinned).numpy()).all()
+    stats = parity.check_units(spec, 900 + k, units, res, workers=3, n_pinned=pinned, rope_base=base)
+    for st in stats:
+        print(f"[parity]   {st}", flush=True)
+    assert all(st["evict_steps"] == T - k for st in stats)
+
+
+def test_repositioned_steps_per_head_variant():
+    """TOVA-head on un-rotated keys: every KV head has its own retained tokens, hence its own positions."""
+    H, H_kv, k = 8, 4, 40
+    spec = StreamSpec("repos_perhead", L=2, B=3, H=H, H_kv=H_kv, d=64, dtype="f32", k=k, T=k + 260)
+    view = spec.replace(B=spec.B * H_kv, H=H // H_kv, H_kv=1)
+    units = [(0, 0), (0, H_kv - 1), (1, view.B - 1)]
+    res = parity.run_gpu(spec, 43, units, per_head=True, rope_base=10000.0)
+    parity.check_global_invariants(view, res)
+    for st in parity.check_units(view, 43, units, res, workers=3, rope_base=10000.0):
+        print(f"[parity]   {st}", flush=True)
+
+
+def test_repositioned_steps_reduce_to_plain_rotary_attention_while_nothing_is_dropped():
+    """While the multi-state has room every gap is 1, so the positions are the ordinary ones: the
+    outputs equal torch's attention over keys and query rotated (by torch, here) at 0..t."""
+    from paper_2401_06104_amd import TovaCache
+    from workloads import Stream
+    spec = StreamSpec("repos_fill", L=1, B=2, H=8, H_kv=4, d=64, dtype="f32", k=64, T=48)
+    base = 10000.0
+    cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype)
+    c = Stream(spec, 77, device="cuda:0").chunk(0, spec.T)
+    out = torch.empty_like(c["q"])
+    ev = torch.empty(spec.T, spec.L, spec.B, dtype=torch.int32, device="cuda:0")
+    cache.decode_steps_repositioned(c["q"], c["k"], c["v"], out, ev, rope_base=base)
+    torch.cuda.synchronize()
+    assert (ev == -1).all() and (cache.occupancy == spec.T).all()
+
+    def rot(x, pos):                              # x [T, ..., d], pos [T]
+        h = spec.d // 2
+        th = base ** (-2.0 * torch.arange(h, dtype=torch.float64) / spec.d)
+        ang = pos.double().view(-1, *([1] * (x.dim() - 2)), 1) * th
+        a, b = x.double()[..., :h], x.double()[..., h:]
+        return torch.cat([a * ang.cos() - b * ang.sin(), b * ang.cos() + a * ang.sin()], dim=-1)
+    pos = torch.arange(spec.T)
+    q = rot(c["q"].cpu(), pos)[:, 0]              # [T, B, H, d]
+    kk = rot(c["k"].cpu(), pos)[:, 0]             # [T, B, H_kv, d]
+    vv = c["v"].cpu().double()[:, 0]
+    G = spec.H // spec.H_kv
+    for t in (0, 1, 17, spec.T - 1):
+        Kt = kk[: t + 1].permute(1, 2, 0, 3).repeat_interleave(G, dim=1)      # [B, H, t+1, d]
+        Vt = vv[: t + 1].permute(1, 2, 0, 3).repeat_interleave(G, dim=1)
+        ref = torch.nn.functional.scaled_dot_product_attention(q[t].unsqueeze(2), Kt, Vt)[:, :, 0]
+        torch.testing.assert_close(out[t, 0].cpu().double(), ref, rtol=1e-5, atol=1e-5)
+    cache.destroy()
+
+
 # ---- variants of the policy ablation (App. A) -----------------------------------------------
 @pytest.mark.parametrize("dtype,H,H_kv,k,pinned,splits", [("f32", 4, 4, 24, 1, 0), ("bf16", 16, 4, 200, 4, 0),
                                                           ("bf16", 8, 2, 150, 4, 3)])
