@@ -52,6 +52,10 @@ def load_library() -> ctypes.CDLL:
     if not os.path.exists(path):
         raise RuntimeError(f"{path} not found: build it with `python -m paper_2401_06104_amd.build` "
                            "(there is no CPU fallback)")
+    # torch first: libtova.so needs the HIP runtime, and a process must have only one -- the one
+    # torch brings.  (Loaded before torch, the library pulls in the system's copy, and its first
+    # launch then reports that there is no device.)
+    import torch  # noqa: F401
     lib = ctypes.CDLL(path)
     cfgp = POINTER(TovaConfig)
     lib.tova_cache_bytes.argtypes = [cfgp, POINTER(c_size_t), POINTER(c_size_t), POINTER(c_size_t)]

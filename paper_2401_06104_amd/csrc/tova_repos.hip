@@ -86,30 +86,39 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
   const int pair0 = unit * p.H_kv;
 
   // ---------------- phase 0: compressed distances (Sec. 7.2) ----------------
-  for (int j = tid; j < n; j += nt) tokS[j] = ld_agent_i(p.slot_token + (size_t)unit * k + j);
-  if (tid == 0) tokS[n] = tok;
+  // (entries from n on hold the largest integer, so that whole 16-byte pieces can be compared)
+  for (int j = tid; j < kp; j += nt) tokS[j] = (j < n) ? ld_agent_i(p.slot_token + (size_t)unit * k + j) : 0x7fffffff;
   __syncthreads();
-  // rank in token order by counting (token indices are distinct); four candidates per thread and trip
-  for (int j0 = tid; j0 < nc; j0 += 4 * nt) {
+  // Rank in token order by counting (token indices are distinct), four cached candidates per thread
+  // and trip, four map entries per read (the same address for every lane: a broadcast).  The
+  // incoming token is the newest: rank n.
+  const int n4 = (n + 3) >> 2;
+  for (int j0 = tid; j0 < n; j0 += 4 * nt) {
     int my[4], r[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
-      my[b] = tokS[min(j0 + b * nt, n)];
+      my[b] = tokS[min(j0 + b * nt, kp - 1)];
       r[b] = 0;
     }
-    for (int i = 0; i < nc; ++i) {
-      const int ti = tokS[i];  // (the same address for every lane: a broadcast)
+#pragma unroll 4
+    for (int i4 = 0; i4 < n4; ++i4) {
+      const int4 t4 = reinterpret_cast<const int4*>(tokS)[i4];
 #pragma unroll
-      for (int b = 0; b < 4; ++b) r[b] += (ti < my[b]) ? 1 : 0;
+      for (int b = 0; b < 4; ++b)
+        r[b] += ((t4.x < my[b]) ? 1 : 0) + ((t4.y < my[b]) ? 1 : 0) + ((t4.z < my[b]) ? 1 : 0) + ((t4.w < my[b]) ? 1 : 0);
     }
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       const int j = j0 + b * nt;
-      if (j < nc) {
+      if (j < n) {
         srt[r[b]] = my[b];
         rnk[j] = r[b];
       }
     }
+  }
+  if (tid == 0) {
+    srt[n] = tok;
+    rnk[n] = n;
   }
   __syncthreads();
   // drank[r] = sum of the compressed gaps between rank r and the newest candidate (rank n, the
@@ -206,7 +215,7 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
 #pragma unroll
         for (int u = 0; u < VEC; ++u) {
           const double rev = dist * turns[u];
-          const float f = (float)(rev - floor(rev));  // the angle as a fraction of a turn, in [0, 1]
+          const float f = (float)__builtin_amdgcn_fract(rev);  // the angle as a fraction of a turn, in [0, 1]
           float sn, cs;
           if constexpr (sizeof(T) == 2) {
             sn = __builtin_amdgcn_sinf(f);  // (take turns, not radians)
