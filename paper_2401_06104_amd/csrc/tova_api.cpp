@@ -512,6 +512,12 @@ int tova_decode_steps_repositioned(tova_cache_t* c, int32_t n_steps, const void*
   // memory); measured 71-74% of peak bandwidth against 61-64% with one workgroup of 512.
   const int cus = tova::device_cus();
   const long long kp = ((long long)r.k + 1 + 3) / 4 * 4;
+  auto plan = [&](int nt, long long* e_fl, long long* lds) {
+    *e_fl = kp * r.G;
+    if ((long long)(nt / 64) * r.G * r.D > *e_fl) *e_fl = (long long)(nt / 64) * r.G * r.D;
+    if (5 * kp > *e_fl) *e_fl = 5 * kp;
+    *lds = (kSmallFloats + *e_fl + kp + 2 * kp) * 4;
+  };
   int nt = 0, per_cu = 1;
   long long e_fl = 0, lds = 0;
   for (int pass = 0; pass < 2; ++pass) {
@@ -520,21 +526,36 @@ int tova_decode_steps_repositioned(tova_cache_t* c, int32_t n_steps, const void*
       const int v = std::atoi(ev);
       if (v >= 64 && v <= 512 && v % 64 == 0) nt = v;
     }
-    e_fl = kp * r.G;
-    if ((long long)(nt / 64) * r.G * r.D > e_fl) e_fl = (long long)(nt / 64) * r.G * r.D;
-    if (5 * kp > e_fl) e_fl = 5 * kp;
-    lds = (kSmallFloats + e_fl + kp + 2 * kp) * 4;
+    plan(nt, &e_fl, &lds);
     per_cu = (int)((160 * 1024) / lds);
     if (per_cu > 2) per_cu = 2;
     if (per_cu < 1) per_cu = 1;
     if (pass == 0 && per_cu == 2 && cus > 0 && r.units >= 2 * cus) break;
   }
   if (lds > kMaxLdsBytesUnit) return TOVA_ENOSUP;
-  int grid = cus > 0 ? cus * per_cu : r.units;
-  if (grid > r.units) grid = r.units;
+
+  // Few units: once the cache is full the KV heads of a unit are dealt to `parts` workgroups of 256
+  // threads, as many as fill the device twice over at most and are resident together (they wait
+  // for each other's results).  It borrows the score rows, counters and state words of the
+  // hand-off form of the step kernel, which exist exactly when there are few units.
+  int parts = 1;
+  long long e_fl_p = 0, lds_p = 0;
+  if (!r.unit_mode && r.H_kv > 1 && cus > 0 && r.units < cus) {
+    plan(256, &e_fl_p, &lds_p);
+    const int cap = tova::repos_resident_blocks(r.bf16, r.D, r.G, 256, (int)lds_p);
+    int limit = 2 * cus < cap ? 2 * cus : cap;
+    if (const char* ev = std::getenv("TOVA_REPOS_PARTS")) {  // tuning aid / test hook: at most this many parts
+      const int v = std::atoi(ev);
+      if (v >= 1 && (long long)v * r.units < limit) limit = v * r.units;
+    }
+    for (int pcand = r.H_kv; pcand >= 2; --pcand)
+      if (r.H_kv % pcand == 0 && (long long)r.units * pcand <= limit && (size_t)pcand * kp <= (size_t)r.H_kv * r.kp) {
+        parts = pcand;
+        break;
+      }
+  }
 
   tova::ReposParams p;
-  p.q = q; p.k_new = k_new; p.v_new = v_new; p.out = out; p.evicted = evicted;
   p.K = c->kv;
   p.V = c->kv + r.v_off;
   p.occupancy = reinterpret_cast<int32_t*>(c->state + r.occ_off);
@@ -542,16 +563,42 @@ int tova_decode_steps_repositioned(tova_cache_t* c, int32_t n_steps, const void*
   p.q_stride = (int64_t)r.units * r.H * r.D;
   p.kv_stride = (int64_t)r.pairs * r.D;
   p.log2_base = std::log2(rope_base > 0.f ? (double)rope_base : 10000.0);
-  p.n0 = (int32_t)(c->t < r.k ? c->t : r.k);
-  p.n_iter = n_steps;
   p.units = r.units; p.H = r.H; p.H_kv = r.H_kv; p.k = r.k; p.n_pinned = r.n_pinned;
-  p.t = (int32_t)c->t;
-  p.e_floats = (int)e_fl;
   p.scale = r.scale;
-  const tova::LaunchPlan lp{grid, nt, (int)lds};
-  const hipError_t e = tova::launch_repos(r.bf16, r.D, r.G, p, lp, static_cast<hipStream_t>(hip_stream));
-  if (e != hipSuccess) return hip_fail(e, "tova_decode_steps_repositioned launch");
-  c->t += n_steps;
+  p.spin = r.persist_spin;
+  p.sg = reinterpret_cast<float*>(c->scratch + r.sg_off);
+  p.cnt_unit = reinterpret_cast<int32_t*>(c->scratch + r.cnt_unit_off);
+  p.pstate = reinterpret_cast<unsigned long long*>(c->scratch + r.pstate_off);
+  p.error_flag = reinterpret_cast<int32_t*>(c->state + r.err_off);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const size_t q_step = (size_t)r.units * r.H * r.D * r.esize;
+  const size_t kv_step = (size_t)r.pairs * r.D * r.esize;
+  for (int32_t i = 0; i < n_steps;) {
+    // with parts: the steps that fill the cache first, a workgroup per unit; then the rest, split
+    const bool split = (parts > 1 && c->t >= r.k);
+    int32_t m = n_steps - i;
+    if (parts > 1 && c->t < r.k && (long long)m > r.k - c->t) m = (int32_t)(r.k - c->t);
+    p.q = static_cast<const char*>(q) + (size_t)i * q_step;
+    p.k_new = static_cast<const char*>(k_new) + (size_t)i * kv_step;
+    p.v_new = static_cast<const char*>(v_new) + (size_t)i * kv_step;
+    p.out = static_cast<char*>(out) + (size_t)i * q_step;
+    p.evicted = evicted ? evicted + (size_t)i * r.units : nullptr;
+    p.n0 = (int32_t)(c->t < r.k ? c->t : r.k);
+    p.n_iter = m;
+    p.t = (int32_t)c->t;
+    p.parts = split ? parts : 1;
+    p.e_floats = (int)(split ? e_fl_p : e_fl);
+    int grid = cus > 0 ? cus * per_cu : r.units;
+    if (grid > r.units) grid = r.units;
+    const tova::LaunchPlan lp = split ? tova::LaunchPlan{r.units * parts, 256, (int)lds_p} : tova::LaunchPlan{grid, nt, (int)lds};
+    hipError_t e = hipSuccess;
+    if (split)  // the units' state words start from "no step finished"
+      e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(p.pstate), 0, (size_t)r.units * 2, s);
+    if (e == hipSuccess) e = tova::launch_repos(r.bf16, r.D, r.G, p, lp, s);
+    if (e != hipSuccess) return hip_fail(e, "tova_decode_steps_repositioned launch");
+    c->t += m;
+    i += m;
+  }
   return TOVA_OK;
 }
 

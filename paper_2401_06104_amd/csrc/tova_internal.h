@@ -100,6 +100,13 @@ struct ReposParams {
   int32_t t;           // index of the first incoming token
   int32_t e_floats;    // floats of the first big LDS area (logits / PV reduction / position scratch)
   float scale;
+  // few units: the KV heads of a unit dealt to `parts` workgroups (cache full, all workgroups resident)
+  int32_t parts;       // 1 = a workgroup owns a unit; else a divisor of H_kv, and the grid is units * parts
+  int32_t spin;        // polls of a unit's state word before a workgroup gives up
+  float* sg;           // [units][parts][k + 1 rounded up to 4] partial head sums of a step
+  int32_t* cnt_unit;   // [units] arrival counters, zero between steps
+  unsigned long long* pstate;  // [units] (victim << 32) | (token index + 1) of the unit's last finished step
+  int32_t* error_flag; // set when a workgroup gave up waiting
 };
 
 struct LaunchPlan {
@@ -111,6 +118,8 @@ hipError_t launch_step(int dtype_is_bf16, int D, int G, const StepParams& p, con
 hipError_t launch_prefill(int dtype_is_bf16, int D, int G, int C, const PrefillParams& p, const LaunchPlan& lp,
                           hipStream_t stream);
 hipError_t launch_repos(int dtype_is_bf16, int D, int G, const ReposParams& p, const LaunchPlan& lp, hipStream_t stream);
+// how many workgroups of that kernel fit on the current device at once; 0 if the query fails
+int repos_resident_blocks(int dtype_is_bf16, int D, int G, int block, int lds_bytes);
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_t stream);
 // how many blocks of the step kernel (given instantiation, block size, dynamic LDS) fit on the
 // current device at once; 0 if the query fails

@@ -30,6 +30,16 @@
 // Nothing leaves the workgroup except its results, so the grid may have any size, the steps of a
 // call run inside one launch, and the fill phase (fewer than k rows cached) runs through the same
 // code with the candidates it has.
+//
+// Few units (the paper runs this experiment at batch 1: 32 layers = 32 units): the KV heads of a unit
+// are dealt to P workgroups (parts), cache full, every workgroup of the grid resident.  A head's
+// softmax is complete inside its part, so what the parts exchange per step is one row of partial
+// head sums each ((k + 1) floats, written past the caches) and an arrival count; the part that
+// arrives last adds the rows in part order, picks the victim, updates the map and publishes
+// (victim, token index) in the unit's 64-bit state word.  Every part finds the positions itself
+// (the map is small), waits -- bounded, with the cache's error flag as the way out -- for that
+// word before the unit's next step, and stores the incoming rows of its own KV heads, so a cached
+// row is only ever written and read by the same workgroup.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -73,17 +83,64 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
   int* rnk = srt + kp;                               // [k + 1] rank by slot
   const float scale2 = p.scale * kLog2e;
 
-  for (int it = 0; it < p.n_iter; ++it) {
-  for (int unit = blockIdx.x; unit < p.units; unit += gridDim.x) {
+  const int P = p.parts;          // workgroups per unit (1: a workgroup owns the unit)
+  const int HP = p.H_kv / P;      // KV heads per part
+  int* flag_lds = reinterpret_cast<int*>(small + 480);
+  // (with parts, an extra pass stores the last step's rows)
+  for (int it = 0; it < p.n_iter + (P > 1 ? 1 : 0); ++it) {
+  for (int item = blockIdx.x; item < p.units * P; item += gridDim.x) {
   int tid = threadIdx.x;
   asm volatile("" : "+v"(tid));  // (opaque per pass: keeps the lane arithmetic of the body out of the loops' live ranges)
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int unit = item / P, part = item - unit * P;
   const int n = min(p.n0 + it, k);  // rows cached before this step
   const bool full = (n == k);
   const int nc = n + 1;             // candidates: the cached rows and the incoming token (index n)
   const int tok = p.t + it;
   const int pair0 = unit * p.H_kv;
+  const int kv0 = part * HP;        // this workgroup's KV heads: kv0 .. kv0 + HP - 1
+
+  if (P > 1 && it > 0) {
+    // Wait (bounded) for the victim of the unit's previous step, then put that step's incoming rows
+    // of this part's KV heads into the freed slot.  If the wait runs out -- it cannot while all
+    // workgroups are resident, which the host checks -- the workgroup raises the cache's error flag
+    // and leaves; every other one sees the flag in its own wait and leaves too.
+    if (tid == 0) {
+      unsigned long long w = 0;
+      int ok = 0;
+      for (int spin = 0;; ++spin) {
+        w = ld_agent_u64(p.pstate + unit);
+        if ((int)(uint32_t)w == tok) {
+          ok = 1;
+          break;
+        }
+        if (spin >= p.spin || ld_agent_i(p.error_flag) != 0) break;
+        __builtin_amdgcn_s_sleep(4);
+      }
+      if (!ok) st_agent_i(p.error_flag, 1);
+      flag_lds[2] = ok;
+      flag_lds[3] = (int)(w >> 32);
+    }
+    __syncthreads();
+    if (flag_lds[2] == 0) return;  // block-uniform
+    const int vic = flag_lds[3];
+    if (vic < k) {  // (vic == k: the incoming token was dropped)
+      const T* kprev = reinterpret_cast<const T*>(p.k_new) + (size_t)(it - 1) * p.kv_stride + (size_t)(pair0 + kv0) * D;
+      const T* vprev = reinterpret_cast<const T*>(p.v_new) + (size_t)(it - 1) * p.kv_stride + (size_t)(pair0 + kv0) * D;
+      T* Ku = reinterpret_cast<T*>(p.K) + ((size_t)(pair0 + kv0) * k + vic) * D;
+      T* Vu = reinterpret_cast<T*>(p.V) + ((size_t)(pair0 + kv0) * k + vic) * D;
+      for (int x = tid; x < HP * ROW16; x += nt) {  // rows of consecutive KV heads are contiguous in k_new
+        const int h = x / ROW16, c = x - h * ROW16;
+        reinterpret_cast<V16*>(Ku + (size_t)h * k * D)[c] = reinterpret_cast<const V16*>(kprev)[x];
+        reinterpret_cast<V16*>(Vu + (size_t)h * k * D)[c] = reinterpret_cast<const V16*>(vprev)[x];
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();  // the rows are in place for this workgroup's passes
+    if (it == p.n_iter) continue;
+  }
 
   // ---------------- phase 0: compressed distances (Sec. 7.2) ----------------
   // (entries from n on hold the largest integer, so that whole 16-byte pieces can be compared)
@@ -174,7 +231,7 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
   for (int u = 0; u < VEC; ++u)
     turns[u] = exp2((double)(-2 * (lr * VEC + u)) / (double)D * p.log2_base) * 0.15915494309189535;  // / (2 pi)
 
-  for (int kvh = 0; kvh < p.H_kv; ++kvh) {
+  for (int kvh = kv0; kvh < kv0 + HP; ++kvh) {
   const int pair = pair0 + kvh;
   const T* Kb = reinterpret_cast<const T*>(p.K) + (size_t)pair * k * D;
   const T* Vb = reinterpret_cast<const T*>(p.V) + (size_t)pair * k * D;
@@ -296,7 +353,7 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
       float a = 0.f;
 #pragma unroll
       for (int g = 0; g < G; ++g) a = fmaf(e_lds[i * G + g], rz[g], a);
-      s_lds[i] = (kvh == 0) ? a : s_lds[i] + a;
+      s_lds[i] = (kvh == kv0) ? a : s_lds[i] + a;
     }
   }
 
@@ -329,8 +386,31 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
   }  // KV heads
 
   // ---------------- the unit's victim and state update (Sec. 4; App. B) ----------------
+  bool decide = true;  // this workgroup picks the unit's victim
+  if (P > 1) {
+    // hand the partial head sums over; the part that arrives last adds them up
+    float* sgp = p.sg + (size_t)unit * P * kp;
+    for (int i = tid; i < nc; i += nt) st_agent(sgp + (size_t)part * kp + i, s_lds[i]);
+    const int prev = arrive(p.cnt_unit + unit, 1, flag_lds, tid);
+    decide = (prev + 1 == P);
+    if (decide) {
+      reset_counter(p.cnt_unit + unit, tid);
+      for (int j = tid; j < nc; j += nt) {
+        float a = 0.f;
+        constexpr int PB = 8;  // parts whose loads are issued together
+        for (int q0 = 0; q0 < P; q0 += PB) {
+          float v[PB];
+#pragma unroll
+          for (int u = 0; u < PB; ++u) v[u] = (q0 + u < P) ? ld_agent(sgp + (size_t)(q0 + u) * kp + j) : 0.f;
+#pragma unroll
+          for (int u = 0; u < PB; ++u) a += v[u];  // (part order)
+        }
+        s_lds[j] = a;  // (entry j is this thread's own)
+      }
+    }
+  }
   int slot = n;  // below capacity the new rows take slot n
-  if (full) {
+  if (full && decide) {
     // argmin of the head sums (the factor 1/H does not move it); a thread takes its candidates in
     // ascending order with a strict <, so the lowest index wins ties; candidates below n_pinned
     // stay out (TOVA+i, App. A)
@@ -372,7 +452,7 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
     if (bj > k) bj = k;  // only reachable with non-finite scores
     slot = bj;
   }
-  if (slot < k) {  // (slot == k: the incoming token itself was dropped)
+  if (P == 1 && slot < k) {  // (slot == k: the incoming token itself was dropped)
     const T* kn = reinterpret_cast<const T*>(p.k_new) + (size_t)it * p.kv_stride + (size_t)pair0 * D;
     const T* vn = reinterpret_cast<const T*>(p.v_new) + (size_t)it * p.kv_stride + (size_t)pair0 * D;
     T* Ku = reinterpret_cast<T*>(p.K) + ((size_t)pair0 * k + slot) * D;
@@ -383,11 +463,17 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
       reinterpret_cast<V16*>(Vu + (size_t)h * k * D)[c] = reinterpret_cast<const V16*>(vn)[x];
     }
   }
-  if (tid == 0) {
+  if (tid == 0 && decide) {
     int32_t* const evp = p.evicted ? p.evicted + (size_t)it * p.units : nullptr;
-    if (evp) evp[unit] = full ? slot : -1;
+    if (evp) st_agent_i(evp + unit, full ? slot : -1);
     if (slot < k) st_agent_i(p.slot_token + (size_t)unit * k + slot, tok);  // (read back, past the caches, in the next step)
-    p.occupancy[unit] = full ? k : n + 1;
+    st_agent_i(p.occupancy + unit, full ? k : n + 1);
+    if (P > 1) {
+      // publish the victim; every part stores the rows of its own KV heads when it comes back to the
+      // unit (the counter's reset and the map entry must have landed first)
+      __builtin_amdgcn_s_waitcnt(0);
+      st_agent_u64(p.pstate + unit, ((unsigned long long)(uint32_t)slot << 32) | (uint32_t)(tok + 1));
+    }
   }
   // the rows and the map entry must have landed before the block reads them in the unit's next step
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -427,7 +513,36 @@ hipError_t launch_repos_d(int D, int G, const ReposParams& p, const LaunchPlan& 
   }
 }
 
+template <typename T, int D>
+int repos_resident_g(int G, int block, int lds) {
+  int per_cu = 0;
+  hipError_t e = hipErrorInvalidValue;
+  switch (G) {
+    case 1: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tova_repos_kernel<T, D, 1>, block, (size_t)lds); break;
+    case 2: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tova_repos_kernel<T, D, 2>, block, (size_t)lds); break;
+    case 4: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tova_repos_kernel<T, D, 4>, block, (size_t)lds); break;
+    case 8: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tova_repos_kernel<T, D, 8>, block, (size_t)lds); break;
+    default: break;
+  }
+  return e == hipSuccess ? per_cu : 0;
+}
+template <typename T>
+int repos_resident_d(int D, int G, int block, int lds) {
+  switch (D) {
+    case 32: return repos_resident_g<T, 32>(G, block, lds);
+    case 64: return repos_resident_g<T, 64>(G, block, lds);
+    case 128: return repos_resident_g<T, 128>(G, block, lds);
+    default: return 0;
+  }
+}
+
 }  // namespace
+
+int repos_resident_blocks(int dtype_is_bf16, int D, int G, int block, int lds_bytes) {
+  if (lds_bytes > 64 * 1024) return 0;  // (the split form is only planned with several workgroups per CU)
+  const int per_cu = dtype_is_bf16 ? repos_resident_d<bf16_t>(D, G, block, lds_bytes) : repos_resident_d<float>(D, G, block, lds_bytes);
+  return per_cu * device_cus();
+}
 
 hipError_t launch_repos(int dtype_is_bf16, int D, int G, const ReposParams& p, const LaunchPlan& lp, hipStream_t stream) {
   return dtype_is_bf16 ? launch_repos_d<bf16_t>(D, G, p, lp, stream) : launch_repos_d<float>(D, G, p, lp, stream);

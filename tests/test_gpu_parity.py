@@ -611,7 +611,37 @@ REPOS_SWEEP = [
 def test_repositioned_steps_shape_sweep(dtype, d, H, H_kv, k, T, L, B, base, pinned):
     """tova_decode_steps_repositioned against the oracle that re-assigns the positions of the
     retained tokens (compressed gaps) and applies the rotary embedding before every attention; the
-    streams are taken as un-rotated q / k.  T goes far enough beyond k for long gaps to form."""
+    streams are taken as un-rotated q / k.  T goes far enough beyond k for long gaps to form.
+    (With few units and several KV heads the full-cache steps run with the KV heads of a unit dealt
+    to several workgroups; the test below keeps a workgroup per unit on such shapes.)"""
+    _repositioned_case(dtype, d, H, H_kv, k, T, L, B, base, pinned)
+
+
+@pytest.mark.parametrize("dtype,d,H,H_kv,k,T,L,B,base,pinned", [REPOS_SWEEP[i] for i in (0, 1, 5, 6, 8)])
+@pytest.mark.parametrize("parts", ["1", "2"])
+def test_repositioned_steps_fewer_workgroups_per_unit(dtype, d, H, H_kv, k, T, L, B, base, pinned, parts, monkeypatch):
+    """The same shapes with at most `parts` workgroups per unit (1: a workgroup owns the unit)."""
+    monkeypatch.setenv("TOVA_REPOS_PARTS", parts)
+    _repositioned_case(dtype, d, H, H_kv, k, T, L, B, base, pinned)
+
+
+def test_repositioned_steps_wait_runs_out_cleanly(monkeypatch):
+    """Failure handling, forced from the host: no polls allowed, so the workgroups that share a unit
+    cannot get its victim; all leave, the kernel ends, the error flag is set."""
+    from paper_2401_06104_amd import TovaCache
+    from workloads import Stream
+    monkeypatch.setenv("TOVA_MULTI_STEP_SPIN", "0")
+    spec = StreamSpec("repos_timeout", L=2, B=2, H=8, H_kv=4, d=64, dtype="bf16", k=64, T=64 + 40)
+    cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype)
+    c = Stream(spec, 14, device="cuda:0").chunk(0, spec.T)
+    out = torch.empty_like(c["q"])
+    cache.decode_steps_repositioned(c["q"], c["k"], c["v"], out, None)
+    torch.cuda.synchronize()
+    assert int(cache.error_flag.item()) == 1
+    cache.destroy()
+
+
+def _repositioned_case(dtype, d, H, H_kv, k, T, L, B, base, pinned):
     spec = StreamSpec(f"repos_{dtype}_d{d}_h{H}_{H_kv}_k{k}", L=L, B=B, H=H, H_kv=H_kv, d=d, dtype=dtype,
                       k=k, T=T, sink="first", n_sinks=2)
     units = sorted({(0, 0), (L - 1, B - 1), (L // 2, B // 2)})
