@@ -171,10 +171,15 @@ int tova_prefill(tova_cache_t* cache, int32_t n_tokens, const void* q, const voi
  * un-rotated rows) are as in tova_decode_steps, the n_pinned / per_head variants included.
  * The caller keeps one convention per cache: a cache stepped through this entry point holds
  * un-rotated keys and must not be handed to the others, and vice versa.
- * One launch covers all n_steps, the fill phase included; a workgroup owns a (layer, sequence)
- * unit, so with fewer units than compute units part of the device idles.  Needs on-chip memory for
- * (k + 1) * (4 * max(H / H_kv, 5) + 12) bytes plus 2 KiB within 152 KiB, else TOVA_ENOSUP (k = 4096
- * fits with up to 4 query heads per KV head, k = 2048 with 8). */
+ * A workgroup owns a (layer, sequence) unit and one launch covers all n_steps, the fill phase
+ * included.  With fewer units than compute units (and more than one KV head, and not the
+ * unit_workgroups layout) the steps on a full cache instead deal the KV heads of a unit to several
+ * workgroups that are all resident; they exchange partial head sums and wait -- bounded -- for the
+ * unit's victim before its next step; should such a wait ever run out the kernel sets the int32 at
+ * error_flag_offset of state_mem and stops early, as described for tova_decode_steps.
+ * Needs on-chip memory for (k + 1) * (4 * max(H / H_kv, 5) + 12) bytes plus 2 KiB within 152 KiB,
+ * else TOVA_ENOSUP (k = 4096 fits with up to 4 query heads per KV head, k = 2048 with 8).
+ * TOVA_REPOS_PARTS=n in the environment allows at most n workgroups per unit (1: never split). */
 int tova_decode_steps_repositioned(tova_cache_t* cache, int32_t n_steps, const void* q, const void* k_new,
                                    const void* v_new, void* out, int32_t* evicted, float rope_base,
                                    void* hip_stream);

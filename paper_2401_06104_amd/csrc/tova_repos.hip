@@ -231,6 +231,102 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
   for (int u = 0; u < VEC; ++u)
     turns[u] = exp2((double)(-2 * (lr * VEC + u)) / (double)D * p.log2_base) * 0.15915494309189535;  // / (2 pi)
 
+  // ---------------- the unit's victim and state update (Sec. 4; App. B) ----------------
+  // (defined here, called below: by a workgroup that owns its unit after the last KV head; with
+  // parts, between the last KV head's softmax and its PV pass, so that the summing part's work
+  // and the victim's way to the other parts overlap everybody's last PV pass)
+  auto victim_and_state = [&]() {
+  bool decide = true;  // this workgroup picks the unit's victim
+  if (P > 1) {
+    // hand the partial head sums over; the part that arrives last adds them up
+    float* sgp = p.sg + (size_t)unit * P * kp;
+    for (int i = tid; i < nc; i += nt) st_agent(sgp + (size_t)part * kp + i, s_lds[i]);
+    const int prev = arrive(p.cnt_unit + unit, 1, flag_lds, tid);
+    decide = (prev + 1 == P);
+    if (decide) {
+      reset_counter(p.cnt_unit + unit, tid);
+      for (int j = tid; j < nc; j += nt) {
+        float a = 0.f;
+        constexpr int PB = 8;  // parts whose loads are issued together
+        for (int q0 = 0; q0 < P; q0 += PB) {
+          float v[PB];
+#pragma unroll
+          for (int u = 0; u < PB; ++u) v[u] = (q0 + u < P) ? ld_agent(sgp + (size_t)(q0 + u) * kp + j) : 0.f;
+#pragma unroll
+          for (int u = 0; u < PB; ++u) a += v[u];  // (part order)
+        }
+        s_lds[j] = a;  // (entry j is this thread's own)
+      }
+    }
+  }
+  int slot = n;  // below capacity the new rows take slot n
+  if (full && decide) {
+    // argmin of the head sums (the factor 1/H does not move it); a thread takes its candidates in
+    // ascending order with a strict <, so the lowest index wins ties; candidates below n_pinned
+    // stay out (TOVA+i, App. A)
+    float best = INFINITY;
+    int bj = 0x7fffffff;
+    for (int j = tid; j <= k; j += nt) {
+      const float sj = s_lds[j];
+      if (j >= p.n_pinned && sj < best) {
+        best = sj;
+        bj = j;
+      }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      const float ob = __shfl_xor(best, o);
+      const int oj = __shfl_xor(bj, o);
+      if (ob < best || (ob == best && oj < bj)) {
+        best = ob;
+        bj = oj;
+      }
+    }
+    float* bv = small + 256;
+    int* bi = reinterpret_cast<int*>(small + 256 + kMaxWaves);
+    if (lane == 0) {
+      bv[wave] = best;
+      bi[wave] = bj;
+    }
+    __syncthreads();
+    best = bv[0];
+    bj = bi[0];
+    for (int w = 1; w < nw; ++w) {
+      const float ob = bv[w];
+      const int oj = bi[w];
+      if (ob < best || (ob == best && oj < bj)) {
+        best = ob;
+        bj = oj;
+      }
+    }
+    if (bj > k) bj = k;  // only reachable with non-finite scores
+    slot = bj;
+  }
+  if (P == 1 && slot < k) {  // (slot == k: the incoming token itself was dropped)
+    const T* kn = reinterpret_cast<const T*>(p.k_new) + (size_t)it * p.kv_stride + (size_t)pair0 * D;
+    const T* vn = reinterpret_cast<const T*>(p.v_new) + (size_t)it * p.kv_stride + (size_t)pair0 * D;
+    T* Ku = reinterpret_cast<T*>(p.K) + ((size_t)pair0 * k + slot) * D;
+    T* Vu = reinterpret_cast<T*>(p.V) + ((size_t)pair0 * k + slot) * D;
+    for (int x = tid; x < p.H_kv * ROW16; x += nt) {  // rows of consecutive KV heads are contiguous in k_new
+      const int h = x / ROW16, c = x - h * ROW16;
+      reinterpret_cast<V16*>(Ku + (size_t)h * k * D)[c] = reinterpret_cast<const V16*>(kn)[x];
+      reinterpret_cast<V16*>(Vu + (size_t)h * k * D)[c] = reinterpret_cast<const V16*>(vn)[x];
+    }
+  }
+  if (tid == 0 && decide) {
+    int32_t* const evp = p.evicted ? p.evicted + (size_t)it * p.units : nullptr;
+    if (evp) st_agent_i(evp + unit, full ? slot : -1);
+    if (slot < k) st_agent_i(p.slot_token + (size_t)unit * k + slot, tok);  // (read back, past the caches, in the next step)
+    st_agent_i(p.occupancy + unit, full ? k : n + 1);
+    if (P > 1) {
+      // publish the victim; every part stores the rows of its own KV heads when it comes back to the
+      // unit (the counter's reset and the map entry must have landed first)
+      __builtin_amdgcn_s_waitcnt(0);
+      st_agent_u64(p.pstate + unit, ((unsigned long long)(uint32_t)slot << 32) | (uint32_t)(tok + 1));
+    }
+  }
+  };
+
   for (int kvh = kv0; kvh < kv0 + HP; ++kvh) {
   const int pair = pair0 + kvh;
   const T* Kb = reinterpret_cast<const T*>(p.K) + (size_t)pair * k * D;
@@ -357,6 +453,8 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
     }
   }
 
+  if (P > 1 && kvh == kv0 + HP - 1) victim_and_state();  // (block-uniform; the exp values and the first V tile stay as they are)
+
   // ---------------- phase 3: PV (values carry no positions) ----------------
   float acc[G][VEC];
   pv_pass<T, D, G>(Vb, n, 1, new_here, [&](int) { return vnew; }, e_lds, G, 0, lane, wave, nw, vA, acc);
@@ -385,96 +483,7 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
   __syncthreads();  // the reduction area is free for the next KV head
   }  // KV heads
 
-  // ---------------- the unit's victim and state update (Sec. 4; App. B) ----------------
-  bool decide = true;  // this workgroup picks the unit's victim
-  if (P > 1) {
-    // hand the partial head sums over; the part that arrives last adds them up
-    float* sgp = p.sg + (size_t)unit * P * kp;
-    for (int i = tid; i < nc; i += nt) st_agent(sgp + (size_t)part * kp + i, s_lds[i]);
-    const int prev = arrive(p.cnt_unit + unit, 1, flag_lds, tid);
-    decide = (prev + 1 == P);
-    if (decide) {
-      reset_counter(p.cnt_unit + unit, tid);
-      for (int j = tid; j < nc; j += nt) {
-        float a = 0.f;
-        constexpr int PB = 8;  // parts whose loads are issued together
-        for (int q0 = 0; q0 < P; q0 += PB) {
-          float v[PB];
-#pragma unroll
-          for (int u = 0; u < PB; ++u) v[u] = (q0 + u < P) ? ld_agent(sgp + (size_t)(q0 + u) * kp + j) : 0.f;
-#pragma unroll
-          for (int u = 0; u < PB; ++u) a += v[u];  // (part order)
-        }
-        s_lds[j] = a;  // (entry j is this thread's own)
-      }
-    }
-  }
-  int slot = n;  // below capacity the new rows take slot n
-  if (full && decide) {
-    // argmin of the head sums (the factor 1/H does not move it); a thread takes its candidates in
-    // ascending order with a strict <, so the lowest index wins ties; candidates below n_pinned
-    // stay out (TOVA+i, App. A)
-    float best = INFINITY;
-    int bj = 0x7fffffff;
-    for (int j = tid; j <= k; j += nt) {
-      const float sj = s_lds[j];
-      if (j >= p.n_pinned && sj < best) {
-        best = sj;
-        bj = j;
-      }
-    }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-      const float ob = __shfl_xor(best, o);
-      const int oj = __shfl_xor(bj, o);
-      if (ob < best || (ob == best && oj < bj)) {
-        best = ob;
-        bj = oj;
-      }
-    }
-    float* bv = small + 256;
-    int* bi = reinterpret_cast<int*>(small + 256 + kMaxWaves);
-    if (lane == 0) {
-      bv[wave] = best;
-      bi[wave] = bj;
-    }
-    __syncthreads();
-    best = bv[0];
-    bj = bi[0];
-    for (int w = 1; w < nw; ++w) {
-      const float ob = bv[w];
-      const int oj = bi[w];
-      if (ob < best || (ob == best && oj < bj)) {
-        best = ob;
-        bj = oj;
-      }
-    }
-    if (bj > k) bj = k;  // only reachable with non-finite scores
-    slot = bj;
-  }
-  if (P == 1 && slot < k) {  // (slot == k: the incoming token itself was dropped)
-    const T* kn = reinterpret_cast<const T*>(p.k_new) + (size_t)it * p.kv_stride + (size_t)pair0 * D;
-    const T* vn = reinterpret_cast<const T*>(p.v_new) + (size_t)it * p.kv_stride + (size_t)pair0 * D;
-    T* Ku = reinterpret_cast<T*>(p.K) + ((size_t)pair0 * k + slot) * D;
-    T* Vu = reinterpret_cast<T*>(p.V) + ((size_t)pair0 * k + slot) * D;
-    for (int x = tid; x < p.H_kv * ROW16; x += nt) {  // rows of consecutive KV heads are contiguous in k_new
-      const int h = x / ROW16, c = x - h * ROW16;
-      reinterpret_cast<V16*>(Ku + (size_t)h * k * D)[c] = reinterpret_cast<const V16*>(kn)[x];
-      reinterpret_cast<V16*>(Vu + (size_t)h * k * D)[c] = reinterpret_cast<const V16*>(vn)[x];
-    }
-  }
-  if (tid == 0 && decide) {
-    int32_t* const evp = p.evicted ? p.evicted + (size_t)it * p.units : nullptr;
-    if (evp) st_agent_i(evp + unit, full ? slot : -1);
-    if (slot < k) st_agent_i(p.slot_token + (size_t)unit * k + slot, tok);  // (read back, past the caches, in the next step)
-    st_agent_i(p.occupancy + unit, full ? k : n + 1);
-    if (P > 1) {
-      // publish the victim; every part stores the rows of its own KV heads when it comes back to the
-      // unit (the counter's reset and the map entry must have landed first)
-      __builtin_amdgcn_s_waitcnt(0);
-      st_agent_u64(p.pstate + unit, ((unsigned long long)(uint32_t)slot << 32) | (uint32_t)(tok + 1));
-    }
-  }
+  if (P == 1) victim_and_state();
   // the rows and the map entry must have landed before the block reads them in the unit's next step
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __builtin_amdgcn_s_waitcnt(0);
