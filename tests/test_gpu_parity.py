@@ -641,6 +641,48 @@ def test_repositioned_steps_wait_runs_out_cleanly(monkeypatch):
     cache.destroy()
 
 
+def test_repositioned_steps_random_shapes_split_units_match_whole_units(monkeypatch):
+    """Forty random small shapes through tova_decode_steps_repositioned, once with the KV heads of a
+    unit dealt to several workgroups (the default for few units) and once with a workgroup per unit,
+    each call cut in two at a random step: same victims, same final state, and -- the arithmetic of a
+    head being the same in both -- bit-identical outputs."""
+    import random
+    from paper_2401_06104_amd import TovaCache
+    rng = random.Random(19)
+    split_seen = 0
+    for case in range(40):
+        d = rng.choice([32, 64, 128]); G = rng.choice([1, 2, 4, 8]); H_kv = rng.choice([2, 3, 4, 6, 8]); H = G * H_kv
+        k = rng.choice([1, 2, 7, 16, 33, 64, 100, 257]); T = k + rng.randint(5, 90)
+        L = rng.choice([1, 2]); B = rng.choice([1, 2, 5]); dtype = rng.choice(["f32", "bf16"])
+        pinned = rng.choice([0, 0, 1]) if k > 2 else 0
+        base = rng.choice([10000.0, 100.0, 0.0])
+        dt = torch.float32 if dtype == "f32" else torch.bfloat16
+        g = torch.Generator().manual_seed(case * 13 + 5)
+        q = torch.randn(T, L, B, H, d, generator=g).to(dt).cuda()
+        kk = torch.randn(T, L, B, H_kv, d, generator=g).to(dt).cuda()
+        vv = torch.randn(T, L, B, H_kv, d, generator=g).to(dt).cuda()
+        runs = []
+        for parts in (None, "1"):
+            if parts is None:
+                monkeypatch.delenv("TOVA_REPOS_PARTS", raising=False)
+            else:
+                monkeypatch.setenv("TOVA_REPOS_PARTS", parts)
+            cache = TovaCache(L, B, k, H, H_kv, d, dtype=dtype, n_pinned=pinned)
+            out = torch.empty_like(q)
+            ev = torch.empty(T, L, B, dtype=torch.int32, device="cuda")
+            cut = rng.randint(1, T - 1)
+            cache.decode_steps_repositioned(q[:cut], kk[:cut], vv[:cut], out[:cut], ev[:cut], rope_base=base)
+            cache.decode_steps_repositioned(q[cut:], kk[cut:], vv[cut:], out[cut:], ev[cut:], rope_base=base)
+            torch.cuda.synchronize()
+            assert int(cache.error_flag.item()) == 0
+            runs.append((out.cpu(), ev.cpu(), cache.slot_token.cpu().clone(), cache.K.cpu().clone(), cache.V.cpu().clone()))
+            cache.destroy()
+        what = f"case {case}: d={d} G={G} H_kv={H_kv} k={k} T={T} L={L} B={B} {dtype} pinned={pinned} base={base}"
+        for a, b, name in zip(runs[0], runs[1], ("outputs", "victims", "slot map", "K", "V")):
+            assert torch.equal(a, b), f"{name} differ, " + what
+        assert ((runs[0][1][k:] >= pinned) & (runs[0][1][k:] <= k)).all() and (runs[0][1][:k] == -1).all(), what
+
+
 def _repositioned_case(dtype, d, H, H_kv, k, T, L, B, base, pinned):
     spec = StreamSpec(f"repos_{dtype}_d{d}_h{H}_{H_kv}_k{k}", L=L, B=B, H=H, H_kv=H_kv, d=d, dtype=dtype,
                       k=k, T=T, sink="first", n_sinks=2)
