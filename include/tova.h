@@ -177,7 +177,7 @@ int tova_prefill(tova_cache_t* cache, int32_t n_tokens, const void* q, const voi
  * workgroups that are all resident; they exchange partial head sums and wait -- bounded -- for the
  * unit's victim before its next step; should such a wait ever run out the kernel sets the int32 at
  * error_flag_offset of state_mem and stops early, as described for tova_decode_steps.
- * Needs on-chip memory for (k + 1) * (4 * max(H / H_kv, 5) + 12) bytes plus 2 KiB within 152 KiB,
+ * Needs on-chip memory for (k + 1) * (4 * max(H / H_kv, 5) + 12) bytes plus 2.5 KiB within 152 KiB,
  * else TOVA_ENOSUP (k = 4096 fits with up to 4 query heads per KV head, k = 2048 with 8).
  * TOVA_REPOS_PARTS=n in the environment allows at most n workgroups per unit (1: never split). */
 int tova_decode_steps_repositioned(tova_cache_t* cache, int32_t n_steps, const void* q, const void* k_new,

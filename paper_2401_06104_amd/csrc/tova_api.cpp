@@ -516,7 +516,7 @@ int tova_decode_steps_repositioned(tova_cache_t* c, int32_t n_steps, const void*
     *e_fl = kp * r.G;
     if ((long long)(nt / 64) * r.G * r.D > *e_fl) *e_fl = (long long)(nt / 64) * r.G * r.D;
     if (5 * kp > *e_fl) *e_fl = 5 * kp;
-    *lds = (kSmallFloats + *e_fl + kp + 2 * kp) * 4;
+    *lds = (kSmallFloats + *e_fl + kp + 2 * kp + r.D) * 4;  // (+ d / 2 doubles: the rotary frequencies)
   };
   int nt = 0, per_cu = 1;
   long long e_fl = 0, lds = 0;

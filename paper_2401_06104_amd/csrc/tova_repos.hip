@@ -43,6 +43,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "tova_internal.h"
 
 #include "tova_device.h"
@@ -82,6 +84,10 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
   int* srt = tokS + kp;                              // [k + 1] token indices in ascending order
   int* rnk = srt + kp;                               // [k + 1] rank by slot
   const float scale2 = p.scale * kLog2e;
+  // the rotary frequencies base^(-2i/d), in turns per unit of position, once per workgroup
+  double* turns_lds = dslot + kp;  // [d / 2]
+  for (int i = threadIdx.x; i < D / 2; i += nt) turns_lds[i] = exp2((double)(-2 * i) / (double)D * p.log2_base) * 0.15915494309189535;  // / (2 pi)
+  __syncthreads();
 
   const int P = p.parts;          // workgroups per unit (1: a workgroup owns the unit)
   const int HP = p.H_kv / P;      // KV heads per part
@@ -146,33 +152,42 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
   // (entries from n on hold the largest integer, so that whole 16-byte pieces can be compared)
   for (int j = tid; j < kp; j += nt) tokS[j] = (j < n) ? ld_agent_i(p.slot_token + (size_t)unit * k + j) : 0x7fffffff;
   __syncthreads();
-  // Rank in token order by counting (token indices are distinct), four cached candidates per thread
-  // and trip, four map entries per read (the same address for every lane: a broadcast).  The
+  // Rank in token order by counting (token indices are distinct), up to four cached candidates per
+  // thread and trip, four map entries per read (the same address for every lane: a broadcast).  The
   // incoming token is the newest: rank n.
   const int n4 = (n + 3) >> 2;
-  for (int j0 = tid; j0 < n; j0 += 4 * nt) {
-    int my[4], r[4];
+  auto count_ranks = [&](auto jb_tag) {
+    constexpr int JB = decltype(jb_tag)::value;  // candidates per thread and trip
+    for (int j0 = tid; j0 < n; j0 += JB * nt) {
+      int my[JB], r[JB];
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      my[b] = tokS[min(j0 + b * nt, kp - 1)];
-      r[b] = 0;
-    }
+      for (int b = 0; b < JB; ++b) {
+        my[b] = tokS[min(j0 + b * nt, kp - 1)];
+        r[b] = 0;
+      }
 #pragma unroll 4
-    for (int i4 = 0; i4 < n4; ++i4) {
-      const int4 t4 = reinterpret_cast<const int4*>(tokS)[i4];
+      for (int i4 = 0; i4 < n4; ++i4) {
+        const int4 t4 = reinterpret_cast<const int4*>(tokS)[i4];
 #pragma unroll
-      for (int b = 0; b < 4; ++b)
-        r[b] += ((t4.x < my[b]) ? 1 : 0) + ((t4.y < my[b]) ? 1 : 0) + ((t4.z < my[b]) ? 1 : 0) + ((t4.w < my[b]) ? 1 : 0);
-    }
+        for (int b = 0; b < JB; ++b)
+          r[b] += ((t4.x < my[b]) ? 1 : 0) + ((t4.y < my[b]) ? 1 : 0) + ((t4.z < my[b]) ? 1 : 0) + ((t4.w < my[b]) ? 1 : 0);
+      }
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const int j = j0 + b * nt;
-      if (j < n) {
-        srt[r[b]] = my[b];
-        rnk[j] = r[b];
+      for (int b = 0; b < JB; ++b) {
+        const int j = j0 + b * nt;
+        if (j < n) {
+          srt[r[b]] = my[b];
+          rnk[j] = r[b];
+        }
       }
     }
-  }
+  };
+  if (n <= nt)
+    count_ranks(std::integral_constant<int, 1>{});
+  else if (n <= 2 * nt)
+    count_ranks(std::integral_constant<int, 2>{});
+  else
+    count_ranks(std::integral_constant<int, 4>{});
   if (tid == 0) {
     srt[n] = tok;
     rnk[n] = n;
@@ -228,8 +243,7 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
   const int lr = lane % LR, rw = lane / LR;
   double turns[VEC];
 #pragma unroll
-  for (int u = 0; u < VEC; ++u)
-    turns[u] = exp2((double)(-2 * (lr * VEC + u)) / (double)D * p.log2_base) * 0.15915494309189535;  // / (2 pi)
+  for (int u = 0; u < VEC; ++u) turns[u] = turns_lds[lr * VEC + u];
 
   // ---------------- the unit's victim and state update (Sec. 4; App. B) ----------------
   // (defined here, called below: by a workgroup that owns its unit after the last KV head; with
