@@ -512,13 +512,17 @@ int tova_decode_steps_repositioned(tova_cache_t* c, int32_t n_steps, const void*
   // memory); measured 71-74% of peak bandwidth against 61-64% with one workgroup of 512.
   const int cus = tova::device_cus();
   const long long kp = ((long long)r.k + 1 + 3) / 4 * 4;
-  auto plan = [&](int nt, long long* e_fl, long long* lds) {
+  // (*persist: room for the token order and the ranks outside the logit area, 8 bytes per candidate, so
+  // that a workgroup that stays with its unit keeps them from step to step; taken when it fits)
+  auto plan = [&](int nt, long long* e_fl, long long* lds, int* persist) {
     *e_fl = kp * r.G;
     if ((long long)(nt / 64) * r.G * r.D > *e_fl) *e_fl = (long long)(nt / 64) * r.G * r.D;
     if (5 * kp > *e_fl) *e_fl = 5 * kp;
     *lds = (kSmallFloats + *e_fl + kp + 2 * kp + r.D) * 4;  // (+ d / 2 doubles: the rotary frequencies)
+    *persist = (*lds + 8 * kp <= kMaxLdsBytesUnit) && (*lds > 80 * 1024 || *lds + 8 * kp <= 80 * 1024);
+    if (*persist) *lds += 8 * kp;
   };
-  int nt = 0, per_cu = 1;
+  int nt = 0, per_cu = 1, persist = 0;
   long long e_fl = 0, lds = 0;
   for (int pass = 0; pass < 2; ++pass) {
     nt = (pass == 0) ? 256 : ((r.k >= 512) ? 512 : 256);
@@ -526,7 +530,7 @@ int tova_decode_steps_repositioned(tova_cache_t* c, int32_t n_steps, const void*
       const int v = std::atoi(ev);
       if (v >= 64 && v <= 512 && v % 64 == 0) nt = v;
     }
-    plan(nt, &e_fl, &lds);
+    plan(nt, &e_fl, &lds, &persist);
     per_cu = (int)((160 * 1024) / lds);
     if (per_cu > 2) per_cu = 2;
     if (per_cu < 1) per_cu = 1;
@@ -540,8 +544,9 @@ int tova_decode_steps_repositioned(tova_cache_t* c, int32_t n_steps, const void*
   // hand-off form of the step kernel, which exist exactly when there are few units.
   int parts = 1;
   long long e_fl_p = 0, lds_p = 0;
+  int persist_p = 0;
   if (!r.unit_mode && r.H_kv > 1 && cus > 0 && r.units < cus) {
-    plan(256, &e_fl_p, &lds_p);
+    plan(256, &e_fl_p, &lds_p, &persist_p);
     const int cap = tova::repos_resident_blocks(r.bf16, r.D, r.G, 256, (int)lds_p);
     int limit = 2 * cus < cap ? 2 * cus : cap;
     if (const char* ev = std::getenv("TOVA_REPOS_PARTS")) {  // tuning aid / test hook: at most this many parts
@@ -588,6 +593,7 @@ int tova_decode_steps_repositioned(tova_cache_t* c, int32_t n_steps, const void*
     p.t = (int32_t)c->t;
     p.parts = split ? parts : 1;
     p.e_floats = (int)(split ? e_fl_p : e_fl);
+    p.persist = split ? persist_p : persist;
     int grid = cus > 0 ? cus * per_cu : r.units;
     if (grid > r.units) grid = r.units;
     const tova::LaunchPlan lp = split ? tova::LaunchPlan{r.units * parts, 256, (int)lds_p} : tova::LaunchPlan{grid, nt, (int)lds};

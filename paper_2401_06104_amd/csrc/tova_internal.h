@@ -99,6 +99,7 @@ struct ReposParams {
   int32_t n_pinned;
   int32_t t;           // index of the first incoming token
   int32_t e_floats;    // floats of the first big LDS area (logits / PV reduction / position scratch)
+  int32_t persist;     // LDS has room for the token order and the ranks outside that area (kept from step to step)
   float scale;
   // few units: the KV heads of a unit dealt to `parts` workgroups (cache full, all workgroups resident)
   int32_t parts;       // 1 = a workgroup owns a unit; else a divisor of H_kv, and the grid is units * parts

@@ -86,6 +86,15 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
   const float scale2 = p.scale * kLog2e;
   // the rotary frequencies base^(-2i/d), in turns per unit of position, once per workgroup
   double* turns_lds = dslot + kp;  // [d / 2]
+  if (p.persist) {
+    // room for the order and the ranks outside the logit area: a workgroup that stays with its unit
+    // then keeps them from step to step (one candidate leaves and one arrives per step) instead of
+    // reading the map and counting again
+    srt = reinterpret_cast<int*>(turns_lds + D / 2);
+    rnk = srt + kp;
+  }
+  const bool stays = p.persist && (int)gridDim.x >= p.units * p.parts;  // one item per workgroup
+  int last_vic = k;  // what the unit's previous step removed (block-uniform)
   for (int i = threadIdx.x; i < D / 2; i += nt) turns_lds[i] = exp2((double)(-2 * i) / (double)D * p.log2_base) * 0.15915494309189535;  // / (2 pi)
   __syncthreads();
 
@@ -131,6 +140,7 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
     __syncthreads();
     if (flag_lds[2] == 0) return;  // block-uniform
     const int vic = flag_lds[3];
+    last_vic = vic;
     if (vic < k) {  // (vic == k: the incoming token was dropped)
       const T* kprev = reinterpret_cast<const T*>(p.k_new) + (size_t)(it - 1) * p.kv_stride + (size_t)(pair0 + kv0) * D;
       const T* vprev = reinterpret_cast<const T*>(p.v_new) + (size_t)(it - 1) * p.kv_stride + (size_t)(pair0 + kv0) * D;
@@ -149,45 +159,64 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
   }
 
   // ---------------- phase 0: compressed distances (Sec. 7.2) ----------------
-  // (entries from n on hold the largest integer, so that whole 16-byte pieces can be compared)
-  for (int j = tid; j < kp; j += nt) tokS[j] = (j < n) ? ld_agent_i(p.slot_token + (size_t)unit * k + j) : 0x7fffffff;
-  __syncthreads();
-  // Rank in token order by counting (token indices are distinct), up to four cached candidates per
-  // thread and trip, four map entries per read (the same address for every lane: a broadcast).  The
-  // incoming token is the newest: rank n.
-  const int n4 = (n + 3) >> 2;
-  auto count_ranks = [&](auto jb_tag) {
-    constexpr int JB = decltype(jb_tag)::value;  // candidates per thread and trip
-    for (int j0 = tid; j0 < n; j0 += JB * nt) {
-      int my[JB], r[JB];
-#pragma unroll
-      for (int b = 0; b < JB; ++b) {
-        my[b] = tokS[min(j0 + b * nt, kp - 1)];
-        r[b] = 0;
+  if (stays && it > 0) {
+    // the order and the ranks of the previous step are still here
+    if (min(p.n0 + it - 1, k) == k && last_vic < k) {
+      // that step removed the candidate in slot last_vic, and its incoming token (rank k then) now
+      // sits in that slot as the newest cached one
+      const int rv = rnk[last_vic];
+      __syncthreads();  // everyone has it before the ranks change
+      int* tmp = tokS;  // (free)
+      for (int r = tid; r < n; r += nt) tmp[r] = (r < rv) ? srt[r] : srt[r + 1];
+      for (int j = tid; j < n; j += nt) {
+        const int rj = rnk[j];
+        rnk[j] = (j == last_vic) ? n - 1 : rj - (rj > rv ? 1 : 0);
       }
-#pragma unroll 4
-      for (int i4 = 0; i4 < n4; ++i4) {
-        const int4 t4 = reinterpret_cast<const int4*>(tokS)[i4];
-#pragma unroll
-        for (int b = 0; b < JB; ++b)
-          r[b] += ((t4.x < my[b]) ? 1 : 0) + ((t4.y < my[b]) ? 1 : 0) + ((t4.z < my[b]) ? 1 : 0) + ((t4.w < my[b]) ? 1 : 0);
-      }
-#pragma unroll
-      for (int b = 0; b < JB; ++b) {
-        const int j = j0 + b * nt;
-        if (j < n) {
-          srt[r[b]] = my[b];
-          rnk[j] = r[b];
+      __syncthreads();
+      for (int r = tid; r < n; r += nt) srt[r] = tmp[r];
+    }
+    // (a step that only appended, or dropped its own token, leaves order and ranks as they are)
+  } else {
+    // (entries from n on hold the largest integer, so that whole 16-byte pieces can be compared)
+    for (int j = tid; j < kp; j += nt) tokS[j] = (j < n) ? ld_agent_i(p.slot_token + (size_t)unit * k + j) : 0x7fffffff;
+    __syncthreads();
+    // Rank in token order by counting (token indices are distinct), up to four cached candidates per
+    // thread and trip, four map entries per read (the same address for every lane: a broadcast).  The
+    // incoming token is the newest: rank n.
+    const int n4 = (n + 3) >> 2;
+    auto count_ranks = [&](auto jb_tag) {
+      constexpr int JB = decltype(jb_tag)::value;  // candidates per thread and trip
+      for (int j0 = tid; j0 < n; j0 += JB * nt) {
+        int my[JB], r[JB];
+  #pragma unroll
+        for (int b = 0; b < JB; ++b) {
+          my[b] = tokS[min(j0 + b * nt, kp - 1)];
+          r[b] = 0;
+        }
+  #pragma unroll 4
+        for (int i4 = 0; i4 < n4; ++i4) {
+          const int4 t4 = reinterpret_cast<const int4*>(tokS)[i4];
+  #pragma unroll
+          for (int b = 0; b < JB; ++b)
+            r[b] += ((t4.x < my[b]) ? 1 : 0) + ((t4.y < my[b]) ? 1 : 0) + ((t4.z < my[b]) ? 1 : 0) + ((t4.w < my[b]) ? 1 : 0);
+        }
+  #pragma unroll
+        for (int b = 0; b < JB; ++b) {
+          const int j = j0 + b * nt;
+          if (j < n) {
+            srt[r[b]] = my[b];
+            rnk[j] = r[b];
+          }
         }
       }
-    }
-  };
-  if (n <= nt)
-    count_ranks(std::integral_constant<int, 1>{});
-  else if (n <= 2 * nt)
-    count_ranks(std::integral_constant<int, 2>{});
-  else
-    count_ranks(std::integral_constant<int, 4>{});
+    };
+    if (n <= nt)
+      count_ranks(std::integral_constant<int, 1>{});
+    else if (n <= 2 * nt)
+      count_ranks(std::integral_constant<int, 2>{});
+    else
+      count_ranks(std::integral_constant<int, 4>{});
+  }
   if (tid == 0) {
     srt[n] = tok;
     rnk[n] = n;
@@ -316,6 +345,7 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
     if (bj > k) bj = k;  // only reachable with non-finite scores
     slot = bj;
   }
+  if (P == 1) last_vic = slot;
   if (P == 1 && slot < k) {  // (slot == k: the incoming token itself was dropped)
     const T* kn = reinterpret_cast<const T*>(p.k_new) + (size_t)it * p.kv_stride + (size_t)pair0 * D;
     const T* vn = reinterpret_cast<const T*>(p.v_new) + (size_t)it * p.kv_stride + (size_t)pair0 * D;
