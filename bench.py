@@ -9,7 +9,7 @@ One "step" = one token for each of the 64 sequences = one pass of the fused kern
 (sequence, KV head); the timed call runs all its steps in ONE launch of that kernel when the
 device can hold all its workgroups at once (otherwise one launch per step).
 
-Prints ONE JSON line (see README / DESIGN for the fields).  `roofline` is the fused step
+Prints ONE JSON line.  `roofline` is the fused step
 kernel against the HBM roofline: algorithmic bytes per launch (bytes per step x steps per launch)
 / average launch duration measured with HIP events on the launch stream over the timed region.  `cpu_baseline` is the fp64 oracle
 timed on host cores on a bounded sample of the same workload.
@@ -193,7 +193,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the path shards by batch/layer "
-              "without communication, see DESIGN.md)", file=sys.stderr)
+              "without communication; nothing here uses a second GPU)", file=sys.stderr)
         sys.exit(2)
 
     import torch
