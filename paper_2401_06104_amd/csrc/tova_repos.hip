@@ -18,7 +18,9 @@
 //   0. positions: the unit's slot -> token map (k integers) gives, by counting, every candidate's
 //      rank in token order; the compressed gaps are summed from the newest candidate backwards
 //      (fp64: distances reach tens of thousands, and the angle D * theta_i is needed to 1e-7
-//      of a turn); D_j lands in LDS, one double per candidate;
+//      of a turn); D_j lands in LDS, one double per candidate; a workgroup that stays with its unit
+//      keeps order and ranks in LDS and updates them per step (one candidate leaves, one arrives)
+//      instead of reading the map and counting again;
 //   1. per KV head: logit pass over the K rows -- a lane holds a 16-byte piece of the first half
 //      of a row and the matching piece of the second half, i.e. both elements of VEC rotary pairs;
 //      the angle's fraction of a turn is taken in fp64, sine and cosine in fp32 (hardware sin/cos
