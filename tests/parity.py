@@ -194,7 +194,7 @@ def check_unit(spec: StreamSpec, seed: int, unit, gpu_out, gpu_evicted, gpu_slot
     return stats
 
 
-def check_window(spec: StreamSpec, seed: int, unit, t0, t1, slot_token_t0, gpu_out, gpu_evicted):
+def check_window(spec: StreamSpec, seed: int, unit, t0, t1, slot_token_t0, gpu_out, gpu_evicted, rope_base=None):
     """PROPERTY check, not parity from the start: every step in [t0, t1) is a correct TOVA
     transition from the state the run itself was in at t0.  That state is rebuilt from the
     stream (rows) and the integer slot -> token map implied by the GPU's evicted log, so an
@@ -208,7 +208,11 @@ def check_window(spec: StreamSpec, seed: int, unit, t0, t1, slot_token_t0, gpu_o
     st = Stream(spec, seed, device="cpu", layers=[l], seqs=[b])
     need = sorted(set(int(x) for x in slot_token_t0 if x >= 0))
     rows_k, rows_v = {}, {}
-    orc = TovaOracle(spec.k, spec.H, spec.H_kv, spec.d)
+    if rope_base is None:
+        orc = TovaOracle(spec.k, spec.H, spec.H_kv, spec.d)
+    else:      # un-rotated stream, positions re-assigned before every attention (Sec. 7.2)
+        from oracle.tova_positions import TovaPositionsOracle
+        orc = TovaPositionsOracle(spec.k, spec.H, spec.H_kv, spec.d, base=rope_base if rope_base > 0 else 10000.0)
     stats = _new_stats(unit, t1 - t0)
     needed = set(need)
     for a in range(0, t1, 2048):

@@ -1,5 +1,6 @@
 """GPU parity tests: the HIP library, called through the C ABI, against the fp64 oracle on
 the same seeded streams.  Bars and the near-tie rule are defined in tests/parity.py."""
+import numpy as np
 import pytest
 import torch
 
@@ -681,6 +682,37 @@ def test_repositioned_steps_random_shapes_split_units_match_whole_units(monkeypa
         for a, b, name in zip(runs[0], runs[1], ("outputs", "victims", "slot map", "K", "V")):
             assert torch.equal(a, b), f"{name} differ, " + what
         assert ((runs[0][1][k:] >= pinned) & (runs[0][1][k:] <= k)).all() and (runs[0][1][:k] == -1).all(), what
+
+
+def test_repositioned_llama7b_70k_stream():
+    """The paper's extrapolation setting at its real shape: one sequence of 70,000 tokens through 32
+    layers of LLaMA-2-7B's shape (32 heads, d = 128, bf16) with a multi-state of 512, keys cached
+    without positions.  Every layer's evicted log is checked for consistency over all 70,000 steps;
+    the oracle follows one layer from the start through the fill and the first 400 evictions
+    (parity), and another layer over a 200-step window starting at token 60,000 -- where the
+    retained tokens lie thousands of positions apart -- from the state the log implies there (a
+    property check, see parity.check_window)."""
+    spec = spec_for("c2_llama7b_layer", L=32, T=70000)
+    base = 10000.0
+    units = [(3, 0), (29, 0)]
+    t_par, w0, w1 = spec.k + 400, 60000, 60200
+    print(f"[parity] {spec.name} x 32 layers, repositioned, full stream T={spec.T}", flush=True)
+    res = parity.run_gpu(spec, 6, units, chunk_steps=500, keep=[(0, t_par), (w0, w1)], progress=True, rope_base=base)
+    parity.check_global_invariants(spec, res)
+    import multiprocessing as mp
+    ev = res["evicted"]
+    st_w0 = parity.replay_slot_tokens(ev[:, 29, 0], spec.k, w0)
+    held = np.sort(st_w0)
+    print(f"[parity]   at token {w0}: oldest retained token {held[0]}, largest gap between neighbours "
+          f"{int(np.diff(held).max())}", flush=True)
+    assert np.diff(held).max() > 10                          # compressed gaps are in play
+    with mp.get_context("spawn").Pool(2) as pool:
+        a = pool.apply_async(parity.check_unit, (spec, 6, (3, 0), res["out"][(0, t_par)][:, 0], ev[:, 3, 0],
+                                                 None, None, None, t_par, False, 0, 0, base))
+        b = pool.apply_async(parity.check_window, (spec, 6, (29, 0), w0, w1, st_w0, res["out"][(w0, w1)][:, 1],
+                                                   ev[:, 29, 0], base))
+        print(f"[parity]   from start: {a.get()}", flush=True)
+        print(f"[parity]   window    : {b.get()}", flush=True)
 
 
 def _repositioned_case(dtype, d, H, H_kv, k, T, L, B, base, pinned):
