@@ -184,6 +184,19 @@ int tova_decode_steps_repositioned(tova_cache_t* cache, int32_t n_steps, const v
                                    const void* v_new, void* out, int32_t* evicted, float rope_base,
                                    void* hip_stream);
 
+/* The policy on its own (App. B, Alg. 1), for callers that compute attention themselves: one step
+ * for every (layer, sequence).  attn_weights: DEVICE fp32 [L][B][H][k+1], the last query's softmax
+ * weights over the k slots (in slot order) followed by the incoming token's (index k); with
+ * per_head the same memory is read as [L][B][H_kv][H / H_kv][k+1].  While the cache has room the
+ * weights are not read and the incoming rows take the next slot (evicted = -1; the early return of
+ * Alg. 1).  Otherwise the weights are summed over the heads in head order, the lowest candidate
+ * (lowest index on ties, candidates below n_pinned kept out) is the victim: evicted[l][b] = its
+ * index, k_new / v_new overwrite its slot, or are not stored if the victim is index k.  k_new,
+ * v_new, evicted as in tova_decode_step; the caller's attention must have been taken over exactly
+ * the slots as they are, which is what the map in state_mem and K / V show. */
+int tova_policy_step(tova_cache_t* cache, const float* attn_weights, const void* k_new,
+                     const void* v_new, int32_t* evicted, void* hip_stream);
+
 /* How tova_decode_steps launches once the cache is full (decided in tova_cache_init, which asks
  * the device how many workgroups fit): *blocks = 0 -> one launch per step; otherwise the number
  * of workgroups of the single launch that runs all remaining steps of a call (with

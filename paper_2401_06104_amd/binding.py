@@ -67,6 +67,7 @@ def load_library() -> ctypes.CDLL:
     lib.tova_prefill.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.tova_decode_steps_repositioned.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                                    c_void_p, c_float, c_void_p]
+    lib.tova_policy_step.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.tova_cache_tokens_seen.argtypes = [c_void_p, POINTER(c_int64)]
     lib.tova_cache_multi_step_blocks.argtypes = [c_void_p, POINTER(c_int32)]
     lib.tova_cache_set_tokens_seen.argtypes = [c_void_p, c_int64]
@@ -256,6 +257,22 @@ class TovaCache:
                                                      out.data_ptr(), ev, float(rope_base), _stream_handle(stream))
         if rc != TOVA_OK:
             raise TovaError(rc, "tova_decode_steps_repositioned")
+
+    def policy_step(self, attn_weights, k_new, v_new, evicted=None, stream=None):
+        """The policy alone: attn_weights fp32 [L][B][H][k+1] computed by the caller over the slots + the new token."""
+        c = self.cfg
+        torch = self._torch
+        if attn_weights.dtype != torch.float32 or not attn_weights.is_contiguous() \
+                or tuple(attn_weights.shape) != (c.n_layers, c.batch, c.n_q_heads, c.capacity_k + 1) \
+                or attn_weights.device != self.kv_mem.device:
+            raise ValueError("attn_weights: expected contiguous float32 [L][B][H][k+1] on the cache's device")
+        self._check("k_new", k_new, (c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        self._check("v_new", v_new, (c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        ev = self._evicted_ptr(evicted, self.state_shape)
+        rc = self.lib.tova_policy_step(self._h, attn_weights.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), ev,
+                                       _stream_handle(stream))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_policy_step")
 
     def _evicted_ptr(self, evicted, shape):
         if evicted is None:

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libtova.so")
 
-SOURCES = ["tova_kernels.hip", "tova_prefill.hip", "tova_repos.hip", "tova_api.cpp"]
+SOURCES = ["tova_kernels.hip", "tova_prefill.hip", "tova_repos.hip", "tova_policy.hip", "tova_api.cpp"]
 
 # -packed-fp32-ops off: the compiler must not form packed fp32 instructions.
 HIPCC_FLAGS = [

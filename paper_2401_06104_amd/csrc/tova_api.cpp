@@ -608,6 +608,29 @@ int tova_decode_steps_repositioned(tova_cache_t* c, int32_t n_steps, const void*
   return TOVA_OK;
 }
 
+int tova_policy_step(tova_cache_t* c, const float* attn_weights, const void* k_new, const void* v_new,
+                     int32_t* evicted, void* hip_stream) {
+  if (!c || !attn_weights || !k_new || !v_new) return TOVA_EINVAL;
+  if (!aligned(attn_weights, 4) || !aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(evicted, 4))
+    return TOVA_EINVAL;
+  const Resolved& r = c->r;
+  if (c->t + 1 > 0x7fffffffLL) return TOVA_ENOSUP;  // token index is kept in 32 bits
+  tova::PolicyParams p;
+  p.w = attn_weights; p.k_new = k_new; p.v_new = v_new; p.evicted = evicted;
+  p.K = c->kv;
+  p.V = c->kv + r.v_off;
+  p.occupancy = reinterpret_cast<int32_t*>(c->state + r.occ_off);
+  p.slot_token = reinterpret_cast<int32_t*>(c->state + r.slot_off);
+  p.n = (int32_t)(c->t < r.k ? c->t : r.k);
+  p.units = r.units; p.H = r.H; p.H_kv = r.H_kv; p.k = r.k; p.n_pinned = r.n_pinned;
+  p.t = (int32_t)c->t;
+  p.row_bytes = r.D * r.esize;
+  const hipError_t e = tova::launch_policy(p, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_fail(e, "tova_policy_step launch");
+  c->t += 1;
+  return TOVA_OK;
+}
+
 int tova_decode_step(tova_cache_t* c, const void* q, const void* k_new, const void* v_new, void* out,
                      int32_t* evicted, void* hip_stream) {
   return tova_decode_steps(c, 1, q, k_new, v_new, out, evicted, hip_stream);

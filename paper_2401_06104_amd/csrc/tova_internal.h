@@ -110,6 +110,23 @@ struct ReposParams {
   int32_t* error_flag; // set when a workgroup gave up waiting
 };
 
+// Arguments of the stand-alone policy kernel (tova_policy.hip): one step, weights given.
+struct PolicyParams {
+  const float* w;      // [units][H][k + 1] last query's attention weights, the incoming token last
+  const void* k_new;   // [units][H_kv][d]
+  const void* v_new;
+  int32_t* evicted;    // [units] or null
+  void* K;             // [units][H_kv][k][d]
+  void* V;
+  int32_t* occupancy;  // [units]
+  int32_t* slot_token; // [units][k]
+  int32_t n;           // rows cached before this step, min(t, k)
+  int32_t units, H, H_kv, k;
+  int32_t n_pinned;
+  int32_t t;           // index of the incoming token
+  int32_t row_bytes;   // d * sizeof(element)
+};
+
 struct LaunchPlan {
   int32_t grid, block, lds_bytes;
 };
@@ -121,6 +138,7 @@ hipError_t launch_prefill(int dtype_is_bf16, int D, int G, int C, const PrefillP
 hipError_t launch_repos(int dtype_is_bf16, int D, int G, const ReposParams& p, const LaunchPlan& lp, hipStream_t stream);
 // how many workgroups of that kernel fit on the current device at once; 0 if the query fails
 int repos_resident_blocks(int dtype_is_bf16, int D, int G, int block, int lds_bytes);
+hipError_t launch_policy(const PolicyParams& p, hipStream_t stream);
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_t stream);
 // how many blocks of the step kernel (given instantiation, block size, dynamic LDS) fit on the
 // current device at once; 0 if the query fails

@@ -776,6 +776,92 @@ def test_repositioned_steps_reduce_to_plain_rotary_attention_while_nothing_is_dr
     cache.destroy()
 
 
+# ---- the policy on its own (App. B, Alg. 1) ----------------------------------------------------
+@pytest.mark.parametrize("dtype,H,H_kv,d,k,T,L,B,pinned,per_head", [
+    ("f32", 4, 4, 32, 16, 90, 1, 2, 0, False),
+    ("bf16", 32, 8, 128, 100, 260, 2, 3, 0, False),
+    ("bf16", 16, 4, 64, 37, 150, 1, 2, 3, False),          # first tokens pinned
+    ("f32", 8, 4, 64, 24, 120, 1, 2, 0, True),             # every KV head its own victim
+])
+def test_policy_step_given_weights(dtype, H, H_kv, d, k, T, L, B, pinned, per_head):
+    """tova_policy_step takes attention weights computed elsewhere -- here by the oracle's attention,
+    rounded to fp32 -- and must pick the victim the appendix algorithm picks on those weights (mean
+    over heads, argmin, lowest index on ties; nothing while the cache has room) and update the cache
+    accordingly: victims as the oracle's rule on the same fp32 weights (near ties within the usual
+    1e-6 exempt), final map and cached rows bit-exact."""
+    from paper_2401_06104_amd import TovaCache
+    from oracle.tova_oracle import TovaOracle
+    from workloads import Stream
+    spec = StreamSpec(f"policy_{dtype}", L=L, B=B, H=H, H_kv=H_kv, d=d, dtype=dtype, k=k, T=T, sink="first", n_sinks=1)
+    cache = TovaCache(L, B, k, H, H_kv, d, dtype=dtype, n_pinned=pinned, per_head=per_head)
+    c = Stream(spec, 23, device="cuda:0").chunk(0, T)
+    qc, kc, vc = (c[x].float().cpu().double().numpy() for x in ("q", "k", "v"))
+    G = H // H_kv
+    heads = [(kvh * G, (kvh + 1) * G, kvh, kvh + 1) for kvh in range(H_kv)] if per_head else [(0, H, 0, H_kv)]
+    orcs = {(l, b, i): TovaOracle(k, h1 - h0, g1 - g0, d, pinned=pinned)
+            for l in range(L) for b in range(B) for i, (h0, h1, g0, g1) in enumerate(heads)}
+    ev = torch.empty(cache.state_shape, dtype=torch.int32, device="cuda:0")
+    near = 0
+    for t in range(T):
+        W = np.zeros((L, B, H, k + 1), dtype=np.float32)
+        for (l, b, i), orc in orcs.items():
+            h0, h1, g0, g1 = heads[i]
+            _, p = orc.attend(qc[t, l, b, h0:h1], kc[t, l, b, g0:g1], vc[t, l, b, g0:g1])
+            W[l, b, h0:h1, : p.shape[1]] = p.astype(np.float32)
+        cache.policy_step(torch.from_numpy(W).cuda(), c["k"][t], c["v"][t], ev)
+        evh = ev.cpu().numpy().reshape(L, B, len(heads))
+        for (l, b, i), orc in orcs.items():
+            h0, h1, g0, g1 = heads[i]
+            got = int(evh[l, b, i])
+            if orc.n < k:
+                assert got == -1
+                orc.update(-1, kc[t, l, b, g0:g1], vc[t, l, b, g0:g1])
+                continue
+            s = W[l, b, h0:h1].astype(np.float64).sum(axis=0) / (h1 - h0)      # the same fp32 weights, summed in fp64
+            j, gap = TovaOracle.select(s, pinned)
+            if got != j:
+                assert gap < parity.GAP_EXEMPT and s[got] - s[j] < parity.GAP_EXEMPT, (t, l, b, i, got, j, gap)
+                near += 1
+            assert pinned <= got <= k
+            orc.update(got, kc[t, l, b, g0:g1], vc[t, l, b, g0:g1])
+    torch.cuda.synchronize()
+    assert cache.tokens_seen == T and (cache.occupancy == k).all()
+    st = cache.slot_token.cpu().numpy().reshape(L, B, len(heads), k)
+    Kg = cache.K.float().cpu().double().numpy().reshape(L, B, H_kv, k, d)
+    Vg = cache.V.float().cpu().double().numpy().reshape(L, B, H_kv, k, d)
+    for (l, b, i), orc in orcs.items():
+        h0, h1, g0, g1 = heads[i]
+        assert np.array_equal(orc.slot_token, st[l, b, i])
+        assert np.array_equal(orc.K, Kg[l, b, g0:g1]) and np.array_equal(orc.V, Vg[l, b, g0:g1])
+    print(f"[parity] policy step {dtype} H={H}/{H_kv} k={k}: {T - k} evicting steps per unit, {near} near-tie choices", flush=True)
+    cache.destroy()
+
+
+def test_policy_step_ties_and_full_size_shape():
+    """Exact ties go to the lowest index that may be dropped (uniform weights: slot n_pinned; a
+    strictly lower incoming token: index k, nothing stored), at config 3's full shape."""
+    from paper_2401_06104_amd import TovaCache
+    spec = spec_for("c3_mistral_gqa")
+    L, B, H, H_kv, d, k = spec.L, spec.B, spec.H, spec.H_kv, spec.d, spec.k
+    for pinned in (0, 4):
+        cache = TovaCache(L, B, k, H, H_kv, d, dtype=spec.dtype, n_pinned=pinned)
+        cache.occupancy.fill_(k)
+        cache.slot_token.copy_(torch.arange(k, dtype=torch.int32, device="cuda:0").expand_as(cache.slot_token))
+        cache.set_tokens_seen(k)
+        kn = torch.randn(L, B, H_kv, d, device="cuda:0").to(torch.bfloat16)
+        vn = torch.randn(L, B, H_kv, d, device="cuda:0").to(torch.bfloat16)
+        ev = torch.empty(L, B, dtype=torch.int32, device="cuda:0")
+        W = torch.full((L, B, H, k + 1), 1.0 / (k + 1), device="cuda:0")
+        cache.policy_step(W, kn, vn, ev)
+        assert (ev == pinned).all()
+        assert (cache.slot_token[..., pinned] == k).all() and torch.equal(cache.K[:, :, :, pinned], kn)
+        W[..., k] = 0.5 / (k + 1)                        # the incoming token strictly lowest
+        before = cache.K.clone()
+        cache.policy_step(W, kn, vn, ev)
+        assert (ev == k).all() and torch.equal(cache.K, before) and cache.tokens_seen == k + 2
+        cache.destroy()
+
+
 # ---- variants of the policy ablation (App. A) -----------------------------------------------
 @pytest.mark.parametrize("dtype,H,H_kv,k,pinned,splits", [("f32", 4, 4, 24, 1, 0), ("bf16", 16, 4, 200, 4, 0),
                                                           ("bf16", 8, 2, 150, 4, 3)])

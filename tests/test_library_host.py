@@ -72,6 +72,7 @@ def test_validation_errors():
     assert lib.tova_decode_steps(None, 3, None, None, None, None, None, None) == TOVA_EINVAL
     assert lib.tova_prefill(None, 3, None, None, None, None, None, None) == TOVA_EINVAL
     assert lib.tova_decode_steps_repositioned(None, 3, None, None, None, None, None, 10000.0, None) == TOVA_EINVAL
+    assert lib.tova_policy_step(None, None, None, None, None, None) == TOVA_EINVAL
     assert lib.tova_cache_destroy(None) == TOVA_EINVAL
     assert lib.tova_cache_tokens_seen(None, None) == TOVA_EINVAL
     assert lib.tova_cache_set_tokens_seen(None, 0) == TOVA_EINVAL
