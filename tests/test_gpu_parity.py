@@ -856,9 +856,9 @@ def test_policy_step_ties_and_full_size_shape():
         assert (ev == pinned).all()
         assert (cache.slot_token[..., pinned] == k).all() and torch.equal(cache.K[:, :, :, pinned], kn)
         W[..., k] = 0.5 / (k + 1)                        # the incoming token strictly lowest
-        before = cache.K.clone()
+        before = cache.K.view(torch.int16).clone()        # (bit patterns: the other slots were never written)
         cache.policy_step(W, kn, vn, ev)
-        assert (ev == k).all() and torch.equal(cache.K, before) and cache.tokens_seen == k + 2
+        assert (ev == k).all() and torch.equal(cache.K.view(torch.int16), before) and cache.tokens_seen == k + 2
         cache.destroy()
 
 
