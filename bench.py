@@ -182,7 +182,7 @@ def main():
     ap.add_argument("--seed", type=int, default=3)
     ap.add_argument("--layers", type=int, default=1, help="stack this many independent layers (1 = the named config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-hbm-variant", action="store_true",  # (also skips the config-4-shape and the repositioned variants)
+    ap.add_argument("--no-hbm-variant", action="store_true",  # (also skips the config-4-shape, repositioned and policy variants)
                     help="skip the extra 32-layer run whose 8 GiB cache cannot sit in the last-level cache")
     ap.add_argument("--prefill", action="store_true",
                     help="lay the first k tokens down directly instead of running k fill steps, so that every "
@@ -271,6 +271,39 @@ def main():
                                           "steps": 32, "ms_per_step": msr, "achieved_GBps": abr / (msr * 1e-3) / 1e9,
                                           "frac": abr / (msr * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                           "sequence_steps_per_s": 1e3 / msr * 32 * 16, "sane": gr["sane"]}
+    if not args.no_hbm_variant and args.layers == 1:
+        # the policy on its own (App. B): fp32 attention weights [L][B][H][k+1] handed in, one launch per step;
+        # config 3's layer shape x 32 layers, cache full
+        from paper_2401_06104_amd import TovaCache
+        sp = spec_for("c3_mistral_gqa", L=32)
+        pc = TovaCache(sp.L, sp.B, sp.k, sp.H, sp.H_kv, sp.d, dtype=sp.dtype, device="cuda:0")
+        pc.occupancy.fill_(sp.k)
+        pc.slot_token.copy_(torch.arange(sp.k, dtype=torch.int32, device="cuda:0").expand_as(pc.slot_token))
+        pc.set_tokens_seen(sp.k)
+        gen = torch.Generator(device="cuda:0").manual_seed(args.seed + 3)
+        W = torch.rand(sp.L, sp.B, sp.H, sp.k + 1, device="cuda:0", generator=gen)
+        W /= W.sum(dim=-1, keepdim=True)
+        kn = torch.randn(sp.L, sp.B, sp.H_kv, sp.d, device="cuda:0", generator=gen).to(torch.bfloat16)
+        vn = torch.randn(sp.L, sp.B, sp.H_kv, sp.d, device="cuda:0", generator=gen).to(torch.bfloat16)
+        evp = torch.empty(sp.L, sp.B, dtype=torch.int32, device="cuda:0")
+        for _ in range(4):
+            pc.policy_step(W, kn, vn, evp)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(32):
+            pc.policy_step(W, kn, vn, evp)
+        e1.record()
+        torch.cuda.synchronize()
+        msp = e0.elapsed_time(e1) / 32
+        bp = W.numel() * 4 + 4 * kn.numel() * 2 + 8 * sp.L * sp.B       # weights in; new rows in, slot rows out; log + map
+        result["policy_variant"] = {"workload": "tova_policy_step: config 3 layer shape x 32 layers (2048 units), fp32 attention "
+                                                "weights [32][64][32][1025] given, one launch per step", "steps": 32,
+                                    "ms_per_step": msp, "algorithmic_bytes_per_step": bp,
+                                    "achieved_GBps": bp / (msp * 1e-3) / 1e9, "frac": bp / (msp * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                    "sane": bool(((evp >= 0) & (evp <= sp.k)).all())}
+        pc.destroy()
+        del W, pc
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")       # 1 GiB
         dst = torch.empty_like(src)
