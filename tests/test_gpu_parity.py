@@ -715,6 +715,28 @@ def test_repositioned_llama7b_70k_stream():
         print(f"[parity]   window    : {b.get()}", flush=True)
 
 
+def test_repositioned_steps_refuse_what_does_not_fit():
+    """A capacity whose candidates do not fit a workgroup's on-chip memory (8 query heads per KV head,
+    k = 8192: 44 bytes per candidate) is refused with TOVA_ENOSUP before anything is
+    launched; so are a NaN rotary base and missing buffers (TOVA_EINVAL).  The cache stays usable."""
+    from paper_2401_06104_amd import TovaCache, TovaError, TOVA_ENOSUP, TOVA_EINVAL
+    cache = TovaCache(1, 1, 8192, 8, 1, 32, dtype="bf16")
+    q = torch.zeros(2, 1, 1, 8, 32, dtype=torch.bfloat16, device="cuda:0")
+    kv = torch.zeros(2, 1, 1, 1, 32, dtype=torch.bfloat16, device="cuda:0")
+    out = torch.empty_like(q)
+    with pytest.raises(TovaError) as e:
+        cache.decode_steps_repositioned(q, kv, kv, out)
+    assert e.value.status == TOVA_ENOSUP and cache.tokens_seen == 0
+    with pytest.raises(TovaError) as e:
+        cache.decode_steps_repositioned(q, kv, kv, out, rope_base=float("nan"))
+    assert e.value.status == TOVA_EINVAL
+    ev = torch.empty(2, 1, 1, dtype=torch.int32, device="cuda:0")
+    cache.decode_steps(q, kv, kv, out, ev)                       # the plain path takes the shape
+    torch.cuda.synchronize()
+    assert (ev == -1).all() and cache.tokens_seen == 2
+    cache.destroy()
+
+
 def _repositioned_case(dtype, d, H, H_kv, k, T, L, B, base, pinned):
     spec = StreamSpec(f"repos_{dtype}_d{d}_h{H}_{H_kv}_k{k}", L=L, B=B, H=H, H_kv=H_kv, d=d, dtype=dtype,
                       k=k, T=T, sink="first", n_sinks=2)
