@@ -45,7 +45,9 @@ typedef enum {
   TOVA_EINVAL = -1, /* null / misaligned pointer, non-positive size, H % H_kv != 0, bad dtype ... */
   TOVA_ENOSUP = -2, /* valid problem, but a shape the kernels do not cover                       */
   TOVA_EHIP = -3,   /* a HIP call (launch) failed                                                  */
-  TOVA_ENOMEM = -4  /* host allocation of the descriptor failed                                     */
+  TOVA_ENOMEM = -4, /* host allocation of the descriptor failed                                     */
+  TOVA_ETOOBIG = -5 /* tova_decode_steps_static: the configuration needs more scratch than the
+                       library's static area holds (TOVA_STATIC_SCRATCH_BYTES)                     */
 } tova_status;
 
 enum { TOVA_F32 = 0, TOVA_BF16 = 1 };
@@ -212,6 +214,26 @@ int tova_cache_tokens_seen(const tova_cache_t* cache, int64_t* t);
  * holding min(t, k) rows and numbers the incoming token t.  The occupancy array in state_mem
  * must agree (it does if it was restored together with the rest).  t >= 0. */
 int tova_cache_set_tokens_seen(tova_cache_t* cache, int64_t t);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, serving loops
+ * and harnesses that forbid hipMalloc): tova_decode_steps with the hand-off scratch (arrival
+ * counters, per-unit state words, partial score rows, chunk statistics, PV partials) taken from
+ * a static device array inside the library instead of the cache's scratch_mem.  Arguments and
+ * results are those of tova_decode_steps, bit for bit.  The call allocates nothing and frees
+ * nothing; what it clears it clears with fill kernels, not memsets.
+ *  - The array holds TOVA_STATIC_SCRATCH_BYTES per GPU for the life of the process.  A
+ *    configuration whose decode steps need more than that (scratch_bytes of tova_cache_bytes less
+ *    the area only tova_prefill uses; the five paper-shaped configurations need at most 22.4 MiB)
+ *    -> TOVA_ETOOBIG, nothing is enqueued.
+ *  - Every call on a GPU shares that GPU's array, which keeps the previous call's contents: the
+ *    call clears the counters it relies on first.  Calls that overlap in time on one GPU (two
+ *    streams, two host threads) race on it: keep them in one stream order.  Stepping one cache
+ *    alternately through this call and tova_decode_steps is fine.
+ *  - tova_cache_init accepts scratch_mem = NULL for a cache that is only ever stepped through this
+ *    call (tova_decode_step, tova_decode_steps and tova_prefill then return TOVA_EINVAL). */
+#define TOVA_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int tova_decode_steps_static(tova_cache_t* cache, int32_t n_steps, const void* q, const void* k_new,
+                             const void* v_new, void* out, int32_t* evicted, void* hip_stream);
 
 /* Frees the host descriptor only; device buffers stay with the caller. */
 int tova_cache_destroy(tova_cache_t* cache);

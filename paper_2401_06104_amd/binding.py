@@ -12,7 +12,7 @@ import os
 from ctypes import POINTER, byref, c_char_p, c_float, c_int, c_int32, c_int64, c_size_t, c_void_p
 from typing import Optional
 
-TOVA_OK, TOVA_EINVAL, TOVA_ENOSUP, TOVA_EHIP, TOVA_ENOMEM = 0, -1, -2, -3, -4
+TOVA_OK, TOVA_EINVAL, TOVA_ENOSUP, TOVA_EHIP, TOVA_ENOMEM, TOVA_ETOOBIG = 0, -1, -2, -3, -4, -5
 TOVA_F32, TOVA_BF16 = 0, 1
 
 _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
@@ -64,6 +64,8 @@ def load_library() -> ctypes.CDLL:
     lib.tova_decode_step.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.tova_decode_steps.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                       c_void_p, c_void_p]
+    lib.tova_decode_steps_static.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+                                             c_void_p, c_void_p]
     lib.tova_prefill.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.tova_decode_steps_repositioned.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                                    c_void_p, c_float, c_void_p]
@@ -75,7 +77,7 @@ def load_library() -> ctypes.CDLL:
     lib.tova_strerror.argtypes = [c_int]
     lib.tova_strerror.restype = c_char_p
     for name in ("tova_cache_bytes", "tova_cache_layout", "tova_cache_init", "tova_decode_step",
-                 "tova_decode_steps", "tova_prefill", "tova_cache_tokens_seen", "tova_cache_set_tokens_seen",
+                 "tova_decode_steps", "tova_decode_steps_static", "tova_prefill", "tova_cache_tokens_seen", "tova_cache_set_tokens_seen",
                  "tova_cache_multi_step_blocks",
                  "tova_cache_destroy"):
         getattr(lib, name).restype = c_int
@@ -115,7 +117,8 @@ class TovaCache:
 
     def __init__(self, n_layers: int, batch: int, capacity_k: int, n_q_heads: int, n_kv_heads: int,
                  head_dim: int, dtype="bf16", softmax_scale: float = 0.0, n_splits: int = 0,
-                 device="cuda:0", stream=None, n_pinned: int = 0, per_head: bool = False):
+                 device="cuda:0", stream=None, n_pinned: int = 0, per_head: bool = False,
+                 own_scratch: bool = True):
         import torch
         self._torch = torch
         self.lib = load_library()
@@ -131,11 +134,13 @@ class TovaCache:
         kvb, stb, scb = tova_cache_bytes(self.cfg)
         self.kv_mem = torch.empty(kvb, dtype=torch.uint8, device=self.device)
         self.state_mem = torch.empty(stb, dtype=torch.uint8, device=self.device)
-        self.scratch_mem = torch.empty(scb, dtype=torch.uint8, device=self.device)
+        # own_scratch=False: no scratch buffer (a cache that is only stepped through decode_steps_static)
+        self.scratch_mem = torch.empty(scb, dtype=torch.uint8, device=self.device) if own_scratch else None
         self._h = c_void_p()
         with torch.cuda.device(self.device):
             rc = self.lib.tova_cache_init(byref(self._h), byref(self.cfg), self.kv_mem.data_ptr(),
-                                          self.state_mem.data_ptr(), self.scratch_mem.data_ptr(),
+                                          self.state_mem.data_ptr(),
+                                          self.scratch_mem.data_ptr() if own_scratch else None,
                                           _stream_handle(stream))
         if rc != TOVA_OK:
             raise TovaError(rc, "tova_cache_init")
@@ -229,6 +234,20 @@ class TovaCache:
                                         out.data_ptr(), ev, _stream_handle(stream))
         if rc != TOVA_OK:
             raise TovaError(rc, "tova_decode_steps")
+
+    def decode_steps_static(self, q, k_new, v_new, out, evicted=None, stream=None):
+        """decode_steps with the hand-off scratch in the library's static device array (allocates nothing)."""
+        c = self.cfg
+        T = q.shape[0]
+        self._check("q", q, (T, c.n_layers, c.batch, c.n_q_heads, c.head_dim))
+        self._check("k_new", k_new, (T, c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        self._check("v_new", v_new, (T, c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        self._check("out", out, (T, c.n_layers, c.batch, c.n_q_heads, c.head_dim))
+        ev = self._evicted_ptr(evicted, (T, *self.state_shape))
+        rc = self.lib.tova_decode_steps_static(self._h, T, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
+                                               out.data_ptr(), ev, _stream_handle(stream))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_decode_steps_static")
 
     def prefill(self, q, k_new, v_new, out, evicted=None, stream=None):
         """A prompt of T tokens known in advance: same arguments and results as decode_steps."""

@@ -17,7 +17,8 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libtova.so")
 
-SOURCES = ["tova_kernels.hip", "tova_prefill.hip", "tova_repos.hip", "tova_policy.hip", "tova_api.cpp"]
+SOURCES = ["tova_kernels.hip", "tova_prefill.hip", "tova_repos.hip", "tova_policy.hip", "tova_static_scratch.hip",
+           "tova_api.cpp"]
 
 # -packed-fp32-ops off: the compiler must not form packed fp32 instructions.
 HIPCC_FLAGS = [
@@ -34,13 +35,28 @@ def hipcc() -> str:
     return exe
 
 
-def build(verbose: bool = True, extra_flags=()) -> str:
-    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags,
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB_PATH]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+def build(verbose: bool = True, extra_flags=(), jobs: int = 8) -> str:
+    """Compiles every source (always: nothing is reused from an earlier build), the translation
+    units side by side, then links them into libtova.so."""
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    with tempfile.TemporaryDirectory(prefix="libtova_build_") as tmp:
+        def compile_one(src):
+            obj = os.path.join(tmp, os.path.splitext(src)[0] + ".o")
+            cmd = [hipcc(), *flags, *extra_flags, *inc, "-c", os.path.join(CSRC, src), "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            subprocess.run(cmd, check=True)
+            return obj
+        with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(SOURCES)))) as pool:
+            objs = list(pool.map(compile_one, SOURCES))
+        link = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH]
+        if verbose:
+            print(" ".join(link), flush=True)
+        subprocess.run(link, check=True)
     return LIB_PATH
 
 

@@ -302,7 +302,7 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
   Resolved r;
   int rc = resolve(cfg, &r);
   if (rc != TOVA_OK) return rc;
-  if (!kv_mem || !state_mem || !scratch_mem) return TOVA_EINVAL;
+  if (!kv_mem || !state_mem) return TOVA_EINVAL;  // (scratch_mem may be null: see tova_decode_steps_static)
   if (!aligned(kv_mem, kAlign) || !aligned(state_mem, kAlign) || !aligned(scratch_mem, kAlign))
     return TOVA_EINVAL;
   tova_cache* c = new (std::nothrow) tova_cache;
@@ -319,7 +319,7 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
   if (e == hipSuccess)
     e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->state + r.slot_off), -1,
                               (size_t)r.units * r.k, s);
-  if (e == hipSuccess)
+  if (e == hipSuccess && c->scratch)
     e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->scratch), 0, r.cnt_bytes / 4, s);
   if (e == hipSuccess)
     e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->state + r.err_off), 0, 1, s);
@@ -377,7 +377,7 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
 
 int tova_prefill(tova_cache_t* c, int32_t n_tokens, const void* q, const void* k_new, const void* v_new,
                  void* out, int32_t* evicted, void* hip_stream) {
-  if (!c || n_tokens < 0) return TOVA_EINVAL;
+  if (!c || n_tokens < 0 || !c->scratch) return TOVA_EINVAL;
   if (n_tokens == 0) return TOVA_OK;
   if (!q || !k_new || !v_new || !out) return TOVA_EINVAL;
   if (!aligned(q, 16) || !aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(out, 16) || !aligned(evicted, 4))
@@ -428,17 +428,28 @@ int tova_prefill(tova_cache_t* c, int32_t n_tokens, const void* q, const void* k
   return TOVA_OK;
 }
 
-int tova_decode_steps(tova_cache_t* c, int32_t n_steps, const void* q, const void* k_new,
-                      const void* v_new, void* out, int32_t* evicted, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+int check_step_args(const tova_cache* c, int32_t n_steps, const void* q, const void* k_new, const void* v_new,
+                    const void* out, const int32_t* evicted) {
   if (!c || n_steps < 0) return TOVA_EINVAL;
   if (n_steps == 0) return TOVA_OK;
   if (!q || !k_new || !v_new || !out) return TOVA_EINVAL;
   if (!aligned(q, 16) || !aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(out, 16) ||
       !aligned(evicted, 4))
     return TOVA_EINVAL;
-  const Resolved& r = c->r;
   if (c->t + n_steps > 0x7fffffffLL) return TOVA_ENOSUP;  // token index is kept in 32 bits
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  return TOVA_OK;
+}
+
+// The launch loop of tova_decode_steps, over a scratch area that is either the caller's
+// (scratch_mem of tova_cache_init) or the library's static one (tova_decode_steps_static).
+// Arguments have been checked; n_steps >= 1.
+int decode_steps_on(tova_cache* c, char* scratch, int32_t n_steps, const void* q, const void* k_new,
+                    const void* v_new, void* out, int32_t* evicted, hipStream_t s) {
+  const Resolved& r = c->r;
 
   const size_t q_step = (size_t)r.units * r.H * r.D * r.esize;
   const size_t kv_step = (size_t)r.pairs * r.D * r.esize;
@@ -447,15 +458,15 @@ int tova_decode_steps(tova_cache_t* c, int32_t n_steps, const void* q, const voi
   p.V = c->kv + r.v_off;
   p.occupancy = reinterpret_cast<int32_t*>(c->state + r.occ_off);
   p.slot_token = reinterpret_cast<int32_t*>(c->state + r.slot_off);
-  p.cnt_pair = reinterpret_cast<int32_t*>(c->scratch + r.cnt_pair_off);
-  p.cnt_unit = reinterpret_cast<int32_t*>(c->scratch + r.cnt_unit_off);
-  p.cnt_pub = reinterpret_cast<int32_t*>(c->scratch + r.cnt_pub_off);
-  p.slow_flag = reinterpret_cast<int32_t*>(c->scratch + r.slow_off);
+  p.cnt_pair = reinterpret_cast<int32_t*>(scratch + r.cnt_pair_off);
+  p.cnt_unit = reinterpret_cast<int32_t*>(scratch + r.cnt_unit_off);
+  p.cnt_pub = reinterpret_cast<int32_t*>(scratch + r.cnt_pub_off);
+  p.slow_flag = reinterpret_cast<int32_t*>(scratch + r.slow_off);
   p.st_off = r.st_off; p.spin_limit = r.spin_limit; p.force_slow = r.force_slow;
-  p.sg = reinterpret_cast<float*>(c->scratch + r.sg_off);
-  p.escr = reinterpret_cast<float*>(c->scratch + r.escr_off);
-  p.stats = reinterpret_cast<float*>(c->scratch + r.stats_off);
-  p.accp = reinterpret_cast<float*>(c->scratch + r.accp_off);
+  p.sg = reinterpret_cast<float*>(scratch + r.sg_off);
+  p.escr = reinterpret_cast<float*>(scratch + r.escr_off);
+  p.stats = reinterpret_cast<float*>(scratch + r.stats_off);
+  p.accp = reinterpret_cast<float*>(scratch + r.accp_off);
   p.accp_half = (int64_t)(round_up((size_t)r.pairs * r.S * r.G * r.D * 4, kAlign) / 4);
   p.pairs = r.pairs; p.H = r.H; p.H_kv = r.H_kv; p.k = r.k; p.n_pinned = r.n_pinned;
   p.S = r.S; p.R = r.R; p.kp = r.kp; p.scale = r.scale;
@@ -463,7 +474,7 @@ int tova_decode_steps(tova_cache_t* c, int32_t n_steps, const void* q, const voi
 
   p.q_stride = (int64_t)(q_step / r.esize);
   p.kv_stride = (int64_t)(kv_step / r.esize);
-  p.pstate = reinterpret_cast<unsigned long long*>(c->scratch + r.pstate_off);
+  p.pstate = reinterpret_cast<unsigned long long*>(scratch + r.pstate_off);
   p.error_flag = reinterpret_cast<int32_t*>(c->state + r.err_off);
   p.persist_spin = r.persist_spin;
 
@@ -492,10 +503,44 @@ int tova_decode_steps(tova_cache_t* c, int32_t n_steps, const void* q, const voi
   return TOVA_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+int tova_decode_steps(tova_cache_t* c, int32_t n_steps, const void* q, const void* k_new,
+                      const void* v_new, void* out, int32_t* evicted, void* hip_stream) {
+  const int rc = check_step_args(c, n_steps, q, k_new, v_new, out, evicted);
+  if (rc != TOVA_OK || n_steps == 0) return rc;
+  if (!c->scratch) return TOVA_EINVAL;  // (a cache made for tova_decode_steps_static only)
+  return decode_steps_on(c, c->scratch, n_steps, q, k_new, v_new, out, evicted, static_cast<hipStream_t>(hip_stream));
+}
+
+int tova_decode_steps_static(tova_cache_t* c, int32_t n_steps, const void* q, const void* k_new,
+                             const void* v_new, void* out, int32_t* evicted, void* hip_stream) {
+  const int rc = check_step_args(c, n_steps, q, k_new, v_new, out, evicted);
+  if (rc != TOVA_OK || n_steps == 0) return rc;
+  const Resolved& r = c->r;
+  // what the decode steps use of the scratch layout: everything in front of the prompt kernel's area
+  if (r.uscr_off > TOVA_STATIC_SCRATCH_BYTES) return TOVA_ETOOBIG;
+  void* area = nullptr;
+  size_t area_bytes = 0;
+  hipError_t e = tova::static_scratch(&area, &area_bytes);  // (a look-up; nothing is allocated)
+  if (e != hipSuccess) return hip_fail(e, "tova_decode_steps_static: static scratch");
+  if (r.uscr_off > area_bytes) return TOVA_ETOOBIG;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  // The area keeps whatever the previous call on this GPU left, possibly under another cache's
+  // layout: the arrival counters, slow-route flags and state words must start at zero (a fill
+  // kernel, so that the call can be recorded into a graph).  Everything else in it is written
+  // before it is read within a step.
+  e = tova::launch_fill_i32(static_cast<int32_t*>(area), 0, r.cnt_bytes / 4, s);
+  if (e != hipSuccess) return hip_fail(e, "tova_decode_steps_static: clearing the counters");
+  return decode_steps_on(c, static_cast<char*>(area), n_steps, q, k_new, v_new, out, evicted, s);
+}
+
 int tova_decode_steps_repositioned(tova_cache_t* c, int32_t n_steps, const void* q, const void* k_new,
                                    const void* v_new, void* out, int32_t* evicted, float rope_base,
                                    void* hip_stream) {
-  if (!c || n_steps < 0) return TOVA_EINVAL;
+  if (!c || n_steps < 0 || !c->scratch) return TOVA_EINVAL;
   if (!(rope_base == rope_base) || std::isinf(rope_base)) return TOVA_EINVAL;
   if (n_steps == 0) return TOVA_OK;
   if (!q || !k_new || !v_new || !out) return TOVA_EINVAL;
@@ -668,6 +713,7 @@ const char* tova_strerror(int status) {
     case TOVA_ENOSUP: return "shape not supported by the gfx950 kernels";
     case TOVA_EHIP: return g_hip_msg[0] ? g_hip_msg : "HIP runtime error";
     case TOVA_ENOMEM: return "out of host memory";
+    case TOVA_ETOOBIG: return "configuration needs more scratch than the library's static area holds (32 MiB)";
     default: return "unknown status";
   }
 }

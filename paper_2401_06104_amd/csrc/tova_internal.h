@@ -145,6 +145,9 @@ hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_
 int resident_blocks(int dtype_is_bf16, int D, int G, int block, int lds_bytes, int unit_mode);
 // compute units of the current device; 0 if the query fails
 int device_cus();
+// device address and size of the library's static scratch area on the current device
+// (tova_static_scratch.hip; looked up once per device, nothing is allocated)
+hipError_t static_scratch(void** ptr, size_t* bytes);
 
 }  // namespace tova
 #endif
