@@ -28,13 +28,16 @@ GAP_EXEMPT = 1e-6
 def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: int = 256,
             single_step_calls: bool = False, device="cuda:0", prefill: bool = False, keep=None,
             progress: bool = False, n_pinned: int = 0, per_head: bool = False, use_prefill: bool = False,
-            rope_base=None):
+            rope_base=None, keep_native: bool = False):
     """units: list of (layer, seq) whose outputs are kept.  Returns a dict of CPU arrays.
 
     prefill=True skips the fill phase: the first k tokens are laid down directly (slot j holds
     token j, which is exactly what k fill steps produce -- App. B's no-op branch) and stepping
     starts at token k through tova_cache_set_tokens_seen.
-    keep: list of (t0, t1) step ranges whose outputs are kept (default: all steps).
+    keep: list of (t0, t1) or (t0, t1, [indices into units]) step ranges whose outputs are kept, for
+    all sampled units or for the named ones (default: all steps, all sampled units); with keep given,
+    res["out"] is a dict keyed by those tuples, each [t1 - t0, n_units_kept, H, d] in the stream's dtype
+    when keep_native, else float32.
     rope_base: not None -> the stream is taken as un-rotated q / k and stepped through
     tova_decode_steps_repositioned with that rotary base (Sec. 7.2).
     n_pinned / per_head: the TOVA+i / TOVA-head variants (App. A).  With per_head the results come
@@ -53,8 +56,10 @@ def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: 
     ub = torch.tensor([u[1] for u in units], device=dev)
     t_begin = spec.k if prefill else 0
     default_keep = keep is None
-    keep = [(t_begin, spec.T)] if keep is None else keep
+    keep = [(t_begin, spec.T)] if keep is None else [tuple(r[:2]) + ((tuple(r[2]),) if len(r) > 2 else ()) for r in keep]
     outs = {r: [] for r in keep}
+    sel = {r: (torch.tensor([units[i][0] for i in r[2]], device=dev), torch.tensor([units[i][1] for i in r[2]], device=dev))
+           if len(r) > 2 else (ul, ub) for r in keep}
     if prefill:
         assert spec.T > spec.k
         K, V = cache.K, cache.V
@@ -79,16 +84,19 @@ def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: 
             cache.prefill(c["q"], c["k"], c["v"], out, evicted[t0:t1])
         else:
             cache.decode_steps(c["q"], c["k"], c["v"], out, evicted[t0:t1])
-        for (a, b) in keep:
-            lo, hi = max(a, t0), min(b, t1)
+        for r in keep:
+            lo, hi = max(r[0], t0), min(r[1], t1)
             if lo < hi:
-                outs[(a, b)].append(out[lo - t0:hi - t0].view(-1, spec.L, Bv, Hv, spec.d)[:, ul, ub].float().cpu())
+                o = out[lo - t0:hi - t0].view(-1, spec.L, Bv, Hv, spec.d)[:, sel[r][0], sel[r][1]]
+                outs[r].append((o if keep_native else o.float()).cpu())
         if progress and (t0 // chunk_steps) % 16 == 0:
             torch.cuda.synchronize(dev)
             print(f"[parity]   gpu at step {t1}/{spec.T}", flush=True)
     torch.cuda.synchronize(dev)
+    assert int(cache.error_flag.item()) == 0, "a multi-step launch gave up waiting (error flag set)"
     res = {
-        "out": {r: (torch.cat(v).numpy() if v else None) for r, v in outs.items()},   # [t, n_units, H, d] f32
+        "out": {r: ((torch.cat(v) if keep_native else torch.cat(v).numpy()) if v else None)
+                for r, v in outs.items()},                                          # [t, n_units, H, d]
         "evicted": evicted.view(spec.T, spec.L, Bv).cpu().numpy(),                  # [T, L, B]
         "slot_token": cache.slot_token.view(spec.L, Bv, spec.k).cpu().numpy(),      # [L, B, k]
         "occupancy": cache.occupancy.view(spec.L, Bv).cpu().numpy(),
@@ -261,7 +269,7 @@ def _check_unit_star(args):
 
 
 def check_units(spec, seed, units, res, workers: int = 1, t_stop=None, out=None, out_t0=None, n_pinned=0,
-                rope_base=None):
+                rope_base=None, keep_native: bool = False):
     """Checks every sampled unit; with workers > 1 in spawned CPU-only processes."""
     jobs = []
     out = res["out"] if out is None else out
@@ -303,3 +311,161 @@ def check_global_invariants(spec, res):
         for b in range(spec.B):
             row = st[l, b][st[l, b] >= 0]
             assert len(set(row.tolist())) == len(row)
+
+
+# ---------------------------------------------------------------------------------------------
+# Parity over a whole long stream, by tiling it with windows that are checked on separate cores.
+#
+# The stream [t_begin, t_end) of one unit is cut into contiguous windows.  Each window starts from
+# the state the run was in there: the slot -> token map that the GPU's integer `evicted` log implies
+# (replayed on integers) and, for every retained token, its K / V rows REGENERATED from the seeded
+# stream -- nothing of the GPU's floating-point results enters the oracle.  Inside a window every
+# step is compared as in check_unit (outputs within tolerance; victim equal, or a counted near tie
+# that the oracle then follows).  The first window starts from the empty multi-state (or from
+# "slot j holds token j" when the run laid the first k tokens down).  If every window passes, every
+# logged victim from the first step on is the oracle's victim given the victims before it, which by
+# induction is parity over the whole stream from the empty cache -- the same statement check_unit
+# makes, computed in parallel.  A single wrong victim anywhere fails the window that contains it.
+# ---------------------------------------------------------------------------------------------
+def _window_job(job):
+    """One window of one unit (runs in a spawned CPU-only process).  job: dict, see check_tiled."""
+    from oracle.tova_oracle import TovaOracle
+    try:
+        from threadpoolctl import threadpool_limits
+        limiter = threadpool_limits(limits=1)            # one core per worker
+    except Exception:                                     # pragma: no cover
+        limiter = None
+    spec, unit, a, b = job["spec"], job["unit"], job["a"], job["b"]
+    tol = OUT_TOL[spec.dtype]
+    if job["rope_base"] is None:
+        orc = TovaOracle(spec.k, spec.H, spec.H_kv, spec.d, pinned=job["n_pinned"])
+    else:
+        from oracle.tova_positions import TovaPositionsOracle
+        rb = job["rope_base"]
+        orc = TovaPositionsOracle(spec.k, spec.H, spec.H_kv, spec.d, pinned=job["n_pinned"],
+                                  base=rb if rb > 0 else 10000.0)
+    st = np.asarray(job["slot_token"], dtype=np.int64)
+    held = st >= 0
+    n = int(held.sum())
+    assert held[:n].all(), "occupied slots must be the first ones"
+    orc.K[:, :n] = np.asarray(job["rows_k"], dtype=np.float64)        # [H_kv, n, d]
+    orc.V[:, :n] = np.asarray(job["rows_v"], dtype=np.float64)
+    orc.slot_token[:] = st
+    orc.n = n
+    orc.t = a
+    q = np.asarray(job["q"], dtype=np.float64)
+    kk = np.asarray(job["k"], dtype=np.float64)
+    vv = np.asarray(job["v"], dtype=np.float64)
+    g = None if job["out"] is None else np.asarray(job["out"], dtype=np.float64)
+    ev = job["evicted"]
+    stats = _new_stats(unit, b - a)
+    stats["window"] = (a, b)
+    for i in range(b - a):
+        _compare_step(spec, unit, a + i, orc, q[i], kk[i], vv[i], None if g is None else g[i], ev[i], stats, tol)
+    stats["slot_token_end"] = orc.slot_token.copy()
+    del limiter
+    return stats
+
+
+def _to_f32(x):
+    return x.float().numpy() if isinstance(x, torch.Tensor) else np.asarray(x, dtype=np.float32)
+
+
+def tiled_jobs(spec: StreamSpec, seed: int, unit, gpu_out, gpu_evicted, t_begin: int, t_end: int, n_windows: int,
+               out_t0: int = 0, laid_down: bool = False, rope_base=None, n_pinned: int = 0):
+    """The window jobs of one unit (see the comment above).  gpu_out [t_end - out_t0 or more, H, d] holds the
+    unit's outputs from step out_t0 on (torch tensor or array; None: outputs are not compared);
+    gpu_evicted [>= t_end] is the unit's log.  laid_down: the run put tokens 0..k-1 into slots 0..k-1
+    directly and t_begin == k.  The windows tile [t_begin, t_end) without a gap (asserted)."""
+    l, b = unit
+    k = spec.k
+    assert 0 <= t_begin < t_end <= spec.T and n_windows >= 1
+    assert t_begin == (k if laid_down else 0), "the first window must start from a known state"
+    st = Stream(spec, seed, device="cpu", layers=[l], seqs=[b])
+    kk_all, vv_all, q_all = [], [], []
+    for a in range(0, t_end, 2048):                         # (contiguous from 0: drifting streams need it)
+        c = st.chunk(a, min(t_end, a + 2048), need_q=min(t_end, a + 2048) > t_begin)
+        kk_all.append(c["k"][:, 0, 0]); vv_all.append(c["v"][:, 0, 0])
+        if c["q"] is not None:
+            q_all.append((a, c["q"][:, 0, 0]))
+    kk_all, vv_all = torch.cat(kk_all), torch.cat(vv_all)              # [t_end, H_kv, d], storage dtype
+    q0 = q_all[0][0]
+    q_all = torch.cat([x for _, x in q_all])                           # steps q0 .. t_end
+    bounds = [t_begin + (t_end - t_begin) * i // n_windows for i in range(n_windows + 1)]
+    bounds = sorted(set(bounds))
+    ev = np.asarray(gpu_evicted)
+    slot_token = np.full(k, -1, dtype=np.int64)
+    t = 0
+    jobs = []
+    for a, bnd in zip(bounds[:-1], bounds[1:]):
+        while t < a:                                        # the integer log, replayed up to the window's start
+            if t < k:
+                assert laid_down or int(ev[t]) == -1, f"unit {unit} step {t}: victim logged while filling"
+                slot_token[t] = t
+            else:
+                e = int(ev[t])
+                assert 0 <= e <= k, f"unit {unit} step {t}: victim {e} out of range"
+                if e < k:
+                    slot_token[e] = t
+            t += 1
+        n = int((slot_token >= 0).sum())
+        tok = torch.from_numpy(slot_token[:n].copy())
+        jobs.append(dict(spec=spec, unit=unit, a=a, b=bnd, slot_token=slot_token.copy(),
+                         rows_k=_to_f32(kk_all[tok].permute(1, 0, 2)), rows_v=_to_f32(vv_all[tok].permute(1, 0, 2)),
+                         q=_to_f32(q_all[a - q0:bnd - q0]), k=_to_f32(kk_all[a:bnd]), v=_to_f32(vv_all[a:bnd]),
+                         out=None if gpu_out is None else _to_f32(gpu_out[a - out_t0:bnd - out_t0]),
+                         evicted=ev[a:bnd].copy(), rope_base=rope_base, n_pinned=n_pinned))
+    assert jobs[0]["a"] == t_begin and jobs[-1]["b"] == t_end
+    assert all(x["b"] == y["a"] for x, y in zip(jobs[:-1], jobs[1:])), "windows must tile the stream without a gap"
+    return jobs
+
+
+def merge_window_stats(unit, stats_list, gpu_evicted, k):
+    """Folds the windows' statistics of one unit into one record; checks that they tile and that each
+    window ended in the state the next one started from (the log's replay, again on integers)."""
+    ws = sorted(stats_list, key=lambda s: s["window"][0])
+    assert all(x["window"][1] == y["window"][0] for x, y in zip(ws[:-1], ws[1:])), "windows do not tile"
+    tot = _new_stats(unit, sum(s["steps"] for s in ws))
+    tot["windows"] = len(ws)
+    tot["t_range"] = (ws[0]["window"][0], ws[-1]["window"][1])
+    for s in ws:
+        for key in ("evict_steps", "near_tie_steps", "mismatches"):
+            tot[key] += s[key]
+        for key in ("max_rel_err", "max_gap_at_mismatch"):
+            tot[key] = max(tot[key], s[key])
+        tot["min_gap"] = min(tot["min_gap"], s["min_gap"])
+        end = s["window"][1]
+        assert np.array_equal(s["slot_token_end"], replay_slot_tokens(gpu_evicted, k, end)), \
+            f"unit {unit}: state after window {s['window']} is not what the log implies"
+    return tot
+
+
+def check_tiled(units_jobs, workers: int = 16):
+    """units_jobs: list of (unit, jobs, gpu_evicted, k).  Runs every window of every unit on a pool of
+    CPU-only processes (largest first) and returns one merged statistics record per unit."""
+    import multiprocessing as mp
+    flat = [(ui, j) for ui, (_, jobs, _, _) in enumerate(units_jobs) for j in jobs]
+    order = sorted(range(len(flat)), key=lambda i: -(flat[i][1]["b"] - flat[i][1]["a"]))
+    with mp.get_context("spawn").Pool(max(1, min(workers, len(flat)))) as pool:
+        results = pool.map(_window_job, [flat[i][1] for i in order], chunksize=1)
+    per_unit = {ui: [] for ui in range(len(units_jobs))}
+    for i, r in zip(order, results):
+        per_unit[flat[i][0]].append(r)
+    return [merge_window_stats(units_jobs[ui][0], per_unit[ui], units_jobs[ui][2], units_jobs[ui][3])
+            for ui in range(len(units_jobs))]
+
+
+def check_final_rows(spec: StreamSpec, seed: int, unit, gpu_slot_token, gpu_K, gpu_V):
+    """The rows the GPU's cache holds at the end are, bit for bit, the stream rows of the tokens its
+    slot -> token map names.  gpu_K / gpu_V [H_kv, k, d] (float32 views of the stored values)."""
+    l, b = unit
+    st = Stream(spec, seed, device="cpu", layers=[l], seqs=[b])
+    kk, vv = [], []
+    for a in range(0, spec.T, 2048):
+        c = st.chunk(a, min(spec.T, a + 2048), need_q=False)
+        kk.append(c["k"][:, 0, 0]); vv.append(c["v"][:, 0, 0])
+    kk, vv = torch.cat(kk).float().numpy(), torch.cat(vv).float().numpy()
+    tok = np.asarray(gpu_slot_token, dtype=np.int64)
+    held = tok >= 0
+    assert np.array_equal(np.asarray(gpu_K)[:, held], kk[tok[held]].transpose(1, 0, 2)), f"unit {unit}: cached K rows differ"
+    assert np.array_equal(np.asarray(gpu_V)[:, held], vv[tok[held]].transpose(1, 0, 2)), f"unit {unit}: cached V rows differ"

@@ -1,5 +1,7 @@
 """GPU parity tests: the HIP library, called through the C ABI, against the fp64 oracle on
 the same seeded streams.  Bars and the near-tie rule are defined in tests/parity.py."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -9,6 +11,8 @@ from workloads import StreamSpec, spec_for
 import parity
 
 pytestmark = pytest.mark.gpu
+
+WORKERS = max(1, min(16, os.cpu_count() or 1))       # host cores for the oracle legs (a one-GPU machine has 16)
 
 
 def _run(spec, seed, units, n_splits=0, workers=1, single_step_calls=False, chunk_steps=256):
@@ -140,54 +144,75 @@ def test_c2_llama7b_layer_full():
 
 
 def test_c3_mistral_gqa_full():
-    """Config 3 complete, in the launch configuration bench.py times (B=64, 512 workgroups):
-    every sequence's evicted log is checked for consistency; 4 sampled sequences are followed
-    by the oracle through all 3072 steps."""
+    """Config 3 complete, in the launch configuration bench.py times (B=64, 512 workgroups): ALL 64
+    sequences are followed by the oracle through all 3072 steps (1024 fill + 2048 evicting), final map
+    and cached rows bit-exact; mismatch / near-tie counts are printed per sequence."""
     spec = spec_for("c3_mistral_gqa")
-    stats, res = _run(spec, seed=3, units=[(0, 0), (0, 21), (0, 42), (0, 63)], workers=4)
+    units = [(0, b) for b in range(spec.B)]
+    stats, res = _run(spec, seed=3, units=units, workers=WORKERS)
     assert res["layout"] == (1, 1024, 512, 512)
+    assert len(stats) == 64 and all(s["steps"] == 3072 and s["evict_steps"] == 2048 for s in stats)
+    print(f"[parity] c3: 64 sequences x 3072 steps; near-tie steps {sum(s['near_tie_steps'] for s in stats)}, "
+          f"mismatches {sum(s['mismatches'] for s in stats)}, max rel err {max(s['max_rel_err'] for s in stats):.2e}", flush=True)
 
 
 def test_c4_llama7b_stack_full_shape():
-    """Config 4 at its real shape (32 layers x 64 sequences, k=4096: 128 GiB of cache, 2,048 units
-    of 32 KV heads each, a workgroup per unit).  The 4096 fill steps are replaced by laying the first 4096 tokens down
-    directly (what the no-op branch produces); then 48 decode steps at full occupancy.  Three
-    sampled units are followed by the oracle; all 2048 units are checked for consistency."""
+    """Config 4 at its real shape (32 layers x 64 sequences, k=4096: 128 GiB of cache, 2,048 units of 32
+    KV heads each, a workgroup per unit).  The 4096 fill steps are replaced by laying the first 4096
+    tokens down directly (what the no-op branch produces); then ALL 512 decode steps at full
+    occupancy.  Eight seeded units are followed by the oracle through all 512 steps (two windows per
+    unit on separate cores, see parity.check_tiled); all 2048 units are checked for consistency."""
     free, _ = torch.cuda.mem_get_info()
     if free < 150 * 2 ** 30:
         pytest.skip("needs ~135 GiB of free HBM")
-    spec = spec_for("c4_llama7b_stack", T=4096 + 48)
-    print(f"[parity] {spec.name} full shape, prefilled, T={spec.T}", flush=True)
-    units = [(0, 0), (17, 40), (31, 63)]
+    spec = spec_for("c4_llama7b_stack")
+    assert spec.T == 4096 + 512
+    print(f"[parity] {spec.name} full shape, first k tokens laid down, T={spec.T}", flush=True)
+    rng = np.random.default_rng(44)
+    units = sorted({(int(l), int(b)) for l, b in zip(rng.integers(0, spec.L, 6), rng.integers(0, spec.B, 6))}
+                   | {(0, 0), (31, 63)})[:8]
+    assert len(units) == 8
     res = parity.run_gpu(spec, 4, units, chunk_steps=16, prefill=True, progress=True)
-    parity.check_global_invariants(spec, res)
-    for s in parity.check_units(spec, 4, units, res, workers=3):
-        print(f"[parity]   {s}", flush=True)
     assert res["layout"][0] == 1 and res["unit_workgroups"] == 1 and res["layout"][3] == 2048
+    parity.check_global_invariants(spec, res)
+    todo = []
+    for ui, (l, b) in enumerate(units):
+        ev = res["evicted"][:, l, b]
+        todo.append(((l, b), parity.tiled_jobs(spec, 4, (l, b), res["out"][:, ui], ev, spec.k, spec.T, 2,
+                                               out_t0=spec.k, laid_down=True), ev, spec.k))
+    stats = parity.check_tiled(todo, workers=WORKERS)
+    for s in stats:
+        print(f"[parity]   {s}", flush=True)
+        assert s["steps"] == 512 and s["evict_steps"] == 512 and s["t_range"] == (4096, 4608)
+    for ui, (l, b) in enumerate(units[:2]):
+        parity.check_final_rows(spec, 4, (l, b), res["slot_token"][l, b], res["K"][ui], res["V"][ui])
 
 
 def test_c5_yi_long_full_stream():
-    """Config 5 complete on the GPU: 70,000 tokens through 32 layers of k=4096 (split cache).
-    Every layer's evicted log is checked for consistency over all 70,000 steps.  The oracle
-    follows one layer from the start through the fill and the first 700 evictions (parity), and
-    a second layer over a 250-step window starting at token 12,000 from the state the log
-    implies there (a property check, see parity.check_window)."""
+    """Config 5 complete: 70,000 tokens through 32 layers of k=4096 (split cache, multi-step launches).
+    Every layer's evicted log is checked for consistency over all 70,000 steps.  The oracle follows ONE
+    LAYER THROUGH THE WHOLE STREAM (all 70,000 steps: 4,096 filling + 65,904 evicting) and two more
+    layers from the empty cache through the first 2,000 evictions, each cut into windows that run on
+    separate cores and start from the state the integer log implies, rows regenerated from the stream
+    (parity.check_tiled: all windows green = parity from the empty cache by induction)."""
     spec = spec_for("c5_yi_long")
-    units = [(5, 0), (30, 0)]
-    t_par, w0, w1 = spec.k + 700, 12000, 12250
+    units = [(5, 0), (17, 0), (30, 0)]
+    t_short = spec.k + 2000
     print(f"[parity] {spec.name} full stream T={spec.T}", flush=True)
-    res = parity.run_gpu(spec, 5, units, chunk_steps=500, keep=[(0, t_par), (w0, w1)], progress=True)
+    res = parity.run_gpu(spec, 5, units, chunk_steps=500, keep=[(0, spec.T, [0]), (0, t_short, [1, 2])],
+                         progress=True, keep_native=True)
     parity.check_global_invariants(spec, res)
-    import multiprocessing as mp
     ev = res["evicted"]
-    st_w0 = parity.replay_slot_tokens(ev[:, 30, 0], spec.k, w0)
-    with mp.get_context("spawn").Pool(2) as pool:
-        a = pool.apply_async(parity.check_unit, (spec, 5, (5, 0), res["out"][(0, t_par)][:, 0], ev[:, 5, 0],
-                                                 None, None, None, t_par))
-        b = pool.apply_async(parity.check_window, (spec, 5, (30, 0), w0, w1, st_w0, res["out"][(w0, w1)][:, 1],
-                                                   ev[:, 30, 0]))
-        print(f"[parity]   from start: {a.get()}", flush=True)
-        print(f"[parity]   window    : {b.get()}", flush=True)
+    full, short = res["out"][(0, spec.T, (0,))], res["out"][(0, t_short, (1, 2))]
+    todo = [((5, 0), parity.tiled_jobs(spec, 5, (5, 0), full[:, 0], ev[:, 5, 0], 0, spec.T, 3 * WORKERS), ev[:, 5, 0], spec.k)]
+    for i, (l, b) in enumerate(units[1:]):
+        todo.append(((l, b), parity.tiled_jobs(spec, 5, (l, b), short[:, i], ev[:, l, b], 0, t_short, 4), ev[:, l, b], spec.k))
+    stats = parity.check_tiled(todo, workers=WORKERS)
+    for s in stats:
+        print(f"[parity]   {s}", flush=True)
+    assert stats[0]["steps"] == 70000 and stats[0]["evict_steps"] == 70000 - 4096 and stats[0]["t_range"] == (0, 70000)
+    assert all(s["steps"] == t_short and s["evict_steps"] == 2000 for s in stats[1:])
+    parity.check_final_rows(spec, 5, (5, 0), res["slot_token"][5, 0], res["K"][0], res["V"][0])
 
 
 # ---- split cache: the path where a chunk cannot finish its own scores -------------------------
@@ -687,32 +712,42 @@ def test_repositioned_steps_random_shapes_split_units_match_whole_units(monkeypa
 def test_repositioned_llama7b_70k_stream():
     """The paper's extrapolation setting at its real shape: one sequence of 70,000 tokens through 32
     layers of LLaMA-2-7B's shape (32 heads, d = 128, bf16) with a multi-state of 512, keys cached
-    without positions.  Every layer's evicted log is checked for consistency over all 70,000 steps;
-    the oracle follows one layer from the start through the fill and the first 400 evictions
-    (parity), and another layer over a 200-step window starting at token 60,000 -- where the
-    retained tokens lie thousands of positions apart -- from the state the log implies there (a
-    property check, see parity.check_window)."""
+    without positions.  Every layer's evicted log is checked for consistency over all 70,000 steps.
+    The oracle (which rotates every cached key at its re-assigned position in fp64 at every step: 50 ms
+    per step and core) follows one layer from the empty cache through the first 6,000 evictions and a
+    second one through the first 2,000, as tiled windows on separate cores (parity.check_tiled: parity
+    from the empty cache); a third layer is looked at over a 200-step window starting at token 60,000
+    -- where the retained tokens lie thousands of positions apart -- from the state the log implies
+    there (a property check of the transitions, see parity.check_window; the whole stream at this
+    oracle's cost would take several minutes on 16 cores)."""
     spec = spec_for("c2_llama7b_layer", L=32, T=70000)
     base = 10000.0
-    units = [(3, 0), (29, 0)]
-    t_par, w0, w1 = spec.k + 400, 60000, 60200
+    units = [(3, 0), (12, 0), (29, 0)]
+    t_a, t_b, w0, w1 = spec.k + 6000, spec.k + 2000, 60000, 60200
     print(f"[parity] {spec.name} x 32 layers, repositioned, full stream T={spec.T}", flush=True)
-    res = parity.run_gpu(spec, 6, units, chunk_steps=500, keep=[(0, t_par), (w0, w1)], progress=True, rope_base=base)
+    res = parity.run_gpu(spec, 6, units, chunk_steps=500, keep=[(0, t_a, [0]), (0, t_b, [1]), (w0, w1, [2])],
+                         progress=True, rope_base=base, keep_native=True)
     parity.check_global_invariants(spec, res)
-    import multiprocessing as mp
     ev = res["evicted"]
     st_w0 = parity.replay_slot_tokens(ev[:, 29, 0], spec.k, w0)
     held = np.sort(st_w0)
     print(f"[parity]   at token {w0}: oldest retained token {held[0]}, largest gap between neighbours "
           f"{int(np.diff(held).max())}", flush=True)
     assert np.diff(held).max() > 10                          # compressed gaps are in play
-    with mp.get_context("spawn").Pool(2) as pool:
-        a = pool.apply_async(parity.check_unit, (spec, 6, (3, 0), res["out"][(0, t_par)][:, 0], ev[:, 3, 0],
-                                                 None, None, None, t_par, False, 0, 0, base))
-        b = pool.apply_async(parity.check_window, (spec, 6, (29, 0), w0, w1, st_w0, res["out"][(w0, w1)][:, 1],
-                                                   ev[:, 29, 0], base))
-        print(f"[parity]   from start: {a.get()}", flush=True)
-        print(f"[parity]   window    : {b.get()}", flush=True)
+    import multiprocessing as mp
+    with mp.get_context("spawn").Pool(1) as pool:            # the far window, beside the tiled windows
+        far = pool.apply_async(parity.check_window, (spec, 6, (29, 0), w0, w1, st_w0,
+                                                     res["out"][(w0, w1, (2,))][:, 0].float().numpy(), ev[:, 29, 0], base))
+        todo = [((3, 0), parity.tiled_jobs(spec, 6, (3, 0), res["out"][(0, t_a, (0,))][:, 0], ev[:, 3, 0], 0, t_a,
+                                           2 * WORKERS - 6, rope_base=base), ev[:, 3, 0], spec.k),
+                ((12, 0), parity.tiled_jobs(spec, 6, (12, 0), res["out"][(0, t_b, (1,))][:, 0], ev[:, 12, 0], 0, t_b,
+                                            5, rope_base=base), ev[:, 12, 0], spec.k)]
+        stats = parity.check_tiled(todo, workers=max(1, WORKERS - 1))
+        for s_ in stats:
+            print(f"[parity]   from the empty cache: {s_}", flush=True)
+        assert stats[0]["steps"] == t_a and stats[0]["evict_steps"] == 6000
+        assert stats[1]["steps"] == t_b and stats[1]["evict_steps"] == 2000
+        print(f"[parity]   window    : {far.get()}", flush=True)
 
 
 def test_repositioned_steps_refuse_what_does_not_fit():
