@@ -52,6 +52,17 @@ typedef enum {
 
 enum { TOVA_F32 = 0, TOVA_BF16 = 1 };
 
+/* Which row leaves a full multi-state (Sec. 3.3: the compression policy).  TOVA is the paper's
+ * method (Sec. 4); the other two are the baseline policies it is compared with (Sec. 4.1). */
+enum {
+  TOVA_POLICY_TOVA = 0,   /* the row with the lowest head-averaged attention weight of the current query   */
+  TOVA_POLICY_WINDOW = 1, /* Window+i: the oldest token that is not one of the first n_pinned (i = n_pinned; */
+                          /* 0 = plain Window, first in first out).  The incoming token is always stored.     */
+  TOVA_POLICY_H2O = 2     /* H2O: the h2o_recent most recent tokens (the incoming one included) always stay;  */
+                          /* among the others the row whose attention weights, head-averaged and summed over  */
+                          /* every step since its token came in (this step included), are lowest.             */
+};
+
 typedef struct tova_cache tova_cache_t; /* opaque host-side descriptor */
 
 /* Problem statement, in the paper's terms (App. B: attn_heads, hidden_dim,
@@ -73,6 +84,14 @@ typedef struct {
                         /* serves, averaged) keeps its own rows and drops its own victim.  Then */
                         /* evicted, occupancy and slot_token have a trailing [H_kv] dimension   */
                         /* after [L][B]: evicted [L][B][H_kv], slot_token [L][B][H_kv][k].      */
+  /* Baseline policies (Sec. 4.1); 0 / 0 is TOVA.                                                    */
+  int32_t policy;       /* TOVA_POLICY_*.  WINDOW and H2O run in the workgroup-per-unit form for any */
+                        /* number of units (TOVA_ENOSUP if a KV head's logits do not fit on-chip     */
+                        /* memory) and through tova_decode_step(s) / tova_decode_steps_static /      */
+                        /* tova_prefill (token by token) only.  per_head gives the head-wise H2O the */
+                        /* paper reports; H2O takes n_pinned = 0.                                     */
+  int32_t h2o_heavy;    /* H2O: rows outside the recent window, 0 <= h < k; 0 selects floor(k / 2)   */
+                        /* ("typically half of the multi-state size"); the window is k - h tokens.   */
 } tova_config_t;
 
 /* Where things live inside the caller's buffers (byte offsets). */
@@ -93,6 +112,9 @@ typedef struct {
                                is then L * B, walked by at most a device-filling number of workgroups */
   int32_t prefill_group;    /* tokens of a prompt that share one pass over the cache in tova_prefill
                                (0: it goes token by token)                                         */
+  size_t h2o_acc_offset;    /* state_mem: float [L][B][k] (H2O only; with per_head [L][B][H_kv][k]): per slot,
+                               the attention weights summed over the query heads and over all steps
+                               since the slot's token came in (divide by H for the head average)   */
 } tova_layout_t;
 
 /* Sizes of the three caller-owned DEVICE buffers.  kv_bytes is exactly
@@ -101,13 +123,19 @@ typedef struct {
 int tova_cache_bytes(const tova_config_t* cfg, size_t* kv_bytes, size_t* state_bytes,
                      size_t* scratch_bytes);
 
-/* Offsets and launch plan for a configuration (host only, no GPU needed). */
+/* Offsets and launch plan for a configuration (host only, no GPU needed).  No passage of the
+ * paper: library bookkeeping -- where the multi-state H_t = (K_t, V_t) of Sec. 3.2 and the
+ * slot -> token map live inside the caller's buffers, and how the step kernel will be launched. */
 int tova_cache_layout(const tova_config_t* cfg, tova_layout_t* layout);
 
-/* Creates a descriptor over caller-owned DEVICE buffers of at least the sizes
- * tova_cache_bytes reports and enqueues a kernel that empties the cache
- * (occupancy 0, slot_token -1, scratch counters 0).  K/V contents are not
- * touched: empty slots are never read. */
+/* The empty multi-state H_0 of a bounded multi-state RNN with g(t) = min(t, k) (Sec. 3.1, 3.3):
+ * creates a descriptor over caller-owned DEVICE buffers of at least the sizes
+ * tova_cache_bytes reports and enqueues kernels that empty the cache
+ * (occupancy 0, slot_token -1, scratch counters 0, error flag 0, H2O sums 0).  K/V contents are
+ * not touched: empty slots are never read.
+ * The environment hooks named in this header (tuning aids and test hooks) are read here and by
+ * tova_cache_layout / tova_cache_bytes only, and kept in the descriptor: no stepping call reads
+ * the environment. */
 int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, void* state_mem,
                     void* scratch_mem, void* hip_stream);
 
@@ -123,7 +151,8 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
 int tova_decode_step(tova_cache_t* cache, const void* q, const void* k_new, const void* v_new,
                      void* out, int32_t* evicted, void* hip_stream);
 
-/* n_steps consecutive decode steps with inputs resident in device memory:
+/* n_steps consecutive decode steps (Sec. 3.2 + Sec. 4, App. B Alg. 1 once per step: the loop an
+ * autoregressive decoder runs over its bounded multi-state) with inputs resident in device memory:
  * the arrays of tova_decode_step with a leading [n_steps] dimension
  * (evicted: [n_steps][L][B], may be NULL).  Same results as n_steps calls.
  * Once the cache is full the remaining steps of a call run in ONE launch.
@@ -134,9 +163,12 @@ int tova_decode_step(tova_cache_t* cache, const void* q, const void* k_new, cons
  *  - Otherwise a workgroup stays with its (sequence, KV head[, chunk]) items for all steps;
  *    sequences advance independently of one another and the only wait in the kernel is a
  *    workgroup's wait for the victim of its own sequence's previous step.  That wait is bounded;
- *    should it ever run out, the kernel sets the int32 at error_flag_offset of state_mem and
- *    stops early (check it after synchronising the stream when results matter; tova_cache_init
- *    clears it).
+ *    should it ever run out (it cannot while all workgroups of the launch are resident, which
+ *    tova_cache_init checks against an otherwise idle device; another kernel sharing the device
+ *    can break that), the kernel sets the int32 at error_flag_offset of state_mem and stops
+ *    early.  The units are then at different steps and the cache contents are not usable:
+ *    tova_cache_status reports the condition, tova_cache_recover takes the cache back into
+ *    service from a snapshot the caller restores (see there).
  * The environment variable TOVA_MULTI_STEP=0 keeps one launch per step; TOVA_UNIT_MODE=0 / 1
  * (read by tova_cache_init / tova_cache_layout) overrides the choice between the two forms. */
 int tova_decode_steps(tova_cache_t* cache, int32_t n_steps, const void* q, const void* k_new,
@@ -157,7 +189,7 @@ int tova_decode_steps(tova_cache_t* cache, int32_t n_steps, const void* q, const
  * multi-state); whatever does not meet that (a
  * remainder shorter than a group, the last rows before the cache is full, other shapes) is
  * processed token by token through tova_decode_steps.  TOVA_PREFILL_GROUP=0 in the environment
- * turns grouping off. */
+ * (read by tova_cache_init) turns grouping off. */
 int tova_prefill(tova_cache_t* cache, int32_t n_tokens, const void* q, const void* k_new,
                  const void* v_new, void* out, int32_t* evicted, void* hip_stream);
 
@@ -181,7 +213,8 @@ int tova_prefill(tova_cache_t* cache, int32_t n_tokens, const void* q, const voi
  * error_flag_offset of state_mem and stops early, as described for tova_decode_steps.
  * Needs on-chip memory for (k + 1) * (4 * max(H / H_kv, 5) + 12) bytes plus 2.5 KiB within 152 KiB,
  * else TOVA_ENOSUP (k = 4096 fits with up to 4 query heads per KV head, k = 2048 with 8).
- * TOVA_REPOS_PARTS=n in the environment allows at most n workgroups per unit (1: never split). */
+ * TOVA_REPOS_PARTS=n in the environment (read by tova_cache_init) allows at most n workgroups
+ * per unit (1: never split). */
 int tova_decode_steps_repositioned(tova_cache_t* cache, int32_t n_steps, const void* q, const void* k_new,
                                    const void* v_new, void* out, int32_t* evicted, float rope_base,
                                    void* hip_stream);
@@ -199,13 +232,15 @@ int tova_decode_steps_repositioned(tova_cache_t* cache, int32_t n_steps, const v
 int tova_policy_step(tova_cache_t* cache, const float* attn_weights, const void* k_new,
                      const void* v_new, int32_t* evicted, void* hip_stream);
 
-/* How tova_decode_steps launches once the cache is full (decided in tova_cache_init, which asks
+/* No passage of the paper: library bookkeeping.
+ * How tova_decode_steps launches once the cache is full (decided in tova_cache_init, which asks
  * the device how many workgroups fit): *blocks = 0 -> one launch per step; otherwise the number
  * of workgroups of the single launch that runs all remaining steps of a call (with
  * unit_workgroups: of every launch).  HOST out pointer. */
 int tova_cache_multi_step_blocks(const tova_cache_t* cache, int32_t* blocks);
 
-/* Number of tokens the cache has seen since tova_cache_init (HOST out pointer). */
+/* Number of tokens the cache has seen since tova_cache_init: t of Sec. 3.1-3.3, the cache
+ * holds g(t) = min(t, k) rows (HOST out pointer). */
 int tova_cache_tokens_seen(const tova_cache_t* cache, int64_t* t);
 
 /* Checkpoint / resume.  The whole state of a cache is the caller's kv_mem and state_mem plus
@@ -235,9 +270,25 @@ int tova_cache_set_tokens_seen(tova_cache_t* cache, int64_t t);
 int tova_decode_steps_static(tova_cache_t* cache, int32_t n_steps, const void* q, const void* k_new,
                              const void* v_new, void* out, int32_t* evicted, void* hip_stream);
 
-/* Frees the host descriptor only; device buffers stay with the caller. */
+/* Failure handling of the multi-step launches (no passage of the paper: library bookkeeping).
+ * tova_cache_status waits for the stream (hipStreamSynchronize) and reads the cache's error flag:
+ * *gave_up = 1 if a multi-step launch of tova_decode_steps / tova_decode_steps_static /
+ * tova_decode_steps_repositioned ran out of its bounded wait since the flag was last cleared, else
+ * 0.  HOST out pointer.  The one call of this library that synchronises. */
+int tova_cache_status(tova_cache_t* cache, void* hip_stream, int32_t* gave_up);
+
+/* After tova_cache_status reported 1: the caller copies a snapshot of kv_mem and state_mem taken
+ * after `tokens_seen` tokens back into place (the library keeps none), then calls this.  It
+ * enqueues kernels that clear the error flag and every hand-off counter in scratch_mem, sets the
+ * token count to `tokens_seen`, and makes this cache use one launch per step from now on (the
+ * launch mode in which no workgroup waits for another), so the steps can simply be issued again. */
+int tova_cache_recover(tova_cache_t* cache, int64_t tokens_seen, void* hip_stream);
+
+/* Frees the host descriptor only; device buffers stay with the caller (no passage of the paper:
+ * library bookkeeping). */
 int tova_cache_destroy(tova_cache_t* cache);
 
+/* Text for a tova_status (no passage of the paper: library bookkeeping). */
 const char* tova_strerror(int status);
 
 #ifdef __cplusplus

@@ -14,6 +14,7 @@ from typing import Optional
 
 TOVA_OK, TOVA_EINVAL, TOVA_ENOSUP, TOVA_EHIP, TOVA_ENOMEM, TOVA_ETOOBIG = 0, -1, -2, -3, -4, -5
 TOVA_F32, TOVA_BF16 = 0, 1
+TOVA_POLICY_TOVA, TOVA_POLICY_WINDOW, TOVA_POLICY_H2O = 0, 1, 2
 
 _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 _LIB: Optional[ctypes.CDLL] = None
@@ -29,14 +30,14 @@ class TovaConfig(ctypes.Structure):
     _fields_ = [("n_layers", c_int32), ("batch", c_int32), ("capacity_k", c_int32),
                 ("n_q_heads", c_int32), ("n_kv_heads", c_int32), ("head_dim", c_int32),
                 ("dtype", c_int32), ("softmax_scale", c_float), ("n_splits", c_int32),
-                ("n_pinned", c_int32), ("per_head", c_int32)]
+                ("n_pinned", c_int32), ("per_head", c_int32), ("policy", c_int32), ("h2o_heavy", c_int32)]
 
 
 class TovaLayout(ctypes.Structure):
     _fields_ = [("k_offset", c_size_t), ("v_offset", c_size_t), ("occupancy_offset", c_size_t),
                 ("slot_token_offset", c_size_t), ("error_flag_offset", c_size_t), ("n_splits", c_int32), ("rows_per_split", c_int32),
                 ("block_threads", c_int32), ("grid_blocks", c_int32), ("lds_bytes", c_int32),
-                ("unit_workgroups", c_int32), ("prefill_group", c_int32)]
+                ("unit_workgroups", c_int32), ("prefill_group", c_int32), ("h2o_acc_offset", c_size_t)]
 
 
 def library_path() -> str:
@@ -73,13 +74,15 @@ def load_library() -> ctypes.CDLL:
     lib.tova_cache_tokens_seen.argtypes = [c_void_p, POINTER(c_int64)]
     lib.tova_cache_multi_step_blocks.argtypes = [c_void_p, POINTER(c_int32)]
     lib.tova_cache_set_tokens_seen.argtypes = [c_void_p, c_int64]
+    lib.tova_cache_status.argtypes = [c_void_p, c_void_p, POINTER(c_int32)]
+    lib.tova_cache_recover.argtypes = [c_void_p, c_int64, c_void_p]
     lib.tova_cache_destroy.argtypes = [c_void_p]
     lib.tova_strerror.argtypes = [c_int]
     lib.tova_strerror.restype = c_char_p
     for name in ("tova_cache_bytes", "tova_cache_layout", "tova_cache_init", "tova_decode_step",
                  "tova_decode_steps", "tova_decode_steps_static", "tova_prefill", "tova_cache_tokens_seen", "tova_cache_set_tokens_seen",
-                 "tova_cache_multi_step_blocks",
-                 "tova_cache_destroy"):
+                 "tova_cache_multi_step_blocks", "tova_cache_status", "tova_cache_recover",
+                 "tova_decode_steps_repositioned", "tova_policy_step", "tova_cache_destroy"):
         getattr(lib, name).restype = c_int
     _LIB = lib
     return lib
@@ -118,14 +121,16 @@ class TovaCache:
     def __init__(self, n_layers: int, batch: int, capacity_k: int, n_q_heads: int, n_kv_heads: int,
                  head_dim: int, dtype="bf16", softmax_scale: float = 0.0, n_splits: int = 0,
                  device="cuda:0", stream=None, n_pinned: int = 0, per_head: bool = False,
-                 own_scratch: bool = True):
+                 own_scratch: bool = True, policy="tova", h2o_heavy: int = 0):
         import torch
         self._torch = torch
         self.lib = load_library()
         code = {"f32": TOVA_F32, "fp32": TOVA_F32, "float32": TOVA_F32, torch.float32: TOVA_F32,
                 "bf16": TOVA_BF16, "bfloat16": TOVA_BF16, torch.bfloat16: TOVA_BF16}[dtype]
+        pol = {"tova": TOVA_POLICY_TOVA, "window": TOVA_POLICY_WINDOW, "h2o": TOVA_POLICY_H2O}.get(policy, policy)
         self.cfg = TovaConfig(n_layers, batch, capacity_k, n_q_heads, n_kv_heads, head_dim, code,
-                              float(softmax_scale), int(n_splits), int(n_pinned), int(bool(per_head)))
+                              float(softmax_scale), int(n_splits), int(n_pinned), int(bool(per_head)),
+                              int(pol), int(h2o_heavy))
         # shape of evicted / occupancy (slot_token: + [k]); TOVA-head keeps them per KV head
         self.state_shape = (n_layers, batch, n_kv_heads) if per_head else (n_layers, batch)
         self.torch_dtype = torch.float32 if code == TOVA_F32 else torch.bfloat16
@@ -178,6 +183,16 @@ class TovaCache:
         return self.state_mem[o:o + 4 * n].view(self._torch.int32).view(*self.state_shape, c.capacity_k)
 
     @property
+    def h2o_acc(self):
+        """H2O: per slot, the attention weights summed over query heads and over the steps since its token came in."""
+        c = self.cfg
+        o = self.layout.h2o_acc_offset
+        n = c.capacity_k
+        for x in self.state_shape:
+            n *= x
+        return self.state_mem[o:o + 4 * n].view(self._torch.float32).view(*self.state_shape, c.capacity_k)
+
+    @property
     def error_flag(self):
         o = self.layout.error_flag_offset
         return self.state_mem[o:o + 4].view(self._torch.int32)
@@ -197,6 +212,20 @@ class TovaCache:
         if rc != TOVA_OK:
             raise TovaError(rc, "tova_cache_tokens_seen")
         return t.value
+
+    def status(self, stream=None) -> int:
+        """Waits for the stream; 1 if a multi-step launch gave up waiting since the flag was last cleared."""
+        f = c_int32()
+        rc = self.lib.tova_cache_status(self._h, _stream_handle(stream), byref(f))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_cache_status")
+        return f.value
+
+    def recover(self, tokens_seen: int, stream=None):
+        """After status() == 1 and after the caller restored kv_mem / state_mem from its snapshot."""
+        rc = self.lib.tova_cache_recover(self._h, int(tokens_seen), _stream_handle(stream))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_cache_recover")
 
     def set_tokens_seen(self, t: int):
         rc = self.lib.tova_cache_set_tokens_seen(self._h, int(t))

@@ -30,6 +30,8 @@ size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct Resolved {
   int L, B, k, H, H_kv, G, D, esize, bf16;
   int n_pinned, per_head;
+  int policy, h2o_recent;  // TOVA_POLICY_*; H2O: tokens of the recent window, the incoming one included
+  size_t acc_off;          // in state_mem: H2O's aggregated weights [units][k] (0 bytes for the other policies)
   int units, pairs, S, R, kp, NT, grid, lds, st_off, spin_limit, force_slow, persist_spin, multi_step, multi_grid, spin_env;
   int unit_mode;  // one workgroup per unit instead of one per (unit, KV head, chunk)
   int pf_C, pf_NT, pf_lds, pf_e_floats, pf_ncp;  // multi-token kernel: tokens per group (0 = not available) and its LDS plan
@@ -52,6 +54,10 @@ int resolve(const tova_config_t* c, Resolved* r) {
   if (c->dtype != TOVA_F32 && c->dtype != TOVA_BF16) return TOVA_EINVAL;
   if (!(c->softmax_scale == c->softmax_scale)) return TOVA_EINVAL;  // NaN
   if (c->n_pinned < 0 || c->n_pinned >= c->capacity_k) return TOVA_EINVAL;
+  if (c->policy != TOVA_POLICY_TOVA && c->policy != TOVA_POLICY_WINDOW && c->policy != TOVA_POLICY_H2O) return TOVA_EINVAL;
+  if (c->h2o_heavy < 0 || c->h2o_heavy >= c->capacity_k) return TOVA_EINVAL;
+  if (c->policy == TOVA_POLICY_H2O && c->n_pinned != 0) return TOVA_EINVAL;
+  if (c->policy != TOVA_POLICY_H2O && c->h2o_heavy != 0) return TOVA_EINVAL;
   const int G = c->n_q_heads / c->n_kv_heads;
   if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return TOVA_ENOSUP;
   if (G != 1 && G != 2 && G != 4 && G != 8) return TOVA_ENOSUP;
@@ -67,6 +73,9 @@ int resolve(const tova_config_t* c, Resolved* r) {
   r->units = (int)units; r->pairs = (int)pairs;
   r->n_pinned = c->n_pinned;
   r->per_head = (c->per_head != 0);
+  r->policy = c->policy;
+  // H2O (Sec. 4.1): h rows outside the window ("typically half of the multi-state size"), k - h inside
+  r->h2o_recent = c->capacity_k - (c->h2o_heavy > 0 ? c->h2o_heavy : c->capacity_k / 2);
   if (r->per_head) {
     // TOVA-head is the same computation with every KV head as a unit of its own: q [L][B][H][d] is
     // [L*B*H_kv][G][d], K/V [L][B][H_kv][k][d] is [L*B*H_kv][1][k][d]; nothing else changes.
@@ -93,7 +102,10 @@ int resolve(const tova_config_t* c, Resolved* r) {
   {
     int want = (r->units >= kUnitModeUnits);
     if (const char* e = std::getenv("TOVA_UNIT_MODE")) want = (std::atoi(e) != 0);  // tuning aid / test hook
-    if (want && c->n_splits <= 1) {
+    // the baseline policies pick their victim inside the workgroup that owns the unit (Window from the
+    // slot -> token map, H2O from per-slot sums it alone updates): this form, whatever the unit count
+    if (r->policy != TOVA_POLICY_TOVA) want = 1;
+    if (want && (c->n_splits <= 1 || r->policy != TOVA_POLICY_TOVA)) {
       const long long e_fl = ((long long)(k + 1) * G + 3) / 4 * 4;
       const long long s_fl = ((long long)k + 1 + 3) / 4 * 4;
       int nt = nt_env ? nt_env : ((k >= 512 && G < 8) ? 512 : 256);
@@ -112,10 +124,12 @@ int resolve(const tova_config_t* c, Resolved* r) {
     }
   }
 
+  if (r->policy != TOVA_POLICY_TOVA && !r->unit_mode) return TOVA_ENOSUP;  // (a KV head's logits do not fit LDS)
+
   // ---- groups of C prompt tokens per pass over the cache (workgroup-per-unit form only) ----
   // C * G (token, head) combinations share a streamed row; the vector passes hold at most 8.
   r->pf_C = 0;
-  if (r->unit_mode) {
+  if (r->unit_mode && r->policy == TOVA_POLICY_TOVA) {
     const int cands[3] = {8, 4, 2};
     for (int ci = 0; ci < 3 && !r->pf_C; ++ci) {
       const int C = cands[ci], GE = G * C;
@@ -219,7 +233,8 @@ int resolve(const tova_config_t* c, Resolved* r) {
   r->occ_off = 0;
   r->slot_off = round_up((size_t)r->units * 4, kAlign);
   r->err_off = r->slot_off + round_up((size_t)r->units * k * 4, kAlign);
-  r->state_bytes = r->err_off + kAlign;
+  r->acc_off = r->err_off + kAlign;
+  r->state_bytes = r->acc_off + (r->policy == TOVA_POLICY_H2O ? round_up((size_t)r->units * k * 4, kAlign) : 0);
 
   size_t off = 0;
   r->cnt_pair_off = off; off += round_up((size_t)r->pairs * 4, kAlign);
@@ -260,6 +275,10 @@ struct tova_cache {
   char* state;
   char* scratch;
   int64_t t;  // tokens seen
+  // environment hooks, read once in tova_cache_init
+  int prefill_group_off;  // TOVA_PREFILL_GROUP=0: prompts go token by token
+  int repos_threads;      // TOVA_REPOS_THREADS (0: the plan's own choice)
+  int repos_parts;        // TOVA_REPOS_PARTS (0: no limit given)
 };
 
 extern "C" {
@@ -292,6 +311,7 @@ int tova_cache_layout(const tova_config_t* cfg, tova_layout_t* layout) {
   layout->lds_bytes = r.lds;
   layout->unit_workgroups = r.unit_mode;
   layout->prefill_group = r.pf_C;
+  layout->h2o_acc_offset = r.acc_off;
   return TOVA_OK;
 }
 
@@ -312,6 +332,18 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
   c->state = static_cast<char*>(state_mem);
   c->scratch = static_cast<char*>(scratch_mem);
   c->t = 0;
+  c->prefill_group_off = 0;
+  if (const char* e = std::getenv("TOVA_PREFILL_GROUP")) c->prefill_group_off = (std::atoi(e) == 0);  // test hook
+  c->repos_threads = 0;
+  if (const char* e = std::getenv("TOVA_REPOS_THREADS")) {  // tuning aid
+    const int v = std::atoi(e);
+    if (v >= 64 && v <= 512 && v % 64 == 0) c->repos_threads = v;
+  }
+  c->repos_parts = 0;
+  if (const char* e = std::getenv("TOVA_REPOS_PARTS")) {  // tuning aid / test hook: at most this many parts
+    const int v = std::atoi(e);
+    if (v >= 1) c->repos_parts = v;
+  }
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   // fill kernels, not memsets, so that the call can be recorded into a HIP graph
   hipError_t e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->state + r.occ_off), 0,
@@ -323,6 +355,8 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
     e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->scratch), 0, r.cnt_bytes / 4, s);
   if (e == hipSuccess)
     e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->state + r.err_off), 0, 1, s);
+  if (e == hipSuccess && r.policy == TOVA_POLICY_H2O)  // (0.0f is the all-zero word)
+    e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->state + r.acc_off), 0, (size_t)r.units * r.k, s);
   // A multi-step launch needs all its blocks resident at once (blocks of a unit wait for each
   // other's results): its grid is capped at what the device can hold, and each block then walks
   // several (unit, KV head) pairs per step.
@@ -344,7 +378,11 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
       if (v >= 1 && v <= r.grid) c->r.multi_grid = v;
     }
   } else if (c->r.multi_step) {
-    const int want = r.grid;
+    int want = r.grid;
+    if (const char* ev = std::getenv("TOVA_MULTI_GRID")) {  // tuning aid: fewer workgroups, several items each per step
+      const int v = std::atoi(ev) / 8 * 8;
+      if (v >= 8 && v < want) want = v;
+    }
     c->r.multi_grid = want < cap ? want : cap;   // never more blocks than fit at once
     if (c->r.multi_grid < 8) c->r.multi_step = 0;
   }
@@ -387,10 +425,7 @@ int tova_prefill(tova_cache_t* c, int32_t n_tokens, const void* q, const void* k
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const size_t q_step = (size_t)r.units * r.H * r.D * r.esize;
   const size_t kv_step = (size_t)r.pairs * r.D * r.esize;
-  int C = r.pf_C;
-  if (const char* e = std::getenv("TOVA_PREFILL_GROUP")) {  // test hook: 0 = token by token
-    if (std::atoi(e) == 0) C = 0;
-  }
+  const int C = c->prefill_group_off ? 0 : r.pf_C;
   for (int32_t i = 0; i < n_tokens;) {
     const void* qi = static_cast<const char*>(q) + (size_t)i * q_step;
     const void* ki = static_cast<const char*>(k_new) + (size_t)i * kv_step;
@@ -469,6 +504,8 @@ int decode_steps_on(tova_cache* c, char* scratch, int32_t n_steps, const void* q
   p.accp = reinterpret_cast<float*>(scratch + r.accp_off);
   p.accp_half = (int64_t)(round_up((size_t)r.pairs * r.S * r.G * r.D * 4, kAlign) / 4);
   p.pairs = r.pairs; p.H = r.H; p.H_kv = r.H_kv; p.k = r.k; p.n_pinned = r.n_pinned;
+  p.policy = r.policy; p.h2o_recent = r.h2o_recent;
+  p.acc = reinterpret_cast<float*>(c->state + r.acc_off);
   p.S = r.S; p.R = r.R; p.kp = r.kp; p.scale = r.scale;
   const tova::LaunchPlan lp{r.grid, r.NT, r.lds};
 
@@ -548,6 +585,7 @@ int tova_decode_steps_repositioned(tova_cache_t* c, int32_t n_steps, const void*
       !aligned(evicted, 4))
     return TOVA_EINVAL;
   const Resolved& r = c->r;
+  if (r.policy != TOVA_POLICY_TOVA) return TOVA_ENOSUP;
   if (c->t + n_steps > 0x7fffffffLL) return TOVA_ENOSUP;  // token index is kept in 32 bits
   // LDS of a workgroup: logits of the k + 1 candidates of a KV head's G query heads (the position
   // scratch, 20 bytes per candidate, and the PV reduction area share that memory), the head-summed
@@ -571,10 +609,7 @@ int tova_decode_steps_repositioned(tova_cache_t* c, int32_t n_steps, const void*
   long long e_fl = 0, lds = 0;
   for (int pass = 0; pass < 2; ++pass) {
     nt = (pass == 0) ? 256 : ((r.k >= 512) ? 512 : 256);
-    if (const char* ev = std::getenv("TOVA_REPOS_THREADS")) {  // tuning aid
-      const int v = std::atoi(ev);
-      if (v >= 64 && v <= 512 && v % 64 == 0) nt = v;
-    }
+    if (c->repos_threads) nt = c->repos_threads;
     plan(nt, &e_fl, &lds, &persist);
     per_cu = (int)((160 * 1024) / lds);
     if (per_cu > 2) per_cu = 2;
@@ -594,10 +629,7 @@ int tova_decode_steps_repositioned(tova_cache_t* c, int32_t n_steps, const void*
     plan(256, &e_fl_p, &lds_p, &persist_p);
     const int cap = tova::repos_resident_blocks(r.bf16, r.D, r.G, 256, (int)lds_p);
     int limit = 2 * cus < cap ? 2 * cus : cap;
-    if (const char* ev = std::getenv("TOVA_REPOS_PARTS")) {  // tuning aid / test hook: at most this many parts
-      const int v = std::atoi(ev);
-      if (v >= 1 && (long long)v * r.units < limit) limit = v * r.units;
-    }
+    if (c->repos_parts && (long long)c->repos_parts * r.units < limit) limit = c->repos_parts * r.units;
     for (int pcand = r.H_kv; pcand >= 2; --pcand)
       if (r.H_kv % pcand == 0 && (long long)r.units * pcand <= limit && (size_t)pcand * kp <= (size_t)r.H_kv * r.kp) {
         parts = pcand;
@@ -659,6 +691,7 @@ int tova_policy_step(tova_cache_t* c, const float* attn_weights, const void* k_n
   if (!aligned(attn_weights, 4) || !aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(evicted, 4))
     return TOVA_EINVAL;
   const Resolved& r = c->r;
+  if (r.policy != TOVA_POLICY_TOVA) return TOVA_ENOSUP;
   if (c->t + 1 > 0x7fffffffLL) return TOVA_ENOSUP;  // token index is kept in 32 bits
   tova::PolicyParams p;
   p.w = attn_weights; p.k_new = k_new; p.v_new = v_new; p.evicted = evicted;
@@ -697,6 +730,31 @@ int tova_cache_set_tokens_seen(tova_cache_t* c, int64_t t) {
   if (!c || t < 0) return TOVA_EINVAL;
   if (t > 0x7fffffffLL) return TOVA_ENOSUP;
   c->t = t;
+  return TOVA_OK;
+}
+
+int tova_cache_status(tova_cache_t* c, void* hip_stream, int32_t* gave_up) {
+  if (!c || !gave_up) return TOVA_EINVAL;
+  int32_t flag = 0;
+  const hipError_t e = tova::read_i32_sync(reinterpret_cast<const int32_t*>(c->state + c->r.err_off),
+                                           static_cast<hipStream_t>(hip_stream), &flag);
+  if (e != hipSuccess) return hip_fail(e, "tova_cache_status");
+  *gave_up = (flag != 0);
+  return TOVA_OK;
+}
+
+int tova_cache_recover(tova_cache_t* c, int64_t tokens_seen, void* hip_stream) {
+  if (!c || tokens_seen < 0) return TOVA_EINVAL;
+  if (tokens_seen > 0x7fffffffLL) return TOVA_ENOSUP;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->state + c->r.err_off), 0, 1, s);
+  if (e == hipSuccess && c->scratch)  // arrival counters, slow-route flags, state words: as after tova_cache_init
+    e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->scratch), 0, c->r.cnt_bytes / 4, s);
+  if (e != hipSuccess) return hip_fail(e, "tova_cache_recover");
+  c->t = tokens_seen;
+  // A launch whose workgroups wait for one another has failed once on this device: from here on
+  // this cache steps with one launch per step, where nobody waits for anybody.
+  if (!c->r.unit_mode) c->r.multi_step = 0;
   return TOVA_OK;
 }
 

@@ -8,6 +8,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace tova {
 namespace {
 
@@ -167,6 +169,40 @@ __device__ __forceinline__ void block_reduce(float (&v)[G], float* red, int lane
   }
 }
 
+// Block-wide argmin of (value, index) pairs, the lowest index winning ties: every wave reduces its
+// lanes by butterfly shuffles, lane 0 posts the wave's pair, and after one barrier every thread
+// combines the posted pairs in wave order.  `red` holds 2 * kMaxWaves words and must not be in use.
+template <typename V>  // float scores, or int token indices
+__device__ __forceinline__ void block_argmin(V& best, int& bj, float* red, int lane, int wave, int nw) {
+  static_assert(sizeof(V) == 4, "one word per posted value");
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const V ob = __shfl_xor(best, o);
+    const int oj = __shfl_xor(bj, o);
+    if (ob < best || (ob == best && oj < bj)) {
+      best = ob;
+      bj = oj;
+    }
+  }
+  V* bv = reinterpret_cast<V*>(red);
+  int* bi = reinterpret_cast<int*>(red + kMaxWaves);
+  if (lane == 0) {
+    bv[wave] = best;
+    bi[wave] = bj;
+  }
+  __syncthreads();
+  best = bv[0];
+  bj = bi[0];
+  for (int w = 1; w < nw; ++w) {
+    const V ob = bv[w];
+    const int oj = bi[w];
+    if (ob < best || (ob == best && oj < bj)) {
+      best = ob;
+      bj = oj;
+    }
+  }
+}
+
 // Cross-workgroup hand-off.  A full agent-scope release fence writes back the whole L2 of
 // the XCD and an acquire fence invalidates it; issued by every wave of every workgroup that
 // costs far more than the step's entire K/V stream.  Instead, everything one workgroup hands
@@ -290,6 +326,22 @@ struct Geo {
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
+
+// A kernel that wants more dynamic LDS than the 64 KB default has to be told so.  Done once per
+// (kernel instantiation, device) for the largest size seen so far, not at every launch.
+template <auto Kernel>
+inline hipError_t ensure_dynamic_lds(int bytes) {
+  constexpr int kDevices = 64;
+  static std::atomic<int> granted[kDevices];  // zero-initialised; one array per instantiation
+  if (bytes <= 64 * 1024) return hipSuccess;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < kDevices && granted[dev].load(std::memory_order_acquire) >= bytes) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && dev >= 0 && dev < kDevices) granted[dev].store(bytes, std::memory_order_release);
+  return e;
+}
 
 // ------------------------------------------------------------------ streaming passes
 // Both kernels stream a KV head's rows twice per token (group): once through the logit pass (K),

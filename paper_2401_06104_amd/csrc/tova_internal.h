@@ -11,6 +11,9 @@ namespace tova {
 
 
 
+// Which row leaves a full multi-state (tova_config_t.policy).
+enum { kPolicyTova = 0, kPolicyWindow = 1, kPolicyH2O = 2 };
+
 // Arguments of one step launch (one token for every unit).
 struct StepParams {
   const void* q;       // [units][H][d]
@@ -46,6 +49,9 @@ struct StepParams {
   int32_t pairs;       // units * H_kv
   int32_t H, H_kv, k;
   int32_t n_pinned;    // candidates 0..n_pinned-1 are never the victim
+  int32_t policy;      // kPolicyTova / kPolicyWindow / kPolicyH2O (the last two: unit_mode only)
+  int32_t h2o_recent;  // H2O: the most recent tokens, the incoming one included, that cannot leave
+  float* acc;          // H2O: [units][k] head-summed attention weights aggregated per slot
   int32_t n;           // rows cached before this step, min(t, k)
   int32_t S, R;        // chunks per KV head, slots per chunk
   int32_t kp;          // k + 1 rounded up to 64: stride of sg / escr
@@ -140,6 +146,8 @@ hipError_t launch_repos(int dtype_is_bf16, int D, int G, const ReposParams& p, c
 int repos_resident_blocks(int dtype_is_bf16, int D, int G, int block, int lds_bytes);
 hipError_t launch_policy(const PolicyParams& p, hipStream_t stream);
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_t stream);
+// waits for the stream, then copies one int32 from device memory to *host
+hipError_t read_i32_sync(const int32_t* dev, hipStream_t stream, int32_t* host);
 // how many blocks of the step kernel (given instantiation, block size, dynamic LDS) fit on the
 // current device at once; 0 if the query fails
 int resident_blocks(int dtype_is_bf16, int D, int G, int block, int lds_bytes, int unit_mode);

@@ -221,7 +221,7 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
   bool have_stats = false;            // sl holds the final statistics of every chunk
   int slow = 0;                       // this chunk's score rows are left to the pair finisher
   if (S == 1) {
-    if (full) {
+    if (full || (UNIT && p.policy == kPolicyH2O)) {  // (H2O aggregates the weights of every step, Sec. 4.1)
       float rz[G];
 #pragma unroll
       for (int g = 0; g < G; ++g) rz[g] = 1.0f / Z[g];
@@ -498,32 +498,7 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
         scan_scores<4 * JM, 4>(sgu, p.H_kv, p.kp, k, p.n_pinned, tid, nt, best, bj);
       else
         scan_scores<2 * JM, 8>(sgu, p.H_kv, p.kp, k, p.n_pinned, tid, nt, best, bj);
-#pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) {
-        float ob = __shfl_xor(best, o);
-        int oj = __shfl_xor(bj, o);
-        if (ob < best || (ob == best && oj < bj)) {
-          best = ob;
-          bj = oj;
-        }
-      }
-      float* bv = small + 256;
-      int* bi = reinterpret_cast<int*>(small + 256 + kMaxWaves);
-      if (lane == 0) {
-        bv[wave] = best;
-        bi[wave] = bj;
-      }
-      __syncthreads();
-      best = bv[0];
-      bj = bi[0];
-      for (int w = 1; w < nw; ++w) {
-        float ob = bv[w];
-        int oj = bi[w];
-        if (ob < best || (ob == best && oj < bj)) {
-          best = ob;
-          bj = oj;
-        }
-      }
+      block_argmin(best, bj, small + 256, lane, wave, nw);
       if (bj > k) bj = k;  // only reachable with non-finite scores
       if (bj < k && !MULTI) {
         T* Ku = reinterpret_cast<T*>(p.K) + ((size_t)unit * p.H_kv * k + bj) * D;
@@ -581,7 +556,45 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
     const T* kn = reinterpret_cast<const T*>(p.k_new) + (size_t)it * p.kv_stride + (size_t)pair0 * D;
     const T* vn = reinterpret_cast<const T*>(p.v_new) + (size_t)it * p.kv_stride + (size_t)pair0 * D;
     int slot = n;  // below capacity (App. B: num_kv <= cache_max_size) the new row takes slot n
-    if (full) {
+    if (p.policy == kPolicyH2O) {
+      // H2O (Sec. 4.1): every row carries the sum of its head-summed weights over all steps since
+      // its token came in; this step's weights are added first, then the row with the lowest sum
+      // outside the window of the h2o_recent most recent tokens (the incoming one included) leaves.
+      // A thread owns the slots j = tid, tid + nt, ...: ascending with a strict <, lowest index on ties.
+      float* accu = p.acc + (size_t)unit * k;
+      const int32_t* stu = p.slot_token + (size_t)unit * k;
+      float best = INFINITY;
+      int bj = 0x7fffffff;
+      for (int j = tid; j < n; j += nt) {
+        const float a = accu[j] + s_lds[j];
+        accu[j] = a;
+        if (full && stu[j] <= tok - p.h2o_recent && a < best) {
+          best = a;
+          bj = j;
+        }
+      }
+      if (full) {
+        block_argmin(best, bj, small + 256, lane, wave, nw);
+        slot = bj < k ? bj : 0;  // (bj >= k is only reachable with non-finite weights)
+      }
+      // the incoming token starts its own sum -- written by the thread that owns the slot, after its
+      // own update of the same entry above
+      if (tid == slot % nt) accu[slot] = s_lds[n];
+    } else if (full && p.policy == kPolicyWindow) {
+      // Window+i (Sec. 4.1): the oldest token that is not one of the first n_pinned leaves; taken from
+      // the slot -> token map, so any restored state is handled (tokens are distinct: no ties)
+      const int32_t* stu = p.slot_token + (size_t)unit * k;
+      int bt = 0x7fffffff, bj = 0x7fffffff;
+      for (int j = tid; j < k; j += nt) {
+        const int tj = stu[j];
+        if (tj >= p.n_pinned && tj < bt) {
+          bt = tj;
+          bj = j;
+        }
+      }
+      block_argmin(bt, bj, small + 256, lane, wave, nw);
+      slot = bj < k ? bj : k - 1;  // (bj >= k is only reachable with a corrupt map)
+    } else if (full) {
       // argmin of the head sums (the factor 1/H does not move it): a thread goes through its
       // candidates in ascending order with a strict <, so the lowest index wins ties; candidates
       // below n_pinned are kept out (TOVA+i, App. A)
@@ -594,32 +607,7 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
           bj = j;
         }
       }
-#pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) {
-        float ob = __shfl_xor(best, o);
-        int oj = __shfl_xor(bj, o);
-        if (ob < best || (ob == best && oj < bj)) {
-          best = ob;
-          bj = oj;
-        }
-      }
-      float* bv = small + 256;
-      int* bi = reinterpret_cast<int*>(small + 256 + kMaxWaves);
-      if (lane == 0) {
-        bv[wave] = best;
-        bi[wave] = bj;
-      }
-      __syncthreads();
-      best = bv[0];
-      bj = bi[0];
-      for (int w = 1; w < nw; ++w) {
-        float ob = bv[w];
-        int oj = bi[w];
-        if (ob < best || (ob == best && oj < bj)) {
-          best = ob;
-          bj = oj;
-        }
-      }
+      block_argmin(best, bj, small + 256, lane, wave, nw);
       if (bj > k) bj = k;  // only reachable with non-finite scores
       slot = bj;
     }
@@ -688,11 +676,9 @@ __global__ void tova_fill_i32_kernel(int32_t* dst, int32_t value, size_t count) 
 template <typename T, int D, int G>
 hipError_t launch_one(const StepParams& p, const LaunchPlan& lp, hipStream_t stream) {
   if (p.unit_mode) {
-    if (lp.lds_bytes > 64 * 1024) {  // more dynamic LDS than the default limit: say so (a workgroup per CU)
-      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tova_step_kernel<T, D, G, true, true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, lp.lds_bytes);
-      if (e != hipSuccess) return e;
-    }
+    // more dynamic LDS than the default limit: say so (a workgroup per CU), once per size and device
+    const hipError_t e = ensure_dynamic_lds<&tova_step_kernel<T, D, G, true, true>>(lp.lds_bytes);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((tova_step_kernel<T, D, G, true, true>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes, stream, p);
   }
   else if (p.persistent)
@@ -740,6 +726,12 @@ int device_cus() {
   if (hipGetDevice(&dev) != hipSuccess) return 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
   return cus;
+}
+
+hipError_t read_i32_sync(const int32_t* dev, hipStream_t stream, int32_t* host) {
+  hipError_t e = hipStreamSynchronize(stream);
+  if (e != hipSuccess) return e;
+  return hipMemcpy(host, dev, sizeof(int32_t), hipMemcpyDeviceToHost);
 }
 
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_t stream) {

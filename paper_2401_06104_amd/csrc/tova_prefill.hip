@@ -380,9 +380,8 @@ template <typename T, int D>
 hipError_t launch_gc(int G, int C, const PrefillParams& p, const LaunchPlan& lp, hipStream_t s) {
 #define TOVA_PREFILL_CASE(g, c)                                                                              \
   if (G == g && C == c) {                                                                                    \
-    if (lp.lds_bytes > 64 * 1024) {                                                                          \
-      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tova_prefill_kernel<T, D, g, c>), \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, lp.lds_bytes);   \
+    {                                                                                                        \
+      const hipError_t e = ensure_dynamic_lds<&tova_prefill_kernel<T, D, g, c>>(lp.lds_bytes);               \
       if (e != hipSuccess) return e;                                                                         \
     }                                                                                                        \
     hipLaunchKernelGGL((tova_prefill_kernel<T, D, g, c>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes, s, p); \

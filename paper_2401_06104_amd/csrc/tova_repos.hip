@@ -540,9 +540,8 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
 
 template <typename T, int D, int G>
 hipError_t launch_repos_one(const ReposParams& p, const LaunchPlan& lp, hipStream_t stream) {
-  if (lp.lds_bytes > 64 * 1024) {  // more dynamic LDS than the default limit: say so
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tova_repos_kernel<T, D, G>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, lp.lds_bytes);
+  {  // more dynamic LDS than the default limit: say so, once per size and device
+    const hipError_t e = ensure_dynamic_lds<&tova_repos_kernel<T, D, G>>(lp.lds_bytes);
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL((tova_repos_kernel<T, D, G>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes, stream, p);

@@ -28,7 +28,7 @@ GAP_EXEMPT = 1e-6
 def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: int = 256,
             single_step_calls: bool = False, device="cuda:0", prefill: bool = False, keep=None,
             progress: bool = False, n_pinned: int = 0, per_head: bool = False, use_prefill: bool = False,
-            rope_base=None, keep_native: bool = False):
+            rope_base=None, keep_native: bool = False, policy="tova", h2o_heavy: int = 0):
     """units: list of (layer, seq) whose outputs are kept.  Returns a dict of CPU arrays.
 
     prefill=True skips the fill phase: the first k tokens are laid down directly (slot j holds
@@ -47,7 +47,8 @@ def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: 
 
     dev = torch.device(device)
     cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype,
-                      n_splits=n_splits, device=dev, n_pinned=n_pinned, per_head=per_head)
+                      n_splits=n_splits, device=dev, n_pinned=n_pinned, per_head=per_head, policy=policy,
+                      h2o_heavy=h2o_heavy)
     stream = Stream(spec, seed, device=dev)
     evicted = torch.full((spec.T, *cache.state_shape), -1, dtype=torch.int32, device=dev)
     Bv = spec.B * spec.H_kv if per_head else spec.B              # sequences / heads per sequence of the view
@@ -109,6 +110,8 @@ def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: 
         "tokens_seen": cache.tokens_seen,
         "prefill": prefill,
     }
+    if policy == "h2o":
+        res["h2o_acc"] = cache.h2o_acc.view(spec.L, Bv, spec.k).cpu().numpy()
     if default_keep:
         res["out"] = res["out"][(t_begin, spec.T)]
         res["out_t0"] = t_begin
@@ -269,7 +272,7 @@ def _check_unit_star(args):
 
 
 def check_units(spec, seed, units, res, workers: int = 1, t_stop=None, out=None, out_t0=None, n_pinned=0,
-                rope_base=None, keep_native: bool = False):
+                rope_base=None, keep_native: bool = False, policy="tova", h2o_heavy: int = 0):
     """Checks every sampled unit; with workers > 1 in spawned CPU-only processes."""
     jobs = []
     out = res["out"] if out is None else out

@@ -616,6 +616,44 @@ def test_multi_step_wait_runs_out_cleanly(monkeypatch):
     cache.destroy()
 
 
+def test_multi_step_wait_runs_out_and_the_cache_recovers(monkeypatch):
+    """The failure path end to end, forced from the host (every kernel exits normally): a multi-step
+    launch whose bounded wait runs out leaves the units at different steps.  tova_cache_status reports
+    it; the caller restores its snapshot of kv_mem / state_mem, tova_cache_recover clears the flag and
+    the hand-off counters, rewinds the token count and puts the cache on one launch per step; the steps
+    are issued again and the whole stream then matches the oracle."""
+    from paper_2401_06104_amd import TovaCache
+    from workloads import Stream
+    monkeypatch.setenv("TOVA_MULTI_STEP", "1")
+    monkeypatch.setenv("TOVA_MULTI_STEP_SPIN", "0")
+    monkeypatch.setenv("TOVA_UNIT_MODE", "0")
+    spec = spec_for("c3_mistral_gqa", B=16, k=128, T=128 + 60)
+    cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype, n_splits=1)
+    assert cache.multi_step_blocks > 0
+    c = Stream(spec, 12, device="cuda:0").chunk(0, spec.T)
+    out = torch.empty_like(c["q"])
+    ev = torch.full((spec.T, spec.L, spec.B), -7, dtype=torch.int32, device="cuda:0")
+    k = spec.k
+    cache.decode_steps(c["q"][:k], c["k"][:k], c["v"][:k], out[:k], ev[:k])        # the fill: one launch per step
+    assert cache.status() == 0
+    snap_kv, snap_state = cache.kv_mem.clone(), cache.state_mem.clone()             # the caller's snapshot after k tokens
+    cache.decode_steps(c["q"][k:], c["k"][k:], c["v"][k:], out[k:], ev[k:])         # gives up: no polls allowed
+    assert cache.status() == 1 and cache.tokens_seen == spec.T
+    cache.kv_mem.copy_(snap_kv); cache.state_mem.copy_(snap_state)
+    cache.recover(k)
+    assert cache.tokens_seen == k and cache.multi_step_blocks == 0
+    cache.decode_steps(c["q"][k:], c["k"][k:], c["v"][k:], out[k:], ev[k:])         # again, per-step launches
+    assert cache.status() == 0 and cache.tokens_seen == spec.T
+    units = [(0, 0), (0, 9), (0, 15)]
+    ul, ub = [u[0] for u in units], [u[1] for u in units]
+    res = {"out": out[:, ul, ub].float().cpu().numpy(), "evicted": ev.cpu().numpy(),
+           "slot_token": cache.slot_token.cpu().numpy(), "K": cache.K[ul, ub].float().cpu().numpy(),
+           "V": cache.V[ul, ub].float().cpu().numpy()}
+    for s_ in parity.check_units(spec, 12, units, res, workers=3):
+        print(f"[parity]   {s_}", flush=True)
+    cache.destroy()
+
+
 # ---- decode steps with re-assigned positions (Sec. 7.2) --------------------------------------
 REPOS_SWEEP = [
     # dtype, d, H, H_kv, k, T, L, B, rope_base, pinned
