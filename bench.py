@@ -48,7 +48,12 @@ def algorithmic_bytes_per_step(spec) -> int:
     return per_unit * spec.L * spec.B
 
 
-def gpu_leg(spec, seed, steps, warmup, device, chunk=256, prefill=False, also_prompt=False, repositioned=False):
+def gpu_leg(spec, seed, steps, warmup, device, chunk=256, prefill=False, also_prompt=False, repositioned=False,
+            repeats=0):
+    """Fills the cache (through the entry point, or with prefill=True by laying the first k tokens down),
+    runs `warmup` untimed steps, then times ONE call of `steps` steps with HIP events on the stream the
+    kernels are launched on.  repeats > 0: the same number of further steps is timed that many more
+    times (fresh tokens each time) and the per-step times of all 1 + repeats calls are returned too."""
     import torch
     from paper_2401_06104_amd import TovaCache
     from workloads import Stream
@@ -56,7 +61,7 @@ def gpu_leg(spec, seed, steps, warmup, device, chunk=256, prefill=False, also_pr
     dev = torch.device(device)
     cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype, device=dev)
     stream = Stream(spec, seed, device=dev)
-    need = spec.k + warmup + steps
+    need = spec.k + warmup + steps * (1 + repeats)
     assert need <= spec.T, f"stream too short: need {need} tokens, spec has {spec.T}"
 
     # repositioned: the stream is taken as un-rotated q / k and stepped through
@@ -111,7 +116,24 @@ def gpu_leg(spec, seed, steps, warmup, device, chunk=256, prefill=False, also_pr
     wall = time.perf_counter() - w0
     ev_ms = e0.elapsed_time(e1)
     ev_host = evicted.cpu()
-    ok = bool(((ev_host >= 0) & (ev_host <= spec.k)).all()) and cache.tokens_seen == need
+    ok = (bool(((ev_host >= 0) & (ev_host <= spec.k)).all()) and cache.tokens_seen == spec.k + warmup + steps
+          and int(cache.error_flag.item()) == 0)
+    rep_ms = [ev_ms / steps]
+    for r in range(repeats):
+        a0 = t0 + steps * (1 + r)
+        qs, ks, vs = [], [], []
+        for a in range(a0, a0 + steps, chunk):
+            c = stream.chunk(a, min(a0 + steps, a + chunk))
+            qs.append(c["q"]); ks.append(c["k"]); vs.append(c["v"])
+        q, k_new, v_new = torch.cat(qs), torch.cat(ks), torch.cat(vs)
+        del qs, ks, vs
+        torch.cuda.synchronize(dev)
+        e0.record()
+        step_fn(q, k_new, v_new, out, evicted)
+        e1.record()
+        torch.cuda.synchronize(dev)
+        rep_ms.append(e0.elapsed_time(e1) / steps)
+        ok = ok and int(cache.error_flag.item()) == 0
     lay = cache.layout
     multi = cache.multi_step_blocks
     plan = dict(multi_step_blocks=multi, n_splits=lay.n_splits, rows_per_split=lay.rows_per_split, block_threads=lay.block_threads,
@@ -127,10 +149,27 @@ def gpu_leg(spec, seed, steps, warmup, device, chunk=256, prefill=False, also_pr
         torch.cuda.synchronize(dev)
         prompt_ms = e0.elapsed_time(e1)
         ev2 = evicted.cpu()
-        ok = ok and bool(((ev2 >= 0) & (ev2 <= spec.k)).all())
+        ok = ok and bool(((ev2 >= 0) & (ev2 <= spec.k)).all()) and int(cache.error_flag.item()) == 0
     cache.destroy()
-    return dict(wall_s=wall, event_ms=ev_ms, plan=plan, sane=ok, prompt_event_ms=prompt_ms,
+    return dict(wall_s=wall, event_ms=ev_ms, plan=plan, sane=ok, prompt_event_ms=prompt_ms, repeat_ms_per_step=rep_ms,
                 new_token_dropped_frac=float((ev_host == spec.k).float().mean()))
+
+
+def leg_record(workload, spec, g, steps, kernel):
+    """One configuration's line: time per step, throughput and the fused step kernel against the HBM roofline."""
+    ms = g["event_ms"] / steps
+    ab = algorithmic_bytes_per_step(spec)
+    spl = steps if g["plan"]["multi_step_blocks"] else 1
+    rec = {"workload": workload, "steps": steps, "ms_per_step": ms, "decode_steps_per_s": 1e3 / ms,
+           "sequence_steps_per_s": 1e3 / ms * spec.L * spec.B,
+           "roofline": {"bound": "hbm", "achieved": ab / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": ab / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "kernel": kernel, "steps_per_launch": spl,
+                        "algorithmic_bytes_per_step": ab, "avg_launch_us": ms * 1e3 * spl},
+           "plan": g["plan"], "sane": g["sane"]}
+    if len(g["repeat_ms_per_step"]) > 1:
+        r = sorted(g["repeat_ms_per_step"])
+        rec["repeat_ms_per_step"] = {"n": len(r), "median": r[len(r) // 2], "min": r[0], "max": r[-1]}
+    return rec
 
 
 def _oracle_worker(args):
@@ -158,20 +197,28 @@ def _oracle_worker(args):
     return dt
 
 
-def cpu_leg(spec, seed, n_timed=768):
+def cpu_leg(spec, seed, n_timed=512):
+    """The fp64 oracle as it stands on the host's cores: one sequence per core on min(16, cores) cores
+    at once (a one-GPU machine's share is 16, whatever os.cpu_count() shows), then one sequence alone on one core."""
     import multiprocessing as mp
     cores = max(1, min(16, os.cpu_count() or 1, spec.B))
     jobs = [(spec, seed, b, n_timed) for b in range(cores)]
     t0 = time.perf_counter()
     with mp.get_context("spawn").Pool(cores) as pool:
         times = pool.map(_oracle_worker, jobs)
+        one = pool.map(_oracle_worker, [(spec, seed, 0, n_timed // 2)])[0]     # alone: the other workers idle
     wall_total = time.perf_counter() - t0
     timed_wall = max(times)                          # workers run concurrently
     unit_steps_per_s = cores * n_timed / timed_wall
+    one_core = (n_timed // 2) / one
     return dict(value=unit_steps_per_s / (spec.L * spec.B), unit="decode steps/s", cores=cores, kind="oracle",
                 sample=(f"{cores} of {spec.B} sequences, one per core, {n_timed} full-occupancy steps each after "
                         f"an untimed {spec.k}-step fill; unit-steps/s scaled by 1/{spec.L * spec.B} units per step"),
-                unit_steps_per_s=unit_steps_per_s, wall_s_including_fill=wall_total)
+                unit_steps_per_s=unit_steps_per_s, wall_s_including_fill=wall_total,
+                one_core={"value": one_core / (spec.L * spec.B), "unit": "decode steps/s", "cores": 1,
+                          "unit_steps_per_s": one_core,
+                          "sample": f"sequence 0 alone on one core, {n_timed // 2} full-occupancy steps after the fill"},
+                os_cpu_count=os.cpu_count())
 
 
 def main():
@@ -202,12 +249,16 @@ def main():
         sys.exit(1)
     from workloads import spec_for
 
-    spec = spec_for("c3_mistral_gqa", L=args.layers, T=1024 + args.warmup + args.steps)
-    g = gpu_leg(spec, args.seed, args.steps, args.warmup, "cuda:0", prefill=args.prefill)
+    REPEATS = 5
+    spec = spec_for("c3_mistral_gqa", L=args.layers, T=1024 + args.warmup + args.steps * (1 + REPEATS))
+    g = gpu_leg(spec, args.seed, args.steps, args.warmup, "cuda:0", prefill=args.prefill, repeats=REPEATS)
     ms_per_step = g["event_ms"] / args.steps
     abytes = algorithmic_bytes_per_step(spec)
     achieved = abytes / (ms_per_step * 1e-3) / 1e9
     steps_per_launch = args.steps if g["plan"]["multi_step_blocks"] else 1
+    per_step_traffic = (PROFILED_TRAFFIC_BYTES_PER_STEP if spec.L == 1 else
+                        PROFILED_TRAFFIC_BYTES_PER_STEP_X32 if spec.L == 32 else None)
+    reps = sorted(g["repeat_ms_per_step"])
     result = {
         "metric": "TOVA decode steps/sec and achieved HBM GB/s (% of peak), 1 MI355X",
         "value": 1e3 / ms_per_step,
@@ -222,44 +273,66 @@ def main():
                    "sequence_steps_per_s": 1e3 / ms_per_step * spec.L * spec.B},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": (PROFILED_TRAFFIC_BYTES_PER_STEP * steps_per_launch if spec.L == 1 else
-                                 PROFILED_TRAFFIC_BYTES_PER_STEP_X32 * steps_per_launch if spec.L == 32 else None),
+                     # bytes that left L2 per launch: the per-step figure of the committed rocprofv3 counter
+                     # runs (not collected live) x the steps of this launch
+                     "traffic": per_step_traffic * steps_per_launch if per_step_traffic else None,
+                     "traffic_per_step_profiled": per_step_traffic,
+                     "traffic_source": "profiles/tova_step_kernel_c3_mistral_gqa.txt (FETCH_SIZE + WRITE_SIZE per step, "
+                                       "scaled by a 1 GiB copy); multiplied by steps_per_launch here",
                      "kernel": "tova_step_kernel<bf16, d=128, G=4, " +
                                ("workgroup per unit, " if g["plan"]["unit_workgroups"] else "") +
                                ("multi-step>" if steps_per_launch > 1 else "per-step>"),
                      "steps_per_launch": steps_per_launch, "algorithmic_bytes_per_step": abytes,
                      "algorithmic_bytes_per_launch": abytes * steps_per_launch,
-                     "avg_launch_us": ms_per_step * 1e3 * steps_per_launch},
+                     "avg_launch_us": ms_per_step * 1e3 * steps_per_launch,
+                     "note": "this workload's 256 MiB of K/V is the size of the memory-side cache, and every step "
+                             "re-reads the same rows: hits there are possible and the counters cannot tell them "
+                             "from HBM.  frac_dram_bound is the same kernel on 32 such layers (8 GiB per step)."},
+        "repeat_ms_per_step": {"n": len(reps), "median": reps[len(reps) // 2], "min": reps[0], "max": reps[-1],
+                               "what": f"the timed call and {REPEATS} more calls of {args.steps} steps each on further tokens"},
         "sane": g["sane"], "new_token_dropped_frac": g["new_token_dropped_frac"],
         "wall_s_timed_region": g["wall_s"],
     }
-    if not args.no_hbm_variant and args.layers == 1:
+    legs = not args.no_hbm_variant and args.layers == 1
+    if legs:
         # same kernel, 32 independent layers: 8 GiB of cache per step cannot be served from the
         # 256 MB last-level cache, so this is the DRAM-bound figure
         s32 = spec_for("c3_mistral_gqa", L=32, T=1024 + 8 + 192)
         g32 = gpu_leg(s32, args.seed, 192, 8, "cuda:0", chunk=32)
-        ms32 = g32["event_ms"] / 192
-        ab32 = algorithmic_bytes_per_step(s32)
-        result["hbm_resident_variant"] = {"workload": "same layer shape x 32 layers (8 GiB cache; 2048 units, a workgroup per unit)", "steps": 192,
-                                          "ms_per_step": ms32, "achieved_GBps": ab32 / (ms32 * 1e-3) / 1e9,
-                                          "frac": ab32 / (ms32 * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                          "sequence_steps_per_s": 1e3 / ms32 * 32 * 64, "sane": g32["sane"]}
-    if not args.no_hbm_variant and args.layers == 1:
-        # config 4's layer shape (LLaMA-2-7B: 32 heads, no grouping, k = 4096) on 4 layers x 64 sequences:
-        # 256 units, 16 GiB of cache per step, a workgroup per unit.  The first 4096 tokens are laid down
-        # directly (what the fill steps produce) to keep the run short.
-        s4 = spec_for("c4_llama7b_stack", L=4, T=4096 + 4 + 32)
-        g4 = gpu_leg(s4, args.seed + 1, 32, 4, "cuda:0", chunk=16, prefill=True, also_prompt=True)
-        ms4 = g4["event_ms"] / 32
-        ab4 = algorithmic_bytes_per_step(s4)
-        result["mha_k4096_variant"] = {"workload": "config 4 layer shape (32 heads MHA, d=128, bf16, k=4096) x 4 layers x 64 "
-                                                   "sequences (16 GiB cache; 256 units, a workgroup per unit)", "steps": 32,
-                                       "ms_per_step": ms4, "achieved_GBps": ab4 / (ms4 * 1e-3) / 1e9,
-                                       "frac": ab4 / (ms4 * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                       "sequence_steps_per_s": 1e3 / ms4 * 4 * 64, "plan": g4["plan"], "sane": g4["sane"],
-                                       "prompt_ms_per_token": g4["prompt_event_ms"] / 32,
-                                       "prompt_speedup_over_decode_steps": ms4 / (g4["prompt_event_ms"] / 32)}
-    if not args.no_hbm_variant and args.layers == 1:
+        r32 = leg_record("config 3's layer shape x 32 layers (8 GiB cache; 2048 units, a workgroup per unit)", s32, g32, 192,
+                         "tova_step_kernel<bf16, d=128, G=4, workgroup per unit, multi-step>")
+        r32["roofline"]["traffic_per_step_profiled"] = PROFILED_TRAFFIC_BYTES_PER_STEP_X32
+        result["hbm_resident_variant"] = r32
+        result["roofline"]["frac_dram_bound"] = r32["roofline"]["frac"]
+    if legs:
+        # config 2: one sequence, one layer, k = 512 -- 32 workgroups, latency-bound (ideal: 1 us per step)
+        s2 = spec_for("c2_llama7b_layer", T=512 + 64 + 2048)
+        g2 = gpu_leg(s2, 2, 2048, 64, "cuda:0")
+        result["c2_llama7b_layer"] = leg_record("config 2: LLaMA-2-7B layer, 32 heads MHA, d=128, bf16, batch 1, k=512; 512 fill "
+                                                "steps, then timed steps at full occupancy", s2, g2, 2048,
+                                                "tova_step_kernel<bf16, d=128, G=1, multi-step>")
+    if legs:
+        # config 5 at its full shape: 32 layers x 1 sequence, 8 query heads per KV head, k = 4096 (split cache,
+        # hand-off form).  The first 4096 tokens are laid down directly (what the fill steps produce).
+        s5 = spec_for("c5_yi_long", T=4096 + 32 + 512)
+        g5 = gpu_leg(s5, 5, 512, 32, "cuda:0", chunk=128, prefill=True)
+        result["c5_yi_long"] = leg_record("config 5: Yi-7B-shaped GQA 32/4, d=128, bf16, batch 1, 32 layers, k=4096 (split cache), "
+                                          "timed steps at full occupancy of the 70,000-token stream's steady state", s5, g5, 512,
+                                          "tova_step_kernel<bf16, d=128, G=8, split cache, multi-step>")
+    if legs:
+        # config 4 at its full shape: 32 layers x 64 sequences of LLaMA-2-7B's layer shape, k = 4096 -- 128 GiB of
+        # cache, 2048 units, a workgroup per unit.  The first 4096 tokens are laid down directly.
+        free, _ = torch.cuda.mem_get_info()
+        L4 = 32 if free > 150 * 2 ** 30 else max(1, int((free - 8 * 2 ** 30) // (4.2 * 2 ** 30)))
+        s4 = spec_for("c4_llama7b_stack", L=L4, T=4096 + 4 + 32)
+        g4 = gpu_leg(s4, 4, 32, 4, "cuda:0", chunk=16, prefill=True, also_prompt=True)
+        r4 = leg_record(f"config 4: LLaMA-2-7B stack, 32 heads MHA, d=128, bf16, batch 64, k=4096, L={L4} "
+                        f"({L4 * 4} GiB cache; {L4 * 64} units, a workgroup per unit), timed steps at full occupancy", s4, g4, 32,
+                        "tova_step_kernel<bf16, d=128, G=1, workgroup per unit, multi-step>")
+        r4["prompt_ms_per_token"] = g4["prompt_event_ms"] / 32
+        r4["prompt_speedup_over_decode_steps"] = r4["ms_per_step"] / (g4["prompt_event_ms"] / 32)
+        result["c4_llama7b_stack"] = r4
+    if legs:
         # decode steps beyond the training length (Sec. 7.2): LLaMA-2-7B layer shape with the multi-state of
         # 512 the paper uses there, keys cached without positions; 32 layers x 16 sequences = 512 units
         sr = spec_for("c2_llama7b_layer", L=32, B=16, T=512 + 8 + 32)
@@ -271,7 +344,7 @@ def main():
                                           "steps": 32, "ms_per_step": msr, "achieved_GBps": abr / (msr * 1e-3) / 1e9,
                                           "frac": abr / (msr * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                           "sequence_steps_per_s": 1e3 / msr * 32 * 16, "sane": gr["sane"]}
-    if not args.no_hbm_variant and args.layers == 1:
+    if legs:
         # the policy on its own (App. B): fp32 attention weights [L][B][H][k+1] handed in, one launch per step;
         # config 3's layer shape x 32 layers, cache full
         from paper_2401_06104_amd import TovaCache
