@@ -24,6 +24,6 @@ What is pinned and what is not:
     passes the pins above.
 """
 from .tova_oracle import TovaOracle, TovaHeadOracle, run_stream  # noqa: F401
-from .tova_literal import tova_policy, LiteralTova  # noqa: F401
+from .tova_literal import OrderedTova  # noqa: F401
 from .tova_masked import tova_masked_prompt  # noqa: F401
 from .tova_positions import TovaPositionsOracle, compress_gap, compressed_positions, rope  # noqa: F401

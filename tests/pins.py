@@ -12,7 +12,7 @@ import math
 import numpy as np
 import torch
 
-from oracle.tova_literal import LiteralTova
+from oracle.tova_literal import OrderedTova
 
 
 def _stream(rng, T, H, H_kv, d, scale=1.0):
@@ -77,7 +77,7 @@ def pin_brute_force(Oracle):
         G = H // H_kv
         scale = 1.0 / math.sqrt(d)
         orc = Oracle(k, H, H_kv, d)
-        lit = LiteralTova(k, H, H_kv, d)
+        lit = OrderedTova(k, H, H_kv, d)
         retained = []                       # token ids, maintained by brute force
         for t in range(T):
             slot_token_before = orc.slot_token.copy()
