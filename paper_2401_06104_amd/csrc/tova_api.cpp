@@ -16,6 +16,7 @@ namespace {
 constexpr size_t kAlign = 256;
 constexpr int kTargetBlocks = 512;     // two workgroups per CU on 256 CUs
 constexpr int kUnitModeUnits = 256;    // from one unit per CU on, a workgroup takes a whole unit
+constexpr int kPrefillMinUnits = 256;   // fewest units for which prompt tokens are grouped (see resolve)
 constexpr int kPrefillMaxGrid = 1024;  // workgroups of the multi-token kernel (each has a scratch area of its own)
 constexpr size_t kMinBytesPerSplit = 256 * 1024;  // K+V bytes of a chunk below which splitting only adds
                                                   // hand-offs (each costs ~1 us of memory round trip)
@@ -32,7 +33,7 @@ struct Resolved {
   int n_pinned, per_head;
   int policy, h2o_recent;  // TOVA_POLICY_*; H2O: tokens of the recent window, the incoming one included
   size_t acc_off;          // in state_mem: H2O's aggregated weights [units][k] (0 bytes for the other policies)
-  int units, pairs, S, R, kp, NT, grid, lds, st_off, spin_limit, force_slow, persist_spin, multi_step, multi_grid, spin_env;
+  int units, pairs, S, R, kp, NT, grid, lds, st_off, red_off, spin_limit, force_slow, persist_spin, multi_step, multi_grid, spin_env;
   int unit_mode;  // one workgroup per unit instead of one per (unit, KV head, chunk)
   int pf_C, pf_NT, pf_lds, pf_e_floats, pf_ncp;  // multi-token kernel: tokens per group (0 = not available) and its LDS plan
   int pf_grid;                                   // ... its workgroups (decided in tova_cache_init)
@@ -118,7 +119,7 @@ int resolve(const tova_config_t* c, Resolved* r) {
       }
       if ((kSmallFloats + st + s_fl) * 4 <= kMaxLdsBytesUnit) {
         r->unit_mode = 1;
-        r->S = 1; r->R = k; r->NT = nt; r->st_off = (int)st;
+        r->S = 1; r->R = k; r->NT = nt; r->st_off = (int)st; r->red_off = 0;
         r->lds = (int)((kSmallFloats + st + s_fl) * 4);
       }
     }
@@ -126,10 +127,18 @@ int resolve(const tova_config_t* c, Resolved* r) {
 
   if (r->policy != TOVA_POLICY_TOVA && !r->unit_mode) return TOVA_ENOSUP;  // (a KV head's logits do not fit LDS)
 
-  // ---- groups of C prompt tokens per pass over the cache (workgroup-per-unit form only) ----
-  // C * G (token, head) combinations share a streamed row; the vector passes hold at most 8.
+  // ---- groups of C prompt tokens per pass over the cache ----
+  // C * G (token, head) combinations share a streamed row; the vector passes hold at most 8.  The
+  // multi-token kernel has a plan of its own (a workgroup per unit, whatever form the single-token
+  // steps take), so it is available from kPrefillMinUnits units on: with C tokens per pass over the
+  // cache even a quarter-full device beats token-by-token steps (measured; see the design notes).
   r->pf_C = 0;
-  if (r->unit_mode && r->policy == TOVA_POLICY_TOVA) {
+  int pf_min_units = kPrefillMinUnits;
+  if (const char* e = std::getenv("TOVA_PREFILL_MIN_UNITS")) {  // tuning aid / test hook
+    const int v = std::atoi(e);
+    if (v >= 1) pf_min_units = v;
+  }
+  if ((r->unit_mode || r->units >= pf_min_units) && r->policy == TOVA_POLICY_TOVA) {
     const int cands[3] = {8, 4, 2};
     for (int ci = 0; ci < 3 && !r->pf_C; ++ci) {
       const int C = cands[ci], GE = G * C;
@@ -180,7 +189,7 @@ int resolve(const tova_config_t* c, Resolved* r) {
   // memory after the PV pass; with several chunks per KV head a small area behind both holds all
   // chunks' softmax statistics and the finisher's merge weights.
   int R = (k + S - 1) / S, NT = 0;
-  long long big = 0, st_off = 0;
+  long long big = 0, st_off = 0, red_off = 0;
   for (; !r->unit_mode;) {
     S = (k + R - 1) / R;  // no dead chunks
     const long long e_fl = ((long long)(R + 1) * G + 3) / 4 * 4;
@@ -191,7 +200,10 @@ int resolve(const tova_config_t* c, Resolved* r) {
     for (int ci = 0; ci < 2 && !ok; ++ci) {
       NT = cand[ci];
       const long long red_fl = (long long)(NT / 64) * G * r->D;
-      st_off = e_fl > red_fl ? e_fl : red_fl;
+      // several chunks per KV head: the exp values are needed again after the PV pass (the chunk's score
+      // rows wait for the siblings' statistics until then), so the reduction area sits behind them
+      st_off = (S > 1) ? e_fl + red_fl : (e_fl > red_fl ? e_fl : red_fl);
+      red_off = (S > 1) ? e_fl : 0;
       big = st_off + (S > 1 ? 3LL * S * G + 2LL * G : 0);
       ok = (big <= big_cap);
     }
@@ -200,7 +212,7 @@ int resolve(const tova_config_t* c, Resolved* r) {
     R -= (R >= 8) ? R / 8 : 1;  // smaller chunks until the chunk fits
   }
   if (!r->unit_mode) {
-    r->S = S; r->R = R; r->NT = NT; r->st_off = (int)st_off;
+    r->S = S; r->R = R; r->NT = NT; r->st_off = (int)st_off; r->red_off = (int)red_off;
     r->lds = (int)((kSmallFloats + big) * 4);
   }
   S = r->S;
@@ -277,6 +289,7 @@ struct tova_cache {
   int64_t t;  // tokens seen
   // environment hooks, read once in tova_cache_init
   int prefill_group_off;  // TOVA_PREFILL_GROUP=0: prompts go token by token
+  int prefill_exact;      // TOVA_PREFILL_EXACT=1: test hook, every grouped token takes the guard's from-scratch route
   int repos_threads;      // TOVA_REPOS_THREADS (0: the plan's own choice)
   int repos_parts;        // TOVA_REPOS_PARTS (0: no limit given)
 };
@@ -334,6 +347,8 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
   c->t = 0;
   c->prefill_group_off = 0;
   if (const char* e = std::getenv("TOVA_PREFILL_GROUP")) c->prefill_group_off = (std::atoi(e) == 0);  // test hook
+  c->prefill_exact = 0;
+  if (const char* e = std::getenv("TOVA_PREFILL_EXACT")) c->prefill_exact = (std::atoi(e) != 0);  // test hook
   c->repos_threads = 0;
   if (const char* e = std::getenv("TOVA_REPOS_THREADS")) {  // tuning aid
     const int v = std::atoi(e);
@@ -449,6 +464,7 @@ int tova_prefill(tova_cache_t* c, int32_t n_tokens, const void* q, const void* k
       p.q_stride = (int64_t)(q_step / r.esize); p.kv_stride = (int64_t)(kv_step / r.esize);
       p.n_chunks = n_chunks; p.units = r.units; p.H = r.H; p.H_kv = r.H_kv; p.k = r.k;
       p.n_pinned = r.n_pinned; p.t = (int32_t)c->t; p.e_floats = r.pf_e_floats; p.ncp = r.pf_ncp; p.scale = r.scale;
+      p.force_exact = c->prefill_exact;
       const tova::LaunchPlan lp{r.pf_grid, r.pf_NT, r.pf_lds};
       const hipError_t e = tova::launch_prefill(r.bf16, r.D, r.G, C, p, lp, s);
       if (e != hipSuccess) return hip_fail(e, "tova_prefill launch");
@@ -497,7 +513,7 @@ int decode_steps_on(tova_cache* c, char* scratch, int32_t n_steps, const void* q
   p.cnt_unit = reinterpret_cast<int32_t*>(scratch + r.cnt_unit_off);
   p.cnt_pub = reinterpret_cast<int32_t*>(scratch + r.cnt_pub_off);
   p.slow_flag = reinterpret_cast<int32_t*>(scratch + r.slow_off);
-  p.st_off = r.st_off; p.spin_limit = r.spin_limit; p.force_slow = r.force_slow;
+  p.st_off = r.st_off; p.red_off = r.red_off; p.spin_limit = r.spin_limit; p.force_slow = r.force_slow;
   p.sg = reinterpret_cast<float*>(scratch + r.sg_off);
   p.escr = reinterpret_cast<float*>(scratch + r.escr_off);
   p.stats = reinterpret_cast<float*>(scratch + r.stats_off);

@@ -35,6 +35,8 @@ struct StepParams {
   int32_t* cnt_pub;    // [pairs] chunks that have published their softmax statistics (S > 1 only)
   int32_t* slow_flag;  // [pairs][S] chunk left its exp values in escr for the finisher (S > 1 only)
   int32_t st_off;      // float offset, inside the big LDS area, of the chunk-statistics area (S > 1)
+  int32_t red_off;     // float offset of the cross-wave PV reduction area: 0 (it reuses the logit area), or
+                       // behind the logits when they are still needed after the PV pass (S > 1)
   int32_t spin_limit;  // how often a chunk re-reads the published count before giving up (S > 1)
   int32_t force_slow;  // test hook: no chunk finishes its own scores
   // multi-step launch
@@ -82,6 +84,7 @@ struct PrefillParams {
   int32_t t;           // index of the first token of the launch
   int32_t e_floats;    // floats of the first big LDS area (logits / reduction / resolution buffers)
   int32_t ncp;         // k + C rounded up to a multiple of 4: stride of the tentative score rows
+  int32_t force_exact; // test hook: every token of a full-cache group is computed from scratch (the guard's route)
   float scale;
 };
 

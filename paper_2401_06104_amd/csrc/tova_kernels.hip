@@ -208,11 +208,13 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
   // Score contributions leave LDS before the PV pass (each thread re-reads only exp values it
   // wrote itself, so no barrier is needed in front).
   //  * one chunk per KV head: Z is final.
-  //  * several chunks: the chunk publishes its (max, sum) and looks, a bounded number of times,
-  //    whether its siblings have published theirs.  They run on neighbouring CUs at the same
-  //    time, so normally they have: the chunk then rescales its exp values to final
-  //    probabilities itself.  If not (a sibling was scheduled much later) it leaves the exp
-  //    values in scratch for the pair's finisher.  No wave ever waits without bound.
+  //  * several chunks: the chunk publishes its (max, sum) now and goes on to its PV pass, which
+  //    needs chunk-local values only.  After the pass it looks, a bounded number of times,
+  //    whether its siblings have published theirs -- they run on neighbouring CUs at the same
+  //    time, so by then they have -- and rescales its exp values, which are kept in LDS through
+  //    the pass (the cross-wave reduction area does not reuse that memory in this case), to
+  //    final probabilities itself.  If not (a sibling was scheduled much later) it leaves the
+  //    exp values in scratch for the pair's finisher.  No wave ever waits without bound.
   const int nact = c_new + 1;         // chunks of this pair that run this step
   float* sl = big + p.st_off;         // [nact][G][2]  all chunks' (max, sum)
   float* wl = sl + 2 * nact * G;      // [nact][G]     2^(m_c - m_g)   (pair finisher)
@@ -250,49 +252,12 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
         st_agent(st + 1, zg);
       }
       if (full) {
+        // ... and says so on the pair's counter once the stores have completed.  Nobody waits here:
+        // the siblings' statistics are only needed after the PV pass (see phase 4a), by which time
+        // they have long arrived.
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_s_waitcnt(0);
-        if (lane == 0) {
-          int seen = __hip_atomic_fetch_add(p.cnt_pub + pair, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
-          for (int it = 0; it < p.spin_limit && seen != nact; ++it) {  // bounded: then the slow route
-            __builtin_amdgcn_s_sleep(16);
-            seen = ld_agent_i(p.cnt_pub + pair);
-          }
-          flag_lds[0] = (seen == nact && !p.force_slow) ? 1 : 0;
-        }
-      }
-    }
-    if (full) {
-      __syncthreads();
-      have_stats = (flag_lds[0] != 0);
-      if (have_stats) {
-        for (int x = tid; x < nact * G * 2; x += nt) sl[x] = ld_agent(stp + x);
-        __syncthreads();
-        float f[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-          float mg = -INFINITY;
-          for (int c = 0; c < nact; ++c) mg = fmaxf(mg, sl[(c * G + g) * 2]);
-          float zg = 0.f;
-          for (int c = 0; c < nact; ++c)
-            zg += sl[(c * G + g) * 2 + 1] * __builtin_amdgcn_exp2f(sl[(c * G + g) * 2] - mg);
-          f[g] = __builtin_amdgcn_exp2f(m[g] - mg) / zg;
-        }
-        float* sg = p.sg + (size_t)pair * p.kp + r0;
-        for (int i = tid; i < nloc; i += nt) {
-          float a = 0.f;
-#pragma unroll
-          for (int g = 0; g < G; ++g) a = fmaf(e_lds[i * G + g], f[g], a);
-          st_agent(sg + i, a);
-        }
-      } else {
-        slow = 1;
-        float* es = p.escr + ((size_t)pair * p.kp + r0) * G;
-        for (int i = tid; i < nloc; i += nt) {
-#pragma unroll
-          for (int g = 0; g < G; ++g) st_agent(es + i * G + g, e_lds[i * G + g]);
-        }
-        if (tid == 0) st_agent_i(p.slow_flag + (size_t)pair * S + chunk, 1);
+        if (lane == 0) __hip_atomic_fetch_add(p.cnt_pub + pair, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
   }
@@ -301,7 +266,7 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
   float acc[G][VEC];
   pv_pass<T, D, G>(Vb, ncached, 1, new_here, [&](int) { return vnew; }, e_lds, G, 0, lane, wave, nw, vA, acc);
   // combine the RV row groups of the wave, then the waves (in wave order)
-  float* red = big;  // [nw][G*D]
+  float* red = big + p.red_off;  // [nw][G*D]; behind the exp values when they are still needed (S > 1)
   if constexpr (LV == 16 && (G * VEC) % 4 == 0) {
     // Four row groups of 16 lanes.  Transposing reduction: swapping rows between the registers of
     // two different values and adding halves the number of live registers at each of the two
@@ -380,6 +345,48 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kern
       float a = red[x];
       for (int w = 1; w < nw; ++w) a += red[w * G * D + x];
       st_agent(ap + x, a);
+    }
+    if (full) {
+      // the siblings' statistics, and with them this chunk's score rows (see phase 2)
+      if (tid == 0) {
+        int seen = ld_agent_i(p.cnt_pub + pair);
+        for (int sp = 0; sp < p.spin_limit && seen != nact; ++sp) {  // bounded: then the slow route
+          __builtin_amdgcn_s_sleep(16);
+          seen = ld_agent_i(p.cnt_pub + pair);
+        }
+        flag_lds[0] = (seen == nact && !p.force_slow) ? 1 : 0;
+      }
+      __syncthreads();
+      have_stats = (flag_lds[0] != 0);
+      if (have_stats) {
+        for (int x = tid; x < nact * G * 2; x += nt) sl[x] = ld_agent(stp + x);
+        __syncthreads();
+        float f[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float mg = -INFINITY;
+          for (int c = 0; c < nact; ++c) mg = fmaxf(mg, sl[(c * G + g) * 2]);
+          float zg = 0.f;
+          for (int c = 0; c < nact; ++c)
+            zg += sl[(c * G + g) * 2 + 1] * __builtin_amdgcn_exp2f(sl[(c * G + g) * 2] - mg);
+          f[g] = __builtin_amdgcn_exp2f(sl[(chunk * G + g) * 2] - mg) / zg;  // (this chunk's own max is in there too)
+        }
+        float* sg = p.sg + (size_t)pair * p.kp + r0;
+        for (int i = tid; i < nloc; i += nt) {
+          float a = 0.f;
+#pragma unroll
+          for (int g = 0; g < G; ++g) a = fmaf(e_lds[i * G + g], f[g], a);
+          st_agent(sg + i, a);
+        }
+      } else {
+        slow = 1;
+        float* es = p.escr + ((size_t)pair * p.kp + r0) * G;
+        for (int i = tid; i < nloc; i += nt) {
+#pragma unroll
+          for (int g = 0; g < G; ++g) st_agent(es + i * G + g, e_lds[i * G + g]);
+        }
+        if (tid == 0) st_agent_i(p.slow_flag + (size_t)pair * S + chunk, 1);
+      }
     }
     int n_slow = slow;
     if (nact > 1) {

@@ -21,6 +21,12 @@
 //                     recomputed exactly from their K rows and the argmin is taken among them
 //                     (lowest slot index on ties, the token itself last)
 //                     out_i = (U_i - sum_{e in E_i} w_i[e] V[e]) / Z'_i
+//   guard             Z' = Z - delta and U' = U - ... lose precision when what was removed carries most
+//                     of a head's weight for this token (relative error ~ eps * Z / Z').  If for any
+//                     head less than kMinKept of Z is left (or nothing: Z' <= 0), the token is not
+//                     corrected but computed from scratch over the candidates that are still there
+//                     -- the single-token step (logit pass, softmax, PV, head-summed scores, argmin)
+//                     inside this kernel; the group's other tokens go on as before.
 //   commit            tokens that still hold a slot at the end are stored there.
 //
 // While the multi-state still has room (App. B: nothing is removed while num_kv <= cache_max_size)
@@ -51,6 +57,11 @@ __device__ __forceinline__ float elem_f32<bf16_t>(const bf16_t* p, int idx) {
 }
 
 constexpr float kBoundSlack = 1e-4f;  // rounding of the streamed sums against the recomputed ones: ~1e-6
+// The corrected sum Z' = Z - (weights of the removed candidates) carries the rounding of Z (a block
+// sum of up to k + C fp32 terms: a few 1e-7 relative) magnified by Z / Z'.  With at least an eighth
+// of Z left the corrected sums, outputs and scores stay within ~4e-6 relative, inside the 1e-5 bar
+// of fp32 data; below that the token is computed from scratch.
+constexpr float kMinKept = 0.125f;
 
 template <typename T, int D, int G, int C>
 __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel(const PrefillParams p) {
@@ -258,7 +269,7 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
       });
     __syncthreads();
     // (b) corrected sums; f = Z / Z' >= 1 per head, f_max its largest value (1 is used as the lower end)
-    float fr[1] = {1.0f};
+    float fr[2] = {1.0f, 0.0f};  // [0] f_max, [1] nonzero: some head kept too little of its sum
     for (int hq = tid; hq < H; hq += nt) {
       const float zf = zst[hq * C + i];
       float d = 0.f;
@@ -266,17 +277,123 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
       const float zc = zf - d;
       zcs[hq] = zc;
       fr[0] = fmaxf(fr[0], zf / zc);
+      if (!(zc > kMinKept * zf)) fr[1] = 1.0f;  // (also Z' <= 0 and NaN)
     }
-    block_reduce<1, true>(fr, small, lane, wave, nw);
+    block_reduce<2, true>(fr, small, lane, wave, nw);
     const float f_max = fr[0];
-    // (c) the smallest upper bound, then the candidates whose lower bound does not exceed it
-    const float* Ti = t_lds + i * ncp;
+    const bool from_scratch = (fr[1] != 0.0f) || p.force_exact;  // block-uniform
+    float* Ti = t_lds + i * ncp;
     auto alive = [&](int c) {
       if (c < p.n_pinned) return false;  // TOVA+i (App. A): the first tokens hold slots 0 .. n_pinned-1
       for (int e = 0; e < i; ++e)
         if (vict[e] == c) return false;
       return true;
     };
+    float best = INFINITY;
+    int bpos = 0x7fffffff, bcand = k + i;
+    if (from_scratch) {
+      // ---- the guard's way out: this token as a single-token step over the candidates that are still
+      //      there (Sec. 3.2, Sec. 4): per KV head a logit pass over the k cached rows and the group's
+      //      tokens up to this one, those that were removed masked out; softmax; scores into the
+      //      token's row of t_lds (its tentative scores are no longer needed); PV; outputs
+      __syncthreads();  // (everyone has read zcs / the query copy: the big area is rewritten below)
+      T* outx = reinterpret_cast<T*>(p.out) + tok_q + (size_t)i * p.q_stride + (size_t)unit * H * D;
+      for (int kvh = 0; kvh < p.H_kv; ++kvh) {
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+        const int lane = tid & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        using Gx = Geo<T, D, G>;
+        const int pair = pair0 + kvh;
+        const T* Kb = reinterpret_cast<const T*>(p.K) + (size_t)pair * k * D;
+        const T* Vb = reinterpret_cast<const T*>(p.V) + (size_t)pair * k * D;
+        const T* knew0 = reinterpret_cast<const T*>(p.k_new) + tok_kv + (size_t)pair * D;
+        const T* vnew0 = reinterpret_cast<const T*>(p.v_new) + tok_kv + (size_t)pair * D;
+        const T* qh = qi + (size_t)kvh * G * D;
+        const int n_own = i + 1, ncx = k + n_own;
+        const bool own_here = (wave == nw - 1);
+        float mx[G], Zx[G];
+        logit_pass<T, D, G>(
+            Kb, k, n_own, own_here, [&](int g) { return qh + g * D; },
+            [&](int r) { return knew0 + (size_t)r * p.kv_stride; },
+            [&](int, int r) { return r < i && pos[r] < 0; },  // an earlier token of the group that holds no slot any more
+            scale2, lane, wave, nw, e_lds, mx);
+        V16 vX[Gx::UV];
+        pv_first_tile<T, D, G>(vX, Vb, k, lane, wave);
+        __syncthreads();  // the logits are in LDS
+        if (tid < i && vict[tid] < k) {  // cached rows that earlier tokens of the group removed
+#pragma unroll
+          for (int g = 0; g < G; ++g) e_lds[vict[tid] * G + g] = -INFINITY;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int g = 0; g < G; ++g) mx[g] = -INFINITY;  // (the pass's running maxima saw the removed rows)
+        for (int c = tid; c < ncx; c += nt) {
+#pragma unroll
+          for (int g = 0; g < G; ++g) mx[g] = fmaxf(mx[g], e_lds[c * G + g]);
+        }
+        block_reduce<G, true>(mx, small, lane, wave, nw);
+#pragma unroll
+        for (int g = 0; g < G; ++g) Zx[g] = 0.f;
+        for (int c = tid; c < ncx; c += nt) {
+#pragma unroll
+          for (int g = 0; g < G; ++g) {
+            const float e = __builtin_amdgcn_exp2f(e_lds[c * G + g] - mx[g]);
+            e_lds[c * G + g] = e;
+            Zx[g] += e;
+          }
+        }
+        block_reduce<G, false>(Zx, small + kMaxWaves * G, lane, wave, nw);
+        {
+          float rz[G];
+#pragma unroll
+          for (int g = 0; g < G; ++g) rz[g] = 1.0f / Zx[g];
+          for (int c = tid; c < ncx; c += nt) {  // (entry c is always this thread's; KV heads in order)
+            float a = 0.f;
+#pragma unroll
+            for (int g = 0; g < G; ++g) a = fmaf(e_lds[c * G + g], rz[g], a);
+            Ti[c] = (kvh == 0) ? a : Ti[c] + a;
+          }
+        }
+        float accx[G][Gx::VEC];
+        pv_pass<T, D, G>(Vb, k, n_own, own_here, [&](int r) { return vnew0 + (size_t)r * p.kv_stride; }, e_lds, G, 0,
+                         lane, wave, nw, vX, accx);
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+          for (int v = 0; v < Gx::VEC; ++v) accx[g][v] = column_sum<Gx::LV>(accx[g][v]);
+        float* red = big;  // [nw][G * D]
+        __syncthreads();   // everyone is done reading the exp values; the reduction area reuses them
+        if (lane / Gx::LV == 0) {
+#pragma unroll
+          for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int v = 0; v < Gx::VEC; ++v) red[(wave * G + g) * D + (lane % Gx::LV) * Gx::VEC + v] = accx[g][v];
+        }
+        __syncthreads();
+        for (int x = tid; x < G * D; x += nt) {
+          float a = red[x];
+          for (int w = 1; w < nw; ++w) a += red[w * G * D + x];
+          float zg = Zx[0];
+#pragma unroll
+          for (int g = 1; g < G; ++g) zg = (x / D == g) ? Zx[g] : zg;
+          E::store(outx + (size_t)kvh * G * D + x, a / zg);
+        }
+        __syncthreads();  // the reduction area is free for the next KV head
+      }
+      // the victim among the candidates that are still there, by (score, slot index)
+      for (int c = tid; c <= k + i; c += nt) {
+        if (!alive(c)) continue;
+        const float sc = Ti[c];
+        const int pc = position(i, c);
+        if (sc < best || (sc == best && pc < bpos)) {
+          best = sc;
+          bpos = pc;
+          bcand = c;
+        }
+      }
+    } else {
+    // (c) the smallest upper bound, then the candidates whose lower bound does not exceed it
     float lo[1] = {-INFINITY};  // -(min T)
     for (int c = tid; c <= k + i; c += nt)
       if (alive(c)) lo[0] = fmaxf(lo[0], -Ti[c]);
@@ -288,8 +405,6 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
     __syncthreads();
     const int ncont = misc[0];
     // (d) exact scores of those (a wave per candidate), argmin by (score, slot index)
-    float best = INFINITY;
-    int bpos = 0x7fffffff, bcand = k + i;
     for (int x = wave; x < ncont; x += nw) {
       const int cand = cont[x];
       float s = 0.f, a = 0.f;
@@ -305,6 +420,18 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
         best = s;
         bpos = pc;
         bcand = cand;
+      }
+    }
+    }  // corrected / from scratch
+    // (the lanes of a wave agree already on the corrected route; from scratch each has its own candidates)
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      const float ob = __shfl_xor(best, o);
+      const int op = __shfl_xor(bpos, o), oc = __shfl_xor(bcand, o);
+      if (ob < best || (ob == best && op < bpos)) {
+        best = ob;
+        bpos = op;
+        bcand = oc;
       }
     }
     float* bv = small + 256;
@@ -338,7 +465,7 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
     }
     // (f) the token's output: the removed candidates' share taken out of the unmasked sums
     T* outi = reinterpret_cast<T*>(p.out) + tok_q + (size_t)i * p.q_stride + (size_t)unit * H * D;
-    for (int x = tid; x < H * D; x += nt) {
+    for (int x = tid; x < H * D && !from_scratch; x += nt) {
       const int hq = x / D, dd = x - hq * D;
       float a = ublk[((size_t)hq * C + i) * D + dd];
       for (int e = 0; e < i; ++e) {

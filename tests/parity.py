@@ -69,6 +69,9 @@ def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: 
             c = stream.chunk(t0, t1, need_q=False)
             K[:, :, :, t0:t1, :] = c["k"].permute(1, 2, 3, 0, 4)
             V[:, :, :, t0:t1, :] = c["v"].permute(1, 2, 3, 0, 4)
+            if callable(progress) and (t0 // chunk_steps) % 32 == 31:
+                torch.cuda.synchronize(dev)
+                progress(f"[parity]   rows of tokens 0..{t1 - 1} of {spec.k} laid down")
         cache.occupancy.fill_(spec.k)
         cache.slot_token.copy_(torch.arange(spec.k, dtype=torch.int32, device=dev).expand_as(cache.slot_token))
         cache.set_tokens_seen(spec.k)
@@ -92,7 +95,7 @@ def run_gpu(spec: StreamSpec, seed: int, units, n_splits: int = 0, chunk_steps: 
                 outs[r].append((o if keep_native else o.float()).cpu())
         if progress and (t0 // chunk_steps) % 16 == 0:
             torch.cuda.synchronize(dev)
-            print(f"[parity]   gpu at step {t1}/{spec.T}", flush=True)
+            (progress if callable(progress) else (lambda m: print(m, flush=True)))(f"[parity]   gpu at step {t1}/{spec.T}")
     torch.cuda.synchronize(dev)
     assert int(cache.error_flag.item()) == 0, "a multi-step launch gave up waiting (error flag set)"
     res = {
@@ -268,12 +271,20 @@ def replay_slot_tokens(evicted_unit, k, t_stop):
 
 
 def _check_unit_star(args):
-    return check_unit(*args)
+    try:
+        from threadpoolctl import threadpool_limits
+        limiter = threadpool_limits(limits=1)            # one core per worker (the pool is the parallelism)
+    except Exception:                                     # pragma: no cover
+        limiter = None
+    r = check_unit(*args)
+    del limiter
+    return r
 
 
 def check_units(spec, seed, units, res, workers: int = 1, t_stop=None, out=None, out_t0=None, n_pinned=0,
-                rope_base=None, keep_native: bool = False, policy="tova", h2o_heavy: int = 0):
-    """Checks every sampled unit; with workers > 1 in spawned CPU-only processes."""
+                rope_base=None, progress=None):
+    """Checks every sampled unit; with workers > 1 in spawned CPU-only processes.  progress: called with
+    a line of text whenever a unit is done (long runs must show that they are alive)."""
     jobs = []
     out = res["out"] if out is None else out
     out_t0 = res.get("out_t0", 0) if out_t0 is None else out_t0
@@ -285,7 +296,13 @@ def check_units(spec, seed, units, res, workers: int = 1, t_stop=None, out=None,
         return [check_unit(*j) for j in jobs]
     import multiprocessing as mp
     with mp.get_context("spawn").Pool(min(workers, len(jobs))) as pool:
-        return pool.map(_check_unit_star, jobs)
+        results = []
+        for i, r in enumerate(pool.imap(_check_unit_star, jobs, chunksize=1)):
+            results.append(r)
+            if progress:
+                progress(f"[parity]   unit {r['unit']} done ({i + 1}/{len(jobs)}): {r['mismatches']} mismatches, "
+                         f"{r['near_tie_steps']} near-tie steps, max rel err {r['max_rel_err']:.2e}")
+        return results
 
 
 def check_global_invariants(spec, res):
@@ -443,14 +460,19 @@ def merge_window_stats(unit, stats_list, gpu_evicted, k):
     return tot
 
 
-def check_tiled(units_jobs, workers: int = 16):
+def check_tiled(units_jobs, workers: int = 16, progress=None):
     """units_jobs: list of (unit, jobs, gpu_evicted, k).  Runs every window of every unit on a pool of
-    CPU-only processes (largest first) and returns one merged statistics record per unit."""
+    CPU-only processes (largest first) and returns one merged statistics record per unit.  progress:
+    called with a line of text whenever a window is done."""
     import multiprocessing as mp
     flat = [(ui, j) for ui, (_, jobs, _, _) in enumerate(units_jobs) for j in jobs]
     order = sorted(range(len(flat)), key=lambda i: -(flat[i][1]["b"] - flat[i][1]["a"]))
     with mp.get_context("spawn").Pool(max(1, min(workers, len(flat)))) as pool:
-        results = pool.map(_window_job, [flat[i][1] for i in order], chunksize=1)
+        results = []
+        for i, r in enumerate(pool.imap(_window_job, [flat[i][1] for i in order], chunksize=1)):
+            results.append(r)
+            if progress:
+                progress(f"[parity]   unit {r['unit']} window {r['window']} done ({i + 1}/{len(flat)})")
     per_unit = {ui: [] for ui in range(len(units_jobs))}
     for i, r in zip(order, results):
         per_unit[flat[i][0]].append(r)

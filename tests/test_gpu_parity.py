@@ -15,13 +15,25 @@ pytestmark = pytest.mark.gpu
 WORKERS = max(1, min(16, os.cpu_count() or 1))       # host cores for the oracle legs (a one-GPU machine has 16)
 
 
-def _run(spec, seed, units, n_splits=0, workers=1, single_step_calls=False, chunk_steps=256):
+@pytest.fixture
+def say(capsys):
+    """Prints a progress line past pytest's capture, so that a test that runs for minutes shows what it
+    has done so far (lines come from finished pieces of work: a GPU pass, a unit, a window)."""
+    def _say(line):
+        with capsys.disabled():
+            print(line, flush=True)
+    return _say
+
+
+def _run(spec, seed, units, n_splits=0, workers=1, single_step_calls=False, chunk_steps=256, progress=None):
     print(f"[parity] {spec.name} L={spec.L} B={spec.B} H={spec.H}/{spec.H_kv} d={spec.d} {spec.dtype} "
           f"k={spec.k} T={spec.T} seed={seed} splits={n_splits} units={units}", flush=True)
     res = parity.run_gpu(spec, seed, units, n_splits=n_splits, single_step_calls=single_step_calls,
                          chunk_steps=chunk_steps)
     parity.check_global_invariants(spec, res)
-    stats = parity.check_units(spec, seed, units, res, workers=workers)
+    if progress:
+        progress(f"[parity] {spec.name}: GPU pass done, {len(units)} unit(s) to the oracle")
+    stats = parity.check_units(spec, seed, units, res, workers=workers, progress=progress)
     for s in stats:
         print(f"[parity]   {s}  plan(S,R,block,grid)={res['layout']}", flush=True)
     return stats, res
@@ -114,25 +126,6 @@ def test_c2_llama7b_layer_prefix():
     assert res["layout"][0] == 16
 
 
-def test_c3_mistral_gqa_reduced_batch():
-    """Config 3 shape per unit (G=4, k=1024), 8 sequences, 1024 fill + 300 decode steps."""
-    spec = spec_for("c3_mistral_gqa", B=8, T=1024 + 300)
-    _run(spec, seed=3, units=[(0, 0), (0, 5), (0, 7)], workers=3)
-
-
-def test_c5_yi_long_reduced():
-    """Config 5 shape per unit (G=8, split cache), 4 layers, k=1024, drifting mean."""
-    spec = spec_for("c5_yi_long", L=4, k=1024, T=1500)
-    _run(spec, seed=5, units=[(0, 0), (3, 0)], workers=2)
-
-
-def test_c4_stack_reduced():
-    """Config 4 shape per unit (MHA, one unsplit chunk, boosted keys), 2 layers x 3 sequences,
-    capacity halved to keep the oracle's fill phase short."""
-    spec = spec_for("c4_llama7b_stack", L=2, B=3, k=2048, T=2048 + 100)
-    _run(spec, seed=4, units=[(1, 2)], chunk_steps=128)
-
-
 # ---- full-size configurations ------------------------------------------------------------------
 def test_c2_llama7b_layer_full():
     """Config 2 complete: 4096-token stream through k=512 (512 fill + 3584 evicting steps).
@@ -143,20 +136,20 @@ def test_c2_llama7b_layer_full():
     assert stats[0]["evict_steps"] == spec.T - spec.k
 
 
-def test_c3_mistral_gqa_full():
+def test_c3_mistral_gqa_full(say):
     """Config 3 complete, in the launch configuration bench.py times (B=64, 512 workgroups): ALL 64
     sequences are followed by the oracle through all 3072 steps (1024 fill + 2048 evicting), final map
     and cached rows bit-exact; mismatch / near-tie counts are printed per sequence."""
     spec = spec_for("c3_mistral_gqa")
     units = [(0, b) for b in range(spec.B)]
-    stats, res = _run(spec, seed=3, units=units, workers=WORKERS)
+    stats, res = _run(spec, seed=3, units=units, workers=WORKERS, progress=say)
     assert res["layout"] == (1, 1024, 512, 512)
     assert len(stats) == 64 and all(s["steps"] == 3072 and s["evict_steps"] == 2048 for s in stats)
-    print(f"[parity] c3: 64 sequences x 3072 steps; near-tie steps {sum(s['near_tie_steps'] for s in stats)}, "
-          f"mismatches {sum(s['mismatches'] for s in stats)}, max rel err {max(s['max_rel_err'] for s in stats):.2e}", flush=True)
+    say(f"[parity] c3: 64 sequences x 3072 steps; near-tie steps {sum(s['near_tie_steps'] for s in stats)}, "
+          f"mismatches {sum(s['mismatches'] for s in stats)}, max rel err {max(s['max_rel_err'] for s in stats):.2e}")
 
 
-def test_c4_llama7b_stack_full_shape():
+def test_c4_llama7b_stack_full_shape(say):
     """Config 4 at its real shape (32 layers x 64 sequences, k=4096: 128 GiB of cache, 2,048 units of 32
     KV heads each, a workgroup per unit).  The 4096 fill steps are replaced by laying the first 4096
     tokens down directly (what the no-op branch produces); then ALL 512 decode steps at full
@@ -172,7 +165,7 @@ def test_c4_llama7b_stack_full_shape():
     units = sorted({(int(l), int(b)) for l, b in zip(rng.integers(0, spec.L, 6), rng.integers(0, spec.B, 6))}
                    | {(0, 0), (31, 63)})[:8]
     assert len(units) == 8
-    res = parity.run_gpu(spec, 4, units, chunk_steps=16, prefill=True, progress=True)
+    res = parity.run_gpu(spec, 4, units, chunk_steps=16, prefill=True, progress=say)
     assert res["layout"][0] == 1 and res["unit_workgroups"] == 1 and res["layout"][3] == 2048
     parity.check_global_invariants(spec, res)
     todo = []
@@ -180,15 +173,15 @@ def test_c4_llama7b_stack_full_shape():
         ev = res["evicted"][:, l, b]
         todo.append(((l, b), parity.tiled_jobs(spec, 4, (l, b), res["out"][:, ui], ev, spec.k, spec.T, 2,
                                                out_t0=spec.k, laid_down=True), ev, spec.k))
-    stats = parity.check_tiled(todo, workers=WORKERS)
+    stats = parity.check_tiled(todo, workers=WORKERS, progress=say)
     for s in stats:
-        print(f"[parity]   {s}", flush=True)
+        say(f"[parity]   {s}")
         assert s["steps"] == 512 and s["evict_steps"] == 512 and s["t_range"] == (4096, 4608)
     for ui, (l, b) in enumerate(units[:2]):
         parity.check_final_rows(spec, 4, (l, b), res["slot_token"][l, b], res["K"][ui], res["V"][ui])
 
 
-def test_c5_yi_long_full_stream():
+def test_c5_yi_long_full_stream(say):
     """Config 5 complete: 70,000 tokens through 32 layers of k=4096 (split cache, multi-step launches).
     Every layer's evicted log is checked for consistency over all 70,000 steps.  The oracle follows ONE
     LAYER THROUGH THE WHOLE STREAM (all 70,000 steps: 4,096 filling + 65,904 evicting) and two more
@@ -200,16 +193,17 @@ def test_c5_yi_long_full_stream():
     t_short = spec.k + 2000
     print(f"[parity] {spec.name} full stream T={spec.T}", flush=True)
     res = parity.run_gpu(spec, 5, units, chunk_steps=500, keep=[(0, spec.T, [0]), (0, t_short, [1, 2])],
-                         progress=True, keep_native=True)
+                         progress=say, keep_native=True)
     parity.check_global_invariants(spec, res)
     ev = res["evicted"]
     full, short = res["out"][(0, spec.T, (0,))], res["out"][(0, t_short, (1, 2))]
     todo = [((5, 0), parity.tiled_jobs(spec, 5, (5, 0), full[:, 0], ev[:, 5, 0], 0, spec.T, 3 * WORKERS), ev[:, 5, 0], spec.k)]
     for i, (l, b) in enumerate(units[1:]):
         todo.append(((l, b), parity.tiled_jobs(spec, 5, (l, b), short[:, i], ev[:, l, b], 0, t_short, 4), ev[:, l, b], spec.k))
-    stats = parity.check_tiled(todo, workers=WORKERS)
+    say("[parity] c5: window jobs built")
+    stats = parity.check_tiled(todo, workers=WORKERS, progress=say)
     for s in stats:
-        print(f"[parity]   {s}", flush=True)
+        say(f"[parity]   {s}")
     assert stats[0]["steps"] == 70000 and stats[0]["evict_steps"] == 70000 - 4096 and stats[0]["t_range"] == (0, 70000)
     assert all(s["steps"] == t_short and s["evict_steps"] == 2000 for s in stats[1:])
     parity.check_final_rows(spec, 5, (5, 0), res["slot_token"][5, 0], res["K"][0], res["V"][0])
@@ -285,10 +279,10 @@ def test_unit_workgroups_single_step_entry_point(monkeypatch):
 def test_unit_workgroups_wide_groups_large_capacity(monkeypatch):
     """Config 5's shape per unit (8 query heads per KV head, k=4096) with a workgroup per unit: the
     logits of a KV head's 8 x 4097 candidates need 131 KB of LDS, so a workgroup takes a CU's LDS to
-    itself.  The first 4096 tokens are laid down directly; 60 evicting steps follow."""
+    itself.  The first 4096 tokens are laid down directly; 40 evicting steps follow."""
     monkeypatch.setenv("TOVA_UNIT_MODE", "1")
-    spec = spec_for("c5_yi_long", L=3, T=4096 + 60)
-    units = [(0, 0), (2, 0)]
+    spec = spec_for("c5_yi_long", L=2, T=4096 + 40)
+    units = [(0, 0), (1, 0)]
     res = parity.run_gpu(spec, 55, units, chunk_steps=32, prefill=True)
     assert res["unit_workgroups"] == 1 and res["layout"][0] == 1
     parity.check_global_invariants(spec, res)
@@ -477,6 +471,77 @@ def test_prefill_variants(variant, monkeypatch):
         parity.check_units(view, 45, units, res, workers=3)
 
 
+@pytest.mark.parametrize("dtype,d,H,H_kv,k,T,L,B,call,group", [PREFILL_SWEEP[i] for i in (0, 2, 4, 5, 7)])
+def test_prefill_groups_from_scratch_route(dtype, d, H, H_kv, k, T, L, B, call, group, monkeypatch):
+    """The guard's way out on every token: TOVA_PREFILL_EXACT=1 sends each token of a full-cache group
+    through the from-scratch route (a single-token step inside the prompt kernel over the candidates
+    that are still there) instead of the corrections.  Same bars against the oracle."""
+    monkeypatch.setenv("TOVA_UNIT_MODE", "1")
+    monkeypatch.setenv("TOVA_PREFILL_EXACT", "1")
+    spec = StreamSpec(f"prefill_exact_{dtype}_d{d}_h{H}_{H_kv}_k{k}", L=L, B=B, H=H, H_kv=H_kv, d=d, dtype=dtype,
+                      k=k, T=T, sink="first", n_sinks=2)
+    units = [(l, b) for l in range(L) for b in range(B)][:4]
+    res = parity.run_gpu(spec, 700 + k, units, n_splits=1, chunk_steps=call, use_prefill=True)
+    assert res["unit_workgroups"] == 1 and res["prefill_group"] == group
+    parity.check_global_invariants(spec, res)
+    stats = parity.check_units(spec, 700 + k, units, res, workers=4)
+    if dtype == "f32":
+        assert all(s["mismatches"] == 0 for s in stats)
+
+
+def test_prefill_guard_when_a_removed_row_held_a_heads_weight():
+    """The case the corrections cannot handle, constructed: a cached row c* is the lowest on the head
+    mean for the first token of a group (every head of that query points away from its key), so it is
+    removed inside the group -- and for a later token of the same group one head points straight at
+    it, so that in the sums taken over everything c* carries all but ~1e-3 of that head's weight.
+    Subtracting it back out would leave that head's output and the token's scores with ~1e-3 relative
+    error; the guard (less than an eighth of the sum left) computes the token from scratch instead.
+    fp32, against the oracle at the 1e-5 bar, victims bit-exact."""
+    from paper_2401_06104_amd import TovaCache
+    from oracle.tova_oracle import TovaOracle
+    L, B, H, H_kv, d, k = 1, 2, 4, 4, 32, 70
+    T = k + 16
+    g = torch.Generator().manual_seed(11)
+    u = torch.randn(d, generator=g); u /= u.norm()
+    q = torch.randn(T, L, B, H, d, generator=g)
+    kk = torch.randn(T, L, B, H_kv, d, generator=g)
+    vv = torch.randn(T, L, B, H_kv, d, generator=g)
+    q -= (q @ u).unsqueeze(-1) * u                       # no query sees u ...
+    kk -= (kk @ u).unsqueeze(-1) * u                     # ... and no key has a component along it
+    c_star, first, later, head = 5, k, k + 3, 2          # token 5 sits in slot 5 when the first full group (tokens k..k+7) starts
+    kk[c_star] += 8.0 * u                                # the special row: logits +-11.3 for queries along -+u
+    q[first] -= 8.0 * u                                  # all heads of the group's first token point away: c* is its victim
+    q[later, :, :, head] += 8.0 * u                      # one head of a later token points straight at it
+    cache = TovaCache(L, B, k, H, H_kv, d, dtype="f32", n_splits=1)
+    assert cache.layout.unit_workgroups == 0             # (few units: force the form that groups prompt tokens)
+    cache.destroy()
+    import os
+    os.environ["TOVA_UNIT_MODE"] = "1"
+    try:
+        cache = TovaCache(L, B, k, H, H_kv, d, dtype="f32", n_splits=1)
+    finally:
+        del os.environ["TOVA_UNIT_MODE"]
+    assert cache.layout.prefill_group == 8
+    qd, kd, vd = q.cuda(), kk.cuda(), vv.cuda()
+    out = torch.empty_like(qd)
+    ev = torch.empty(T, L, B, dtype=torch.int32, device="cuda:0")
+    cache.prefill(qd, kd, vd, out, ev)
+    torch.cuda.synchronize()
+    ev, out = ev.cpu().numpy(), out.cpu().double().numpy()
+    assert (ev[first] == c_star).all()                   # the construction works: c* leaves at the group's first token
+    worst = 0.0
+    for b in range(B):
+        orc = TovaOracle(k, H, H_kv, d)
+        for t in range(T):
+            r = orc.step(q[t, 0, b].double().numpy(), kk[t, 0, b].double().numpy(), vv[t, 0, b].double().numpy())
+            assert r.evicted == int(ev[t, 0, b]), (t, b, r.evicted, int(ev[t, 0, b]))
+            err = (np.abs(out[t, 0, b] - r.out).max(axis=1) / np.abs(r.out).max(axis=1)).max()
+            assert err <= 1e-5, f"token {t} sequence {b}: output rel err {err:.2e}"
+            worst = max(worst, err)
+    print(f"[parity] prompt guard: max rel err {worst:.2e}", flush=True)
+    cache.destroy()
+
+
 def test_prefill_identical_keys_evict_slot_zero(monkeypatch):
     """Exact ties inside a group: with all keys equal every candidate scores the same for every
     token, so each token must take slot 0 from its predecessor (lowest slot index, the token
@@ -663,7 +728,7 @@ REPOS_SWEEP = [
     ("f32", 128, 4, 2, 1, 60, 1, 1, 10000.0, 0),          # capacity 1
     ("f32", 64, 4, 4, 600, 1300, 1, 1, 10000.0, 0),       # gap sums over several candidates per thread
     ("bf16", 128, 32, 8, 300, 900, 1, 3, 10000.0, 0),
-    ("bf16", 128, 32, 32, 512, 1500, 1, 2, 10000.0, 0),   # the paper's setting: a multi-state of 512, every head its own KV head
+    ("bf16", 128, 32, 32, 512, 1000, 1, 2, 10000.0, 0),   # the paper's setting: a multi-state of 512, every head its own KV head
     ("bf16", 64, 16, 2, 130, 500, 2, 2, 10000.0, 0),      # eight query heads per KV head
     ("bf16", 32, 8, 2, 77, 400, 1, 5, 100.0, 4),          # first tokens pinned
     ("bf16", 64, 2, 2, 2100, 2600, 1, 1, 10000.0, 0),     # more than four candidates per thread in the rank count
@@ -747,7 +812,7 @@ def test_repositioned_steps_random_shapes_split_units_match_whole_units(monkeypa
         assert ((runs[0][1][k:] >= pinned) & (runs[0][1][k:] <= k)).all() and (runs[0][1][:k] == -1).all(), what
 
 
-def test_repositioned_llama7b_70k_stream():
+def test_repositioned_llama7b_70k_stream(say):
     """The paper's extrapolation setting at its real shape: one sequence of 70,000 tokens through 32
     layers of LLaMA-2-7B's shape (32 heads, d = 128, bf16) with a multi-state of 512, keys cached
     without positions.  Every layer's evicted log is checked for consistency over all 70,000 steps.
@@ -764,7 +829,7 @@ def test_repositioned_llama7b_70k_stream():
     t_a, t_b, w0, w1 = spec.k + 6000, spec.k + 2000, 60000, 60200
     print(f"[parity] {spec.name} x 32 layers, repositioned, full stream T={spec.T}", flush=True)
     res = parity.run_gpu(spec, 6, units, chunk_steps=500, keep=[(0, t_a, [0]), (0, t_b, [1]), (w0, w1, [2])],
-                         progress=True, rope_base=base, keep_native=True)
+                         progress=say, rope_base=base, keep_native=True)
     parity.check_global_invariants(spec, res)
     ev = res["evicted"]
     st_w0 = parity.replay_slot_tokens(ev[:, 29, 0], spec.k, w0)
@@ -780,12 +845,12 @@ def test_repositioned_llama7b_70k_stream():
                                            2 * WORKERS - 6, rope_base=base), ev[:, 3, 0], spec.k),
                 ((12, 0), parity.tiled_jobs(spec, 6, (12, 0), res["out"][(0, t_b, (1,))][:, 0], ev[:, 12, 0], 0, t_b,
                                             5, rope_base=base), ev[:, 12, 0], spec.k)]
-        stats = parity.check_tiled(todo, workers=max(1, WORKERS - 1))
+        stats = parity.check_tiled(todo, workers=max(1, WORKERS - 1), progress=say)
         for s_ in stats:
-            print(f"[parity]   from the empty cache: {s_}", flush=True)
+            say(f"[parity]   from the empty cache: {s_}")
         assert stats[0]["steps"] == t_a and stats[0]["evict_steps"] == 6000
         assert stats[1]["steps"] == t_b and stats[1]["evict_steps"] == 2000
-        print(f"[parity]   window    : {far.get()}", flush=True)
+        say(f"[parity]   window    : {far.get()}")
 
 
 def test_repositioned_steps_refuse_what_does_not_fit():
