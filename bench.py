@@ -231,6 +231,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hbm-variant", action="store_true",  # (also skips the config-4-shape, repositioned and policy variants)
                     help="skip the extra 32-layer run whose 8 GiB cache cannot sit in the last-level cache")
+    ap.add_argument("--legs", default="all",
+                    help="which of the further configurations to run after the headline: comma list of "
+                         "x32,c2,c5,c4,repos,policy, or all / none (for profiling one kernel at a time)")
     ap.add_argument("--prefill", action="store_true",
                     help="lay the first k tokens down directly instead of running k fill steps, so that every "
                          "step-kernel dispatch in the process is a full-occupancy one (for rocprofv3 --stats)")
@@ -294,7 +297,9 @@ def main():
         "wall_s_timed_region": g["wall_s"],
     }
     legs = not args.no_hbm_variant and args.layers == 1
-    if legs:
+    want = (set() if args.legs == "none" else {"x32", "c2", "c5", "c4", "repos", "policy"} if args.legs == "all"
+            else set(args.legs.split(",")))
+    if legs and "x32" in want:
         # same kernel, 32 independent layers: 8 GiB of cache per step cannot be served from the
         # 256 MB last-level cache, so this is the DRAM-bound figure
         s32 = spec_for("c3_mistral_gqa", L=32, T=1024 + 8 + 192)
@@ -304,14 +309,16 @@ def main():
         r32["roofline"]["traffic_per_step_profiled"] = PROFILED_TRAFFIC_BYTES_PER_STEP_X32
         result["hbm_resident_variant"] = r32
         result["roofline"]["frac_dram_bound"] = r32["roofline"]["frac"]
-    if legs:
+    else:
+        result["roofline"]["frac_dram_bound"] = None
+    if legs and "c2" in want:
         # config 2: one sequence, one layer, k = 512 -- 32 workgroups, latency-bound (ideal: 1 us per step)
         s2 = spec_for("c2_llama7b_layer", T=512 + 64 + 2048)
         g2 = gpu_leg(s2, 2, 2048, 64, "cuda:0")
         result["c2_llama7b_layer"] = leg_record("config 2: LLaMA-2-7B layer, 32 heads MHA, d=128, bf16, batch 1, k=512; 512 fill "
                                                 "steps, then timed steps at full occupancy", s2, g2, 2048,
                                                 "tova_step_kernel<bf16, d=128, G=1, multi-step>")
-    if legs:
+    if legs and "c5" in want:
         # config 5 at its full shape: 32 layers x 1 sequence, 8 query heads per KV head, k = 4096 (split cache,
         # hand-off form).  The first 4096 tokens are laid down directly (what the fill steps produce).
         s5 = spec_for("c5_yi_long", T=4096 + 32 + 512)
@@ -319,7 +326,7 @@ def main():
         result["c5_yi_long"] = leg_record("config 5: Yi-7B-shaped GQA 32/4, d=128, bf16, batch 1, 32 layers, k=4096 (split cache), "
                                           "timed steps at full occupancy of the 70,000-token stream's steady state", s5, g5, 512,
                                           "tova_step_kernel<bf16, d=128, G=8, split cache, multi-step>")
-    if legs:
+    if legs and "c4" in want:
         # config 4 at its full shape: 32 layers x 64 sequences of LLaMA-2-7B's layer shape, k = 4096 -- 128 GiB of
         # cache, 2048 units, a workgroup per unit.  The first 4096 tokens are laid down directly.
         free, _ = torch.cuda.mem_get_info()
@@ -332,7 +339,7 @@ def main():
         r4["prompt_ms_per_token"] = g4["prompt_event_ms"] / 32
         r4["prompt_speedup_over_decode_steps"] = r4["ms_per_step"] / (g4["prompt_event_ms"] / 32)
         result["c4_llama7b_stack"] = r4
-    if legs:
+    if legs and "repos" in want:
         # decode steps beyond the training length (Sec. 7.2): LLaMA-2-7B layer shape with the multi-state of
         # 512 the paper uses there, keys cached without positions; 32 layers x 16 sequences = 512 units
         sr = spec_for("c2_llama7b_layer", L=32, B=16, T=512 + 8 + 32)
@@ -344,7 +351,7 @@ def main():
                                           "steps": 32, "ms_per_step": msr, "achieved_GBps": abr / (msr * 1e-3) / 1e9,
                                           "frac": abr / (msr * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                           "sequence_steps_per_s": 1e3 / msr * 32 * 16, "sane": gr["sane"]}
-    if legs:
+    if legs and "policy" in want:
         # the policy on its own (App. B): fp32 attention weights [L][B][H][k+1] handed in, one launch per step;
         # config 3's layer shape x 32 layers, cache full
         from paper_2401_06104_amd import TovaCache
