@@ -130,10 +130,13 @@ int resolve(const tova_config_t* c, Resolved* r) {
   // ---- groups of C prompt tokens per pass over the cache ----
   // C * G (token, head) combinations share a streamed row; the vector passes hold at most 8.  The
   // multi-token kernel has a plan of its own (a workgroup per unit, whatever form the single-token
-  // steps take), so it is available from kPrefillMinUnits units on: with C tokens per pass over the
-  // cache even a quarter-full device beats token-by-token steps (measured; see the design notes).
+  // steps take), so it can be used with fewer units than fill the device when it still pays.
   r->pf_C = 0;
-  int pf_min_units = kPrefillMinUnits;
+  // Measured on MI355X (us per token, tova_decode_steps -> tova_prefill): one query head per KV head
+  // (groups of 8 or 4 tokens) wins from 128 units on at k = 512 (x1.28; 192 units x1.89; 64 units x0.69)
+  // and from 64 units on at k >= 1024 (x1.4-1.7); grouped heads (groups of 2) only once the units
+  // fill the device (200 units x0.89).  Below that the workgroups of this form are too few.
+  int pf_min_units = (G == 1) ? (k >= 1024 ? 64 : 128) : kPrefillMinUnits;
   if (const char* e = std::getenv("TOVA_PREFILL_MIN_UNITS")) {  // tuning aid / test hook
     const int v = std::atoi(e);
     if (v >= 1) pf_min_units = v;

@@ -77,6 +77,9 @@ def test_validation_errors():
     assert lib.tova_cache_tokens_seen(None, None) == TOVA_EINVAL
     assert lib.tova_cache_set_tokens_seen(None, 0) == TOVA_EINVAL
     assert lib.tova_cache_multi_step_blocks(None, None) == TOVA_EINVAL
+    assert lib.tova_decode_steps_static(None, 3, None, None, None, None, None, None) == TOVA_EINVAL
+    assert lib.tova_cache_status(None, None, None) == TOVA_EINVAL
+    assert lib.tova_cache_recover(None, 0, None) == TOVA_EINVAL
 
 
 @pytest.mark.parametrize("c,expect_S", [
@@ -115,10 +118,38 @@ def test_launch_plan(c, expect_S):
     (cfg(L=8, B=64, k=1024, H=32, Hkv=32, d=128, dt=TOVA_BF16), 1, 8),
     (cfg(L=32, B=16, k=4096, H=32, Hkv=4, d=128, dt=TOVA_BF16), 1, 0),    # 8 heads per KV head: no room for a second token
     (cfg(B=64, k=1024, H=32, Hkv=8, d=128, dt=TOVA_BF16), 0, 0),          # 64 units: the hand-off form, token by token
+    (cfg(L=32, B=4, k=512, H=32, Hkv=32, d=128, dt=TOVA_BF16), 0, 8),     # 128 units, no grouping of heads: prompts are grouped all the same
+    (cfg(L=32, B=2, k=1024, H=32, Hkv=32, d=128, dt=TOVA_BF16), 0, 8),    # 64 units at k >= 1024 likewise
+    (cfg(L=32, B=1, k=512, H=32, Hkv=32, d=128, dt=TOVA_BF16), 0, 0),     # the paper's batch-1 scoring (32 units): token by token
+    (cfg(L=2, B=100, k=1024, H=32, Hkv=8, d=128, dt=TOVA_BF16), 0, 0),    # grouped heads below 256 units: token by token
 ])
 def test_prompt_groups_in_the_plan(c, unit, group):
     lay = tova_cache_layout(c)
     assert lay.unit_workgroups == unit and lay.prefill_group == group
+
+
+def test_policy_fields():
+    """Baseline policies (Sec. 4.1): validated, always planned in the workgroup-per-unit form, H2O with an
+    extra per-slot array in state_mem."""
+    base = dict(L=1, B=3, k=64, H=8, Hkv=4, d=64, dt=TOVA_BF16)
+    def mk(policy=0, heavy=0, pinned=0, **kw):
+        a = dict(base, **kw)
+        return TovaConfig(a["L"], a["B"], a["k"], a["H"], a["Hkv"], a["d"], a["dt"], 0.0, 0, pinned, 0, policy, heavy)
+    _, st0, _ = tova_cache_bytes(mk())
+    for c in (mk(policy=1), mk(policy=1, pinned=4), mk(policy=2), mk(policy=2, heavy=10)):
+        lay = tova_cache_layout(c)
+        assert lay.unit_workgroups == 1 and lay.prefill_group == 0
+    _, st2, _ = tova_cache_bytes(mk(policy=2))
+    lay2 = tova_cache_layout(mk(policy=2))
+    assert st2 >= st0 + 4 * 3 * 64 and lay2.h2o_acc_offset + 4 * 3 * 64 <= st2 and lay2.h2o_acc_offset > lay2.error_flag_offset
+    for bad in (mk(policy=3), mk(policy=-1), mk(policy=2, pinned=1), mk(policy=2, heavy=64), mk(policy=0, heavy=3),
+                mk(policy=1, heavy=3)):
+        with pytest.raises(TovaError) as e:
+            tova_cache_bytes(bad)
+        assert e.value.status == TOVA_EINVAL
+    with pytest.raises(TovaError) as e:                      # a KV head's logits must fit on-chip memory in this form
+        tova_cache_layout(mk(policy=1, k=1 << 16, H=8, Hkv=1, d=128))
+    assert e.value.status == TOVA_ENOSUP
 
 
 def test_forced_splits_are_normalised():
