@@ -357,7 +357,7 @@ inline hipError_t ensure_dynamic_lds(int bytes) {
 // logit_pass writes the log2-domain logits l2[j][h] = scale2 * q_h . K[j] to e_lds[j * NH + h]
 // (own candidate r is row nrows + r) and leaves per-lane running maxima in m (to be block-reduced).
 
-template <typename T, int D, int NH, typename QPtr, typename OwnPtr, typename Mask>
+template <typename T, int D, int NH, int UM = 2, typename QPtr, typename OwnPtr, typename Mask>
 __device__ __forceinline__ void logit_pass(const T* Kb, int nrows, int n_own, bool own_here, QPtr&& qp,
                                            OwnPtr&& ownp, Mask&& masked, float scale2, int lane, int wave,
                                            int nw, float* e_lds, float (&m)[NH]) {
@@ -373,8 +373,7 @@ __device__ __forceinline__ void logit_pass(const T* Kb, int nrows, int n_own, bo
     // eight elements a lane holds is free as long as A and B agree: MFMA kk takes the 16-byte
     // chunk kk * 4 + l / 16, so the four lanes of a row load 64 contiguous bytes.  Result register
     // r of lane l is the logit of row (l / 16) * 4 + r for column l % 16.
-    constexpr int KK = D / 32;
-    constexpr int UM = 2;  // 16-row tiles per register buffer
+    constexpr int KK = D / 32;  // (UM: 16-row tiles per register buffer)
     const int r16 = lane & 15, c4 = lane >> 4;
     V16 qm[KK];
 #pragma unroll
@@ -536,8 +535,7 @@ __device__ __forceinline__ void logit_pass(const T* Kb, int nrows, int n_own, bo
 template <typename T, int D, int NH, int UVN>
 __device__ __forceinline__ void pv_first_tile(V16 (&vA)[UVN], const T* Vb, int nrows, int lane, int wave) {
   using Ge = Geo<T, D, NH>;
-  constexpr int VEC = Ge::VEC, LV = Ge::LV, RV = Ge::RV, UV = Ge::UV;
-  static_assert(UVN == UV, "tile shape");
+  constexpr int VEC = Ge::VEC, LV = Ge::LV, RV = Ge::RV, UV = UVN;  // (rows per lane and buffer: the caller's choice)
   const int lv = lane % LV, rv = lane / LV;
   const int base = wave * RV * UV;
 #pragma unroll
@@ -553,8 +551,8 @@ __device__ __forceinline__ void pv_pass(const T* Vb, int nrows, int n_own, bool 
                                         V16 (&vA)[UVN], float (&acc)[NH][VECN]) {
   using E = Elem<T>;
   using Ge = Geo<T, D, NH>;
-  constexpr int VEC = Ge::VEC, LV = Ge::LV, RV = Ge::RV, UV = Ge::UV;
-  static_assert(UVN == UV && VECN == VEC, "tile shape");
+  constexpr int VEC = Ge::VEC, LV = Ge::LV, RV = Ge::RV, UV = UVN;
+  static_assert(VECN == VEC, "tile shape");
   const int lv = lane % LV, rv = lane / LV;
   constexpr int TILEV = RV * UV;
   const int stridev = nw * TILEV;

@@ -45,11 +45,16 @@ namespace {
 
 
 template <typename T, int D, int G, bool MULTI, bool UNIT = false>
-__global__ __launch_bounds__(512, (G >= 8 && MULTI) ? 3 : 4) void tova_step_kernel(const StepParams p) {
+__global__ __launch_bounds__(512, (G >= 8 && MULTI) ? (UNIT ? 3 : 2) : 4) void tova_step_kernel(const StepParams p) {
   static_assert(MULTI || !UNIT, "the one-block-per-unit form is built on the multi-step loop");
   using E = Elem<T>;
   using Ge = Geo<T, D, G>;
-  constexpr int VEC = Ge::VEC, LV = Ge::LV, UV = Ge::UV;
+  constexpr int VEC = Ge::VEC, LV = Ge::LV;
+  // V rows per lane and register buffer.  Wide groups in the hand-off form run two 256-thread workgroups per
+  // CU (two waves per SIMD): with so few waves the V stream is bound by the loads in flight, so the tiles are
+  // twice as deep there (config 5: 59.6 -> 57.1 us per step; a workgroup per unit has more waves and loses
+  // with the deeper tiles, 759 -> 839 us, so it keeps the shallow ones; deeper K tiles gave nothing).
+  constexpr int UV = (G >= 8 && MULTI && !UNIT) ? 4 : Ge::UV;
 
   extern __shared__ float4 smem4[];
   float* small = reinterpret_cast<float*>(smem4);  // kSmallFloats
