@@ -112,6 +112,8 @@ typedef struct {
                                is then L * B, walked by at most a device-filling number of workgroups */
   int32_t prefill_group;    /* tokens of a prompt that share one pass over the cache in tova_prefill
                                (0: it goes token by token)                                         */
+  size_t tokens_seen_offset; /* state_mem: int32, the token count as the device sees it; only kept current by
+                               the calls below that say so (tova_decode_step_graph and its two helpers)  */
   size_t h2o_acc_offset;    /* state_mem: float [L][B][k] (H2O only; with per_head [L][B][H_kv][k]): per slot,
                                the attention weights summed over the query heads and over all steps
                                since the slot's token came in (divide by H for the head average)   */
@@ -269,6 +271,29 @@ int tova_cache_set_tokens_seen(tova_cache_t* cache, int64_t t);
 #define TOVA_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
 int tova_decode_steps_static(tova_cache_t* cache, int32_t n_steps, const void* q, const void* k_new,
                              const void* v_new, void* out, int32_t* evicted, void* hip_stream);
+
+/* One decode step that can be recorded into a HIP graph and replayed for token after token (no
+ * passage of the paper: it is tova_decode_step, Sec. 3.2 + Sec. 4, for callers that replay launches
+ * instead of issuing them).  A launch recorded by the other calls carries the token index as a
+ * host-side argument, so replaying it would process "the same token" again; this call's kernels
+ * read the index from the int32 at tokens_seen_offset of state_mem and a kernel of its own adds 1
+ * to it afterwards.  Arguments and results are those of tova_decode_step; the caller rewrites
+ * q / k_new / v_new in place between replays and reads out / evicted after each.
+ *  - The cache must be full (tokens seen >= k: the launch shape of a filling step depends on the
+ *    row count), else TOVA_ENOSUP.
+ *  - tova_cache_publish_tokens_seen enqueues a kernel that writes the host's count into state_mem:
+ *    call it once, outside the graph, before the first recording or replay, and again after any
+ *    other stepping call or tova_cache_set_tokens_seen.
+ *  - Called on a stream that is being captured, the call records its kernels and leaves the
+ *    host's count alone (nothing ran); called eagerly it counts one token like any other call.
+ *  - After replays the host's count is behind: tova_cache_fetch_tokens_seen waits for the stream,
+ *    reads the count back from state_mem (HOST out pointer t, may be NULL) and makes it the
+ *    host's; do that before any other call on the cache.
+ * Nothing is allocated and no memset is recorded (fill kernels only). */
+int tova_decode_step_graph(tova_cache_t* cache, const void* q, const void* k_new, const void* v_new,
+                           void* out, int32_t* evicted, void* hip_stream);
+int tova_cache_publish_tokens_seen(tova_cache_t* cache, void* hip_stream);
+int tova_cache_fetch_tokens_seen(tova_cache_t* cache, void* hip_stream, int64_t* t);
 
 /* Failure handling of the multi-step launches (no passage of the paper: library bookkeeping).
  * tova_cache_status waits for the stream (hipStreamSynchronize) and reads the cache's error flag:

@@ -37,7 +37,7 @@ class TovaLayout(ctypes.Structure):
     _fields_ = [("k_offset", c_size_t), ("v_offset", c_size_t), ("occupancy_offset", c_size_t),
                 ("slot_token_offset", c_size_t), ("error_flag_offset", c_size_t), ("n_splits", c_int32), ("rows_per_split", c_int32),
                 ("block_threads", c_int32), ("grid_blocks", c_int32), ("lds_bytes", c_int32),
-                ("unit_workgroups", c_int32), ("prefill_group", c_int32), ("h2o_acc_offset", c_size_t)]
+                ("unit_workgroups", c_int32), ("prefill_group", c_int32), ("tokens_seen_offset", c_size_t), ("h2o_acc_offset", c_size_t)]
 
 
 def library_path() -> str:
@@ -74,6 +74,9 @@ def load_library() -> ctypes.CDLL:
     lib.tova_cache_tokens_seen.argtypes = [c_void_p, POINTER(c_int64)]
     lib.tova_cache_multi_step_blocks.argtypes = [c_void_p, POINTER(c_int32)]
     lib.tova_cache_set_tokens_seen.argtypes = [c_void_p, c_int64]
+    lib.tova_decode_step_graph.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.tova_cache_publish_tokens_seen.argtypes = [c_void_p, c_void_p]
+    lib.tova_cache_fetch_tokens_seen.argtypes = [c_void_p, c_void_p, POINTER(c_int64)]
     lib.tova_cache_status.argtypes = [c_void_p, c_void_p, POINTER(c_int32)]
     lib.tova_cache_recover.argtypes = [c_void_p, c_int64, c_void_p]
     lib.tova_cache_destroy.argtypes = [c_void_p]
@@ -81,7 +84,8 @@ def load_library() -> ctypes.CDLL:
     lib.tova_strerror.restype = c_char_p
     for name in ("tova_cache_bytes", "tova_cache_layout", "tova_cache_init", "tova_decode_step",
                  "tova_decode_steps", "tova_decode_steps_static", "tova_prefill", "tova_cache_tokens_seen", "tova_cache_set_tokens_seen",
-                 "tova_cache_multi_step_blocks", "tova_cache_status", "tova_cache_recover",
+                 "tova_cache_multi_step_blocks", "tova_cache_status", "tova_cache_recover", "tova_decode_step_graph",
+                 "tova_cache_publish_tokens_seen", "tova_cache_fetch_tokens_seen",
                  "tova_decode_steps_repositioned", "tova_policy_step", "tova_cache_destroy"):
         getattr(lib, name).restype = c_int
     _LIB = lib
@@ -250,6 +254,31 @@ class TovaCache:
                                        out.data_ptr(), ev, _stream_handle(stream))
         if rc != TOVA_OK:
             raise TovaError(rc, "tova_decode_step")
+
+    def decode_step_graph(self, q, k_new, v_new, out, evicted=None, stream=None):
+        """decode_step whose token index lives in state_mem: can be recorded into a graph and replayed."""
+        c = self.cfg
+        self._check("q", q, (c.n_layers, c.batch, c.n_q_heads, c.head_dim))
+        self._check("k_new", k_new, (c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        self._check("v_new", v_new, (c.n_layers, c.batch, c.n_kv_heads, c.head_dim))
+        self._check("out", out, (c.n_layers, c.batch, c.n_q_heads, c.head_dim))
+        ev = self._evicted_ptr(evicted, self.state_shape)
+        rc = self.lib.tova_decode_step_graph(self._h, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
+                                             out.data_ptr(), ev, _stream_handle(stream))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_decode_step_graph")
+
+    def publish_tokens_seen(self, stream=None):
+        rc = self.lib.tova_cache_publish_tokens_seen(self._h, _stream_handle(stream))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_cache_publish_tokens_seen")
+
+    def fetch_tokens_seen(self, stream=None) -> int:
+        t = c_int64()
+        rc = self.lib.tova_cache_fetch_tokens_seen(self._h, _stream_handle(stream), byref(t))
+        if rc != TOVA_OK:
+            raise TovaError(rc, "tova_cache_fetch_tokens_seen")
+        return t.value
 
     def decode_steps(self, q, k_new, v_new, out, evicted=None, stream=None):
         c = self.cfg

@@ -41,7 +41,7 @@ struct Resolved {
   float scale;
   size_t kv_bytes, state_bytes, scratch_bytes;
   size_t v_off;                                   // in kv_mem
-  size_t occ_off, slot_off, err_off;              // in state_mem
+  size_t occ_off, slot_off, err_off, tok_off;     // in state_mem
   size_t cnt_pair_off, cnt_unit_off, cnt_pub_off, slow_off, pstate_off, cnt_bytes;   // in scratch_mem
   size_t sg_off, escr_off, stats_off, accp_off;
 };
@@ -248,6 +248,7 @@ int resolve(const tova_config_t* c, Resolved* r) {
   r->occ_off = 0;
   r->slot_off = round_up((size_t)r->units * 4, kAlign);
   r->err_off = r->slot_off + round_up((size_t)r->units * k * 4, kAlign);
+  r->tok_off = r->err_off + 64;  // (same 256-byte block as the error flag)
   r->acc_off = r->err_off + kAlign;
   r->state_bytes = r->acc_off + (r->policy == TOVA_POLICY_H2O ? round_up((size_t)r->units * k * 4, kAlign) : 0);
 
@@ -328,6 +329,7 @@ int tova_cache_layout(const tova_config_t* cfg, tova_layout_t* layout) {
   layout->unit_workgroups = r.unit_mode;
   layout->prefill_group = r.pf_C;
   layout->h2o_acc_offset = r.acc_off;
+  layout->tokens_seen_offset = r.tok_off;
   return TOVA_OK;
 }
 
@@ -373,6 +375,8 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
     e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->scratch), 0, r.cnt_bytes / 4, s);
   if (e == hipSuccess)
     e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->state + r.err_off), 0, 1, s);
+  if (e == hipSuccess)
+    e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->state + r.tok_off), 0, 1, s);
   if (e == hipSuccess && r.policy == TOVA_POLICY_H2O)  // (0.0f is the all-zero word)
     e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->state + r.acc_off), 0, (size_t)r.units * r.k, s);
   // A multi-step launch needs all its blocks resident at once (blocks of a unit wait for each
@@ -502,7 +506,7 @@ int check_step_args(const tova_cache* c, int32_t n_steps, const void* q, const v
 // (scratch_mem of tova_cache_init) or the library's static one (tova_decode_steps_static).
 // Arguments have been checked; n_steps >= 1.
 int decode_steps_on(tova_cache* c, char* scratch, int32_t n_steps, const void* q, const void* k_new,
-                    const void* v_new, void* out, int32_t* evicted, hipStream_t s) {
+                    const void* v_new, void* out, int32_t* evicted, hipStream_t s, bool token_from_device = false) {
   const Resolved& r = c->r;
 
   const size_t q_step = (size_t)r.units * r.H * r.D * r.esize;
@@ -541,7 +545,8 @@ int decode_steps_on(tova_cache* c, char* scratch, int32_t n_steps, const void* q
     p.out = static_cast<char*>(out) + (size_t)i * q_step;
     p.evicted = evicted ? evicted + (size_t)i * r.units : nullptr;
     p.n = (int32_t)(c->t < r.k ? c->t : r.k);
-    p.t = (int32_t)c->t;
+    p.t = token_from_device ? 0 : (int32_t)c->t;
+    p.t_dev = token_from_device ? reinterpret_cast<const int32_t*>(c->state + r.tok_off) : nullptr;
     // all remaining steps in one launch once the cache is full (see tova.h)
     const int32_t m = (r.multi_step && c->t >= r.k && n_steps - i >= 2) ? n_steps - i : 1;
     p.n_iter = m;
@@ -569,6 +574,43 @@ int tova_decode_steps(tova_cache_t* c, int32_t n_steps, const void* q, const voi
   if (rc != TOVA_OK || n_steps == 0) return rc;
   if (!c->scratch) return TOVA_EINVAL;  // (a cache made for tova_decode_steps_static only)
   return decode_steps_on(c, c->scratch, n_steps, q, k_new, v_new, out, evicted, static_cast<hipStream_t>(hip_stream));
+}
+
+int tova_cache_publish_tokens_seen(tova_cache_t* c, void* hip_stream) {
+  if (!c) return TOVA_EINVAL;
+  const hipError_t e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(c->state + c->r.tok_off), (int32_t)c->t, 1,
+                                             static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_fail(e, "tova_cache_publish_tokens_seen");
+  return TOVA_OK;
+}
+
+int tova_cache_fetch_tokens_seen(tova_cache_t* c, void* hip_stream, int64_t* t) {
+  if (!c) return TOVA_EINVAL;
+  int32_t v = 0;
+  const hipError_t e = tova::read_i32_sync(reinterpret_cast<const int32_t*>(c->state + c->r.tok_off),
+                                           static_cast<hipStream_t>(hip_stream), &v);
+  if (e != hipSuccess) return hip_fail(e, "tova_cache_fetch_tokens_seen");
+  if (v < 0) return TOVA_EINVAL;
+  c->t = v;
+  if (t) *t = v;
+  return TOVA_OK;
+}
+
+int tova_decode_step_graph(tova_cache_t* c, const void* q, const void* k_new, const void* v_new, void* out,
+                           int32_t* evicted, void* hip_stream) {
+  const int rc = check_step_args(c, 1, q, k_new, v_new, out, evicted);
+  if (rc != TOVA_OK) return rc;
+  if (!c->scratch) return TOVA_EINVAL;
+  if (c->t < c->r.k) return TOVA_ENOSUP;  // (the launch shape of a filling step depends on the row count)
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const bool capturing = tova::stream_is_capturing(s) != 0;
+  const int64_t t_before = c->t;
+  const int rs = decode_steps_on(c, c->scratch, 1, q, k_new, v_new, out, evicted, s, true);
+  if (rs != TOVA_OK) return rs;
+  const hipError_t e = tova::launch_add_i32(reinterpret_cast<int32_t*>(c->state + c->r.tok_off), 1, s);
+  if (e != hipSuccess) return hip_fail(e, "tova_decode_step_graph: advancing the token count");
+  if (capturing) c->t = t_before;  // nothing ran: the replays will, and the count in state_mem follows them
+  return TOVA_OK;
 }
 
 int tova_decode_steps_static(tova_cache_t* c, int32_t n_steps, const void* q, const void* k_new,

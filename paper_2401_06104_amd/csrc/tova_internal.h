@@ -58,6 +58,7 @@ struct StepParams {
   int32_t S, R;        // chunks per KV head, slots per chunk
   int32_t kp;          // k + 1 rounded up to 64: stride of sg / escr
   int32_t t;           // index of the incoming token
+  const int32_t* t_dev;  // non-null: read the index from there instead (a step recorded into a graph)
   float scale;
 };
 
@@ -149,6 +150,10 @@ hipError_t launch_repos(int dtype_is_bf16, int D, int G, const ReposParams& p, c
 int repos_resident_blocks(int dtype_is_bf16, int D, int G, int block, int lds_bytes);
 hipError_t launch_policy(const PolicyParams& p, hipStream_t stream);
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_t stream);
+// *dst += add, by a kernel of its own (so that it is ordered behind the kernels that read *dst)
+hipError_t launch_add_i32(int32_t* dst, int32_t add, hipStream_t stream);
+// nonzero while the stream is being recorded into a graph
+int stream_is_capturing(hipStream_t stream);
 // waits for the stream, then copies one int32 from device memory to *host
 hipError_t read_i32_sync(const int32_t* dev, hipStream_t stream, int32_t* host);
 // how many blocks of the step kernel (given instantiation, block size, dynamic LDS) fit on the

@@ -116,7 +116,9 @@ __global__ __launch_bounds__(512, (G >= 8 && MULTI) ? (UNIT ? 3 : 2) : 4) void t
   const int ncached = r1 - r0;                 // cached rows of this chunk
   const bool has_new = (chunk == c_new);       // local candidate `ncached` is the incoming token
   const int nloc = ncached + (has_new ? 1 : 0);  // local candidates, >= 1
-  const int tok = p.t + it;  // index of the incoming token
+  // index of the incoming token: the host's count, or (a step recorded into a graph, replayed for token
+  // after token) the count kept in state_mem, which a kernel of its own advances after this one
+  const int tok = (p.t_dev ? __builtin_amdgcn_readfirstlane(ld_agent_i(p.t_dev)) : p.t) + it;
 
   if (MULTI && !UNIT && it > 0) {
     const int pair = pair0;
@@ -738,6 +740,24 @@ int device_cus() {
   if (hipGetDevice(&dev) != hipSuccess) return 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
   return cus;
+}
+
+__global__ void tova_add_i32_kernel(int32_t* dst, int32_t add) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) *dst += add;
+}
+
+hipError_t launch_add_i32(int32_t* dst, int32_t add, hipStream_t stream) {
+  hipLaunchKernelGGL(tova_add_i32_kernel, dim3(1), dim3(64), 0, stream, dst, add);
+  return hipGetLastError();
+}
+
+int stream_is_capturing(hipStream_t stream) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &st) != hipSuccess) {
+    (void)hipGetLastError();  // (the legacy default stream cannot be asked while another one captures)
+    return 0;
+  }
+  return st == hipStreamCaptureStatusActive;
 }
 
 hipError_t read_i32_sync(const int32_t* dev, hipStream_t stream, int32_t* host) {

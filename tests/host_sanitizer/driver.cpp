@@ -105,6 +105,17 @@ int main() {
       EXPECT(tova_decode_steps_repositioned(h, 4, q, q, q, q, ev, 0.f, nullptr) == TOVA_ENOSUP);
       EXPECT(tova_policy_step(h, reinterpret_cast<const float*>(q), q, q, ev, nullptr) == TOVA_ENOSUP);
     }
+    {  // the replayable step: refused while the cache fills, counted like any step when run eagerly
+      EXPECT(tova_cache_set_tokens_seen(h, k - 1 > 0 ? k - 1 : 0) == TOVA_OK);
+      if (k > 1) EXPECT(tova_decode_step_graph(h, q, q, q, q, ev, nullptr) == TOVA_ENOSUP);
+      EXPECT(tova_cache_set_tokens_seen(h, k + 3) == TOVA_OK);
+      EXPECT(tova_cache_publish_tokens_seen(h, nullptr) == TOVA_OK);
+      EXPECT(tova_decode_step_graph(h, q, q, q, q, ev, nullptr) == TOVA_OK);
+      EXPECT(tova_cache_tokens_seen(h, &t) == TOVA_OK && t == k + 4);
+      int64_t td = -1;
+      EXPECT(tova_cache_fetch_tokens_seen(h, nullptr, &td) == TOVA_OK && td == 0);   // (the stub's device memory reads 0)
+      EXPECT(tova_decode_step_graph(nullptr, q, q, q, q, ev, nullptr) == TOVA_EINVAL);
+    }
     int32_t gave_up = 7, blocks = -1;
     EXPECT(tova_cache_status(h, nullptr, &gave_up) == TOVA_OK && gave_up == 0);
     EXPECT(tova_cache_recover(h, k, nullptr) == TOVA_OK && tova_cache_tokens_seen(h, &t) == TOVA_OK && t == k);

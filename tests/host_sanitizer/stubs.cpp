@@ -61,6 +61,12 @@ hipError_t launch_fill_i32(int32_t* dst, int32_t, size_t count, hipStream_t) {
   ++g_launches;
   return hipSuccess;
 }
+hipError_t launch_add_i32(int32_t* dst, int32_t, hipStream_t) {
+  require(dst != nullptr, "counter to advance");
+  ++g_launches;
+  return hipSuccess;
+}
+int stream_is_capturing(hipStream_t) { return 0; }
 hipError_t read_i32_sync(const int32_t*, hipStream_t, int32_t* host) {
   *host = 0;
   return hipSuccess;

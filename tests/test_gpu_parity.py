@@ -719,6 +719,65 @@ def test_multi_step_wait_runs_out_and_the_cache_recovers(monkeypatch):
     cache.destroy()
 
 
+# ---- one recorded step, replayed for token after token ------------------------------------------
+@pytest.mark.parametrize("unit_mode,splits", [("0", 1), ("0", 3), ("1", 1)])
+def test_decode_step_graph_replays(unit_mode, splits, monkeypatch):
+    """tova_decode_step_graph keeps the token index in state_mem, so ONE recorded step can be replayed
+    for every further token: the stream's inputs are copied into the recorded buffers (eager work between
+    the replays), the graph is replayed, the outputs are copied out.  Every replay is compared with the
+    same stream stepped eagerly through tova_decode_steps on a twin cache -- bit for bit: outputs,
+    victims, map, rows -- and two sequences are followed by the oracle.  Both forms of the step kernel;
+    the split cache as well."""
+    from paper_2401_06104_amd import TovaCache, TovaError, TOVA_ENOSUP
+    from workloads import Stream
+    monkeypatch.setenv("TOVA_UNIT_MODE", unit_mode)
+    spec = StreamSpec(f"graph_u{unit_mode}_s{splits}", L=2, B=3, H=8, H_kv=2, d=64, dtype="bf16", k=150, T=150 + 40,
+                      sink="first", n_sinks=1)
+    c = Stream(spec, 88, device="cuda:0").chunk(0, spec.T)
+    k, T = spec.k, spec.T
+    ref = TovaCache(spec.L, spec.B, k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype, n_splits=splits)
+    out_ref = torch.empty_like(c["q"])
+    ev_ref = torch.empty(T, spec.L, spec.B, dtype=torch.int32, device="cuda:0")
+    ref.decode_steps(c["q"], c["k"], c["v"], out_ref, ev_ref)
+    cache = TovaCache(spec.L, spec.B, k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype, n_splits=splits)
+    out = torch.empty_like(c["q"])
+    ev = torch.empty(T, spec.L, spec.B, dtype=torch.int32, device="cuda:0")
+    qs, ks, vs = c["q"][0].clone(), c["k"][0].clone(), c["v"][0].clone()       # the recorded call's buffers
+    os_, es = torch.empty_like(qs), torch.empty(spec.L, spec.B, dtype=torch.int32, device="cuda:0")
+    with pytest.raises(TovaError) as e:                                         # not while the cache fills
+        cache.decode_step_graph(qs, ks, vs, os_, es)
+    assert e.value.status == TOVA_ENOSUP
+    cache.decode_steps(c["q"][:k + 2], c["k"][:k + 2], c["v"][:k + 2], out[:k + 2], ev[:k + 2])
+    cache.publish_tokens_seen()
+    qs.copy_(c["q"][k + 2]); ks.copy_(c["k"][k + 2]); vs.copy_(c["v"][k + 2])
+    cache.decode_step_graph(qs, ks, vs, os_, es)                                # once eagerly (also warms everything up)
+    out[k + 2].copy_(os_); ev[k + 2].copy_(es)
+    assert cache.tokens_seen == k + 3
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        cache.decode_step_graph(qs, ks, vs, os_, es)
+    assert cache.tokens_seen == k + 3                                            # recording ran nothing
+    for t in range(k + 3, T):
+        qs.copy_(c["q"][t]); ks.copy_(c["k"][t]); vs.copy_(c["v"][t])
+        g.replay()
+        out[t].copy_(os_); ev[t].copy_(es)
+        if t % 7 == 0:
+            torch.cuda.synchronize()                                             # (host synchronisations between replays too)
+    assert cache.fetch_tokens_seen() == T and cache.tokens_seen == T and cache.status() == 0
+    for name, a, b in (("out", out, out_ref), ("evicted", ev, ev_ref), ("slot_token", cache.slot_token, ref.slot_token),
+                       ("K", cache.K, ref.K), ("V", cache.V, ref.V)):
+        assert torch.equal(a, b), f"{name}: replayed steps differ from tova_decode_steps"
+    units = [(0, 0), (1, 2)]
+    ul, ub = [u[0] for u in units], [u[1] for u in units]
+    res = {"out": out[:, ul, ub].float().cpu().numpy(), "evicted": ev.cpu().numpy(),
+           "slot_token": cache.slot_token.cpu().numpy(), "K": cache.K[ul, ub].float().cpu().numpy(),
+           "V": cache.V[ul, ub].float().cpu().numpy()}
+    parity.check_units(spec, 88, units, res, workers=2)
+    del g
+    cache.destroy(); ref.destroy()
+
+
 # ---- decode steps with re-assigned positions (Sec. 7.2) --------------------------------------
 REPOS_SWEEP = [
     # dtype, d, H, H_kv, k, T, L, B, rope_base, pinned
