@@ -17,6 +17,8 @@ constexpr size_t kAlign = 256;
 constexpr int kTargetBlocks = 512;     // two workgroups per CU on 256 CUs
 constexpr int kUnitModeUnits = 256;    // from one unit per CU on, a workgroup takes a whole unit
 constexpr int kPrefillMinUnits = 256;   // fewest units for which prompt tokens are grouped (see resolve)
+constexpr double kPrefillPartsMinBytes = 600e6;  // ... and the K + V bytes a step must stream for that to pay (see resolve)
+constexpr int kPrefillMaxParts = 16;    // ... and, with fewer units, the most workgroups a unit's KV heads are dealt to
 constexpr int kPrefillMaxGrid = 1024;  // workgroups of the multi-token kernel (each has a scratch area of its own)
 constexpr size_t kMinBytesPerSplit = 256 * 1024;  // K+V bytes of a chunk below which splitting only adds
                                                   // hand-offs (each costs ~1 us of memory round trip)
@@ -37,7 +39,8 @@ struct Resolved {
   int unit_mode;  // one workgroup per unit instead of one per (unit, KV head, chunk)
   int pf_C, pf_NT, pf_lds, pf_e_floats, pf_ncp;  // multi-token kernel: tokens per group (0 = not available) and its LDS plan
   int pf_grid;                                   // ... its workgroups (decided in tova_cache_init)
-  size_t uscr_off;
+  int pf_parts_max;                              // few units: at most this many workgroups per unit (0: a workgroup per unit only)
+  size_t uscr_off, tpart_off, stat_off, gpos_off;
   float scale;
   size_t kv_bytes, state_bytes, scratch_bytes;
   size_t v_off;                                   // in kv_mem
@@ -141,7 +144,27 @@ int resolve(const tova_config_t* c, Resolved* r) {
     const int v = std::atoi(e);
     if (v >= 1) pf_min_units = v;
   }
-  if ((r->unit_mode || r->units >= pf_min_units) && r->policy == TOVA_POLICY_TOVA) {
+  // Fewer units than that: the KV heads of a unit are dealt to several workgroups (see tova_prefill.hip);
+  // how many is decided in tova_cache_init, which can ask the device how many fit at once.
+  // Measured (us per token, decode steps -> prompt with parts; 32 heads, d = 128, bf16): it pays once a
+  // step streams enough for the one workgroup per unit that resolves a group not to be the bottleneck --
+  // 32 units at k = 512 / 1024 / 1536 / 2048 / 4096: x0.47 / 0.92 / 1.55 / 1.98 / 2.49; 64 units at
+  // k = 512 x1.02; 8 / 16 units at k = 4096 x1.03 / 1.71; 4 heads per KV head, k = 1024, 64 / 128 / 160
+  // units: x0.69 / 1.15 / 1.22 -- i.e. from about 600 MB of K and V per step on.
+  r->pf_parts_max = 0;
+  if (!r->unit_mode && r->units < pf_min_units && r->H_kv >= 2) {
+    const double step_bytes = 2.0 * (double)r->pairs * k * r->D * r->esize;
+    const char* e = std::getenv("TOVA_PREFILL_PARTS");  // tuning aid / test hook: at most this many (1: never); given, it
+    if (step_bytes >= kPrefillPartsMinBytes || e) {     // also lifts the size condition
+      r->pf_parts_max = r->H_kv < kPrefillMaxParts ? r->H_kv : kPrefillMaxParts;
+      if (e) {
+        const int v = std::atoi(e);
+        if (v >= 1 && v < r->pf_parts_max) r->pf_parts_max = v;
+      }
+      if (r->pf_parts_max < 2) r->pf_parts_max = 0;
+    }
+  }
+  if ((r->unit_mode || r->units >= pf_min_units || r->pf_parts_max) && r->policy == TOVA_POLICY_TOVA) {
     const int cands[3] = {8, 4, 2};
     for (int ci = 0; ci < 3 && !r->pf_C; ++ci) {
       const int C = cands[ci], GE = G * C;
@@ -272,6 +295,12 @@ int resolve(const tova_config_t* c, Resolved* r) {
     const size_t blocks = (size_t)(r->units < kPrefillMaxGrid ? r->units : kPrefillMaxGrid);
     off += round_up(blocks * r->H * r->pf_C * r->D * 4, kAlign);
   }
+  r->tpart_off = r->stat_off = r->gpos_off = off;
+  if (r->pf_C && r->pf_parts_max) {  // what the parts of a unit hand to the one that resolves a group
+    r->tpart_off = off; off += round_up((size_t)r->units * r->pf_parts_max * r->pf_C * r->pf_ncp * 4, kAlign);
+    r->stat_off = off; off += round_up((size_t)r->units * r->H * r->pf_C * 2 * 4, kAlign);
+    r->gpos_off = off; off += round_up((size_t)r->units * 8 * 4, kAlign);
+  }
   r->scratch_bytes = off;
   return TOVA_OK;
 }
@@ -293,6 +322,7 @@ struct tova_cache {
   int64_t t;  // tokens seen
   // environment hooks, read once in tova_cache_init
   int prefill_group_off;  // TOVA_PREFILL_GROUP=0: prompts go token by token
+  int pf_parts;           // workgroups per unit of the multi-token kernel: 1, or (few units) >= 2; 0: no grouping
   int prefill_exact;      // TOVA_PREFILL_EXACT=1: test hook, every grouped token takes the guard's from-scratch route
   int repos_threads;      // TOVA_REPOS_THREADS (0: the plan's own choice)
   int repos_parts;        // TOVA_REPOS_PARTS (0: no limit given)
@@ -427,6 +457,18 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
     if (g > r.units) g = r.units;
     c->r.pf_grid = g;
   }
+  c->pf_parts = r.pf_C ? 1 : 0;
+  if (r.pf_C && r.pf_parts_max) {
+    // few units: as many workgroups per unit as divide the KV heads and are all resident (the parts of
+    // a unit wait for the one that resolves a group)
+    const int cap = tova::prefill_resident_blocks(r.bf16, r.D, r.G, r.pf_C, r.pf_NT, r.pf_lds);
+    c->pf_parts = 0;
+    for (int pc = r.pf_parts_max; pc >= 2; --pc)
+      if (r.H_kv % pc == 0 && (long long)r.units * pc <= cap) {
+        c->pf_parts = pc;
+        break;
+      }
+  }
   if (e != hipSuccess) {
     delete c;
     return hip_fail(e, "tova_cache_init");
@@ -447,7 +489,8 @@ int tova_prefill(tova_cache_t* c, int32_t n_tokens, const void* q, const void* k
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const size_t q_step = (size_t)r.units * r.H * r.D * r.esize;
   const size_t kv_step = (size_t)r.pairs * r.D * r.esize;
-  const int C = c->prefill_group_off ? 0 : r.pf_C;
+  const int C = (c->prefill_group_off || c->pf_parts == 0) ? 0 : r.pf_C;
+  const int parts = c->pf_parts > 1 ? c->pf_parts : 1;
   for (int32_t i = 0; i < n_tokens;) {
     const void* qi = static_cast<const char*>(q) + (size_t)i * q_step;
     const void* ki = static_cast<const char*>(k_new) + (size_t)i * kv_step;
@@ -472,8 +515,19 @@ int tova_prefill(tova_cache_t* c, int32_t n_tokens, const void* q, const void* k
       p.n_chunks = n_chunks; p.units = r.units; p.H = r.H; p.H_kv = r.H_kv; p.k = r.k;
       p.n_pinned = r.n_pinned; p.t = (int32_t)c->t; p.e_floats = r.pf_e_floats; p.ncp = r.pf_ncp; p.scale = r.scale;
       p.force_exact = c->prefill_exact;
-      const tova::LaunchPlan lp{r.pf_grid, r.pf_NT, r.pf_lds};
-      const hipError_t e = tova::launch_prefill(r.bf16, r.D, r.G, C, p, lp, s);
+      p.parts = parts;
+      p.spin = r.persist_spin;
+      p.tpart = reinterpret_cast<float*>(c->scratch + r.tpart_off);
+      p.stat = reinterpret_cast<float*>(c->scratch + r.stat_off);
+      p.gpos = reinterpret_cast<int32_t*>(c->scratch + r.gpos_off);
+      p.cnt_unit = reinterpret_cast<int32_t*>(c->scratch + r.cnt_unit_off);
+      p.pstate = reinterpret_cast<unsigned long long*>(c->scratch + r.pstate_off);
+      p.error_flag = reinterpret_cast<int32_t*>(c->state + r.err_off);
+      const tova::LaunchPlan lp{parts > 1 ? r.units * parts : r.pf_grid, r.pf_NT, r.pf_lds};
+      hipError_t e = hipSuccess;
+      if (parts > 1 && !filling)  // the units' group counters start from "no group resolved"
+        e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(p.pstate), 0, (size_t)r.units * 2, s);
+      if (e == hipSuccess) e = tova::launch_prefill(r.bf16, r.D, r.G, C, p, lp, s);
       if (e != hipSuccess) return hip_fail(e, "tova_prefill launch");
       c->t += m;
       i += m;

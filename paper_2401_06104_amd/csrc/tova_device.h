@@ -233,6 +233,19 @@ __device__ __forceinline__ float2 ld_agent2(const float* p) {  // p is 8-byte al
   return make_float2(__uint_as_float((uint32_t)r), __uint_as_float((uint32_t)(r >> 32)));
 }
 
+// A 16-byte piece of a cached row: an ordinary load, or (COH) past the caches, for rows that another
+// workgroup of the same launch may have written through.
+template <bool COH>
+__device__ __forceinline__ V16 ld_v16(const void* p) {
+  if constexpr (COH) {
+    const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);
+    const unsigned long long a = ld_agent_u64(q), b = ld_agent_u64(q + 1);
+    return V16{{(uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32)}};
+  } else {
+    return *reinterpret_cast<const V16*>(p);
+  }
+}
+
 // Arrival on a counter.  All threads of the block call it after writing their results with
 // st_agent; it adds `add` to the counter once the block's stores have completed and returns the
 // counter's previous value to every thread.  The caller decides from that value whether it is
@@ -357,7 +370,7 @@ inline hipError_t ensure_dynamic_lds(int bytes) {
 // logit_pass writes the log2-domain logits l2[j][h] = scale2 * q_h . K[j] to e_lds[j * NH + h]
 // (own candidate r is row nrows + r) and leaves per-lane running maxima in m (to be block-reduced).
 
-template <typename T, int D, int NH, int UM = 2, typename QPtr, typename OwnPtr, typename Mask>
+template <typename T, int D, int NH, int UM = 2, bool COH = false, typename QPtr, typename OwnPtr, typename Mask>
 __device__ __forceinline__ void logit_pass(const T* Kb, int nrows, int n_own, bool own_here, QPtr&& qp,
                                            OwnPtr&& ownp, Mask&& masked, float scale2, int lane, int wave,
                                            int nw, float* e_lds, float (&m)[NH]) {
@@ -391,7 +404,7 @@ __device__ __forceinline__ void logit_pass(const T* Kb, int nrows, int n_own, bo
         if (j < nrows) {
           const T* row = Kb + (size_t)j * D;
 #pragma unroll
-          for (int kk = 0; kk < KK; ++kk) dst[u][kk] = *reinterpret_cast<const V16*>(row + (kk * 4 + c4) * 8);
+          for (int kk = 0; kk < KK; ++kk) dst[u][kk] = ld_v16<COH>(row + (kk * 4 + c4) * 8);
         }
       }
     };
@@ -462,7 +475,7 @@ __device__ __forceinline__ void logit_pass(const T* Kb, int nrows, int n_own, bo
         if (j < nrows) {
           const T* row = Kb + (size_t)j * D;
 #pragma unroll
-          for (int c = 0; c < CK; ++c) dst[u][c] = *reinterpret_cast<const V16*>(row + (c * LK + lk) * VEC);
+          for (int c = 0; c < CK; ++c) dst[u][c] = ld_v16<COH>(row + (c * LK + lk) * VEC);
         }
       }
     };
@@ -532,7 +545,7 @@ __device__ __forceinline__ void logit_pass(const T* Kb, int nrows, int n_own, bo
 // (LV lanes per row, RV rows per wave-level load); the caller requests the first tile early with
 // pv_first_tile (so that the V stream is in flight during the softmax barriers) and combines the RV
 // row groups and the waves afterwards.
-template <typename T, int D, int NH, int UVN>
+template <typename T, int D, int NH, bool COH = false, int UVN>
 __device__ __forceinline__ void pv_first_tile(V16 (&vA)[UVN], const T* Vb, int nrows, int lane, int wave) {
   using Ge = Geo<T, D, NH>;
   constexpr int VEC = Ge::VEC, LV = Ge::LV, RV = Ge::RV, UV = UVN;  // (rows per lane and buffer: the caller's choice)
@@ -542,10 +555,10 @@ __device__ __forceinline__ void pv_first_tile(V16 (&vA)[UVN], const T* Vb, int n
   for (int u = 0; u < UV; ++u) {
     const int j = base + u * RV + rv;
     vA[u] = V16{{0u, 0u, 0u, 0u}};
-    if (j < nrows) vA[u] = *reinterpret_cast<const V16*>(Vb + (size_t)j * D + lv * VEC);
+    if (j < nrows) vA[u] = ld_v16<COH>(Vb + (size_t)j * D + lv * VEC);
   }
 }
-template <typename T, int D, int NH, typename OwnPtr, int UVN, int VECN>
+template <typename T, int D, int NH, bool COH = false, typename OwnPtr, int UVN, int VECN>
 __device__ __forceinline__ void pv_pass(const T* Vb, int nrows, int n_own, bool own_here, OwnPtr&& ownp,
                                         const float* e_lds, int NHT, int col0, int lane, int wave, int nw,
                                         V16 (&vA)[UVN], float (&acc)[NH][VECN]) {
@@ -561,7 +574,7 @@ __device__ __forceinline__ void pv_pass(const T* Vb, int nrows, int n_own, bool 
     for (int u = 0; u < UV; ++u) {
       const int j = base + u * RV + rv;
       dst[u] = V16{{0u, 0u, 0u, 0u}};
-      if (j < nrows) dst[u] = *reinterpret_cast<const V16*>(Vb + (size_t)j * D + lv * VEC);
+      if (j < nrows) dst[u] = ld_v16<COH>(Vb + (size_t)j * D + lv * VEC);
     }
   };
   auto accumulate = [&](const V16& row, const float(&w)[NH]) {

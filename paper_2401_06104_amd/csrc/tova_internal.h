@@ -87,6 +87,15 @@ struct PrefillParams {
   int32_t ncp;         // k + C rounded up to a multiple of 4: stride of the tentative score rows
   int32_t force_exact; // test hook: every token of a full-cache group is computed from scratch (the guard's route)
   float scale;
+  // few units: the KV heads of a unit dealt to `parts` workgroups, every workgroup of the grid resident
+  int32_t parts;       // 1 = a workgroup owns a unit; else a divisor of H_kv, and the grid is units * parts
+  int32_t spin;        // polls of a unit's state word before a workgroup gives up
+  float* tpart;        // [units][parts][C][ncp] partial tentative-score rows
+  float* stat;         // [units][H][C][2]       (max, sum) per (head, token)
+  int32_t* gpos;       // [units][8]             slot every token of the unit's last resolved group ended up in (-1: none)
+  int32_t* cnt_unit;   // [units] arrival counters, zero between groups
+  unsigned long long* pstate;  // [units] groups of this launch resolved so far
+  int32_t* error_flag; // set when a workgroup gave up waiting
 };
 
 // Arguments of one launch of the kernel for decode steps with re-assigned positions (tova_repos.hip):
@@ -148,6 +157,7 @@ hipError_t launch_prefill(int dtype_is_bf16, int D, int G, int C, const PrefillP
 hipError_t launch_repos(int dtype_is_bf16, int D, int G, const ReposParams& p, const LaunchPlan& lp, hipStream_t stream);
 // how many workgroups of that kernel fit on the current device at once; 0 if the query fails
 int repos_resident_blocks(int dtype_is_bf16, int D, int G, int block, int lds_bytes);
+int prefill_resident_blocks(int dtype_is_bf16, int D, int G, int C, int block, int lds_bytes);
 hipError_t launch_policy(const PolicyParams& p, hipStream_t stream);
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, size_t count, hipStream_t stream);
 // *dst += add, by a kernel of its own (so that it is ordered behind the kernels that read *dst)

@@ -35,6 +35,17 @@
 //
 // One workgroup per (layer, sequence) unit, KV heads in turn (the form of the single-token kernel
 // for many units): nothing is exchanged between workgroups.  One chunk per KV head.
+//
+// Few units (the paper scores one text at a time: 32 layers = 32 units): the KV heads of a unit are
+// dealt to P workgroups ("parts"), all resident.  Pass A is independent per KV head, so every part
+// runs it for its own heads and hands over, through device memory, its partial tentative-score rows,
+// its heads' softmax statistics and unmasked PV sums; the part that arrives last adds the rows in
+// part order and resolves the group for the whole unit exactly as above, then publishes where every
+// token of the group ended up (its slot, or none) and a per-unit group counter.  Every part waits --
+// bounded, with the cache's error flag as the way out -- for that counter before its next group and
+// stores the rows of its own KV heads itself, written through; the resolving part reads the few rows
+// it needs of other parts' heads past the caches.  While the multi-state still has room nothing is
+// exchanged at all: every part finishes its own heads.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -54,6 +65,26 @@ __device__ __forceinline__ float elem_f32<float>(const float* p, int idx) {
 template <>
 __device__ __forceinline__ float elem_f32<bf16_t>(const bf16_t* p, int idx) {
   return __uint_as_float((uint32_t)p[idx].x << 16);
+}
+
+// element idx of a row that another workgroup of this launch may have written (written through): read
+// past the caches, as the aligned 32-bit word that holds it
+template <typename T>
+__device__ __forceinline__ float elem_f32_agent(const T* p, int idx);
+template <>
+__device__ __forceinline__ float elem_f32_agent<float>(const float* p, int idx) {
+  return ld_agent(p + idx);
+}
+template <>
+__device__ __forceinline__ float elem_f32_agent<bf16_t>(const bf16_t* p, int idx) {
+  const uint32_t w = (uint32_t)ld_agent_i(reinterpret_cast<const int32_t*>(p) + (idx >> 1));
+  return __uint_as_float((idx & 1) ? (w & 0xffff0000u) : (w << 16));
+}
+// a 16-byte piece written through (two 64-bit stores)
+__device__ __forceinline__ void st_agent_v16(V16* dst, const V16& v) {
+  unsigned long long* d = reinterpret_cast<unsigned long long*>(dst);
+  st_agent_u64(d, ((unsigned long long)v.w[1] << 32) | v.w[0]);
+  st_agent_u64(d + 1, ((unsigned long long)v.w[3] << 32) | v.w[2]);
 }
 
 constexpr float kBoundSlack = 1e-4f;  // rounding of the streamed sums against the recomputed ones: ~1e-6
@@ -89,11 +120,19 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
   int* vict = pos + 8;                             // [C] candidate removed at step i
   int* misc = vict + 8;                            // [0] contender count
   const float scale2 = p.scale * kLog2e;
-  float* const ublk = p.uscr + (size_t)blockIdx.x * H * C * D;  // [H][C][D] unmasked PV sums of the unit at hand
+  const int P = p.parts;                 // workgroups per unit (1: a workgroup owns the unit)
+  const int HP = p.H_kv / P;             // KV heads per part
+  int* flag_lds = reinterpret_cast<int*>(small + 480);
+  const bool shared = (P > 1 && !p.filling);  // the parts of a unit hand their results to the one that resolves the group
 
-  for (int ch = 0; ch < p.n_chunks; ++ch) {
-  for (int unit = blockIdx.x; unit < p.units; unit += gridDim.x) {
+  // (with parts on a full cache, an extra pass stores the last group's rows)
+  for (int ch = 0; ch < p.n_chunks + (shared ? 1 : 0); ++ch) {
+  for (int item = blockIdx.x; item < p.units * P; item += gridDim.x) {  // (parts: the grid covers every item)
+  const int unit = item / P, part = item - unit * P;
   const int pair0 = unit * p.H_kv;
+  const int kv0 = part * HP;             // this workgroup's KV heads: kv0 .. kv0 + HP - 1
+  // [H][C][D] unmasked PV sums of the unit at hand: the workgroup's own area, or the unit's when parts share it
+  float* const ublk = p.uscr + (size_t)(P > 1 ? unit : (int)blockIdx.x) * H * C * D;
   // rows cached when the group starts: k once the multi-state is full; while it fills (App. B: nothing
   // is removed while num_kv <= cache_max_size) the groups simply append their tokens
   const int n = p.filling ? p.n0 + ch * C : k;
@@ -101,8 +140,51 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
   const size_t tok_q = (size_t)ch * C * p.q_stride;    // element offset of the group's first token in q / out
   const size_t tok_kv = (size_t)ch * C * p.kv_stride;  // ... in k_new / v_new
 
+  if (shared && ch > 0) {
+    // Wait (bounded) until the unit's previous group is resolved, then put that group's rows of this
+    // part's KV heads into the slots its tokens ended up in.  If the wait runs out -- it cannot while
+    // all workgroups are resident, which the host checks -- the workgroup raises the cache's error flag
+    // and leaves; every other one sees the flag in its own wait and leaves too.
+    const int tid = threadIdx.x;
+    if (tid == 0) {
+      int ok = 0;
+      for (int spin = 0;; ++spin) {
+        if ((int)(uint32_t)ld_agent_u64(p.pstate + unit) == ch) {
+          ok = 1;
+          break;
+        }
+        if (spin >= p.spin || ld_agent_i(p.error_flag) != 0) break;
+        __builtin_amdgcn_s_sleep(4);
+      }
+      if (!ok) st_agent_i(p.error_flag, 1);
+      flag_lds[2] = ok;
+    }
+    __syncthreads();
+    if (flag_lds[2] == 0) return;  // block-uniform
+    if (tid < C) pos[tid] = ld_agent_i(p.gpos + (size_t)unit * 8 + tid);
+    __syncthreads();
+    const size_t prev_kv = (size_t)(ch - 1) * C * p.kv_stride;
+    for (int i = 0; i < C; ++i) {
+      const int ps = pos[i];
+      if (ps < 0) continue;  // block-uniform
+      const T* kn = reinterpret_cast<const T*>(p.k_new) + prev_kv + (size_t)i * p.kv_stride + (size_t)(pair0 + kv0) * D;
+      const T* vn = reinterpret_cast<const T*>(p.v_new) + prev_kv + (size_t)i * p.kv_stride + (size_t)(pair0 + kv0) * D;
+      T* Ku = reinterpret_cast<T*>(p.K) + ((size_t)(pair0 + kv0) * k + ps) * D;
+      T* Vu = reinterpret_cast<T*>(p.V) + ((size_t)(pair0 + kv0) * k + ps) * D;
+      for (int x = tid; x < HP * ROW16; x += nt) {  // (written through: the resolving part may read these rows)
+        const int h = x / ROW16, c16 = x - h * ROW16;
+        st_agent_v16(reinterpret_cast<V16*>(Ku + (size_t)h * k * D) + c16, reinterpret_cast<const V16*>(kn)[x]);
+        st_agent_v16(reinterpret_cast<V16*>(Vu + (size_t)h * k * D) + c16, reinterpret_cast<const V16*>(vn)[x]);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();  // the rows are in place for this workgroup's passes
+    if (ch == p.n_chunks) continue;
+  }
+
   // ================= pass A: one stream of K and V per KV head for all C tokens =================
-  for (int kvh = 0; kvh < p.H_kv; ++kvh) {
+  for (int kvh = kv0; kvh < kv0 + HP; ++kvh) {
   // (a fresh opaque copy of the thread index per KV head: otherwise the lane arithmetic of the
   // body is hoisted out of the loops and kept in registers across them)
   int tid = threadIdx.x;
@@ -156,7 +238,7 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
         float a = 0.f;
 #pragma unroll
         for (int g = 0; g < G; ++g) a = fmaf(e_lds[c * GE + i * G + g], rz[i * G + g], a);
-        if (!p.filling) t_lds[i * ncp + c] = (kvh == 0) ? a : t_lds[i * ncp + c] + a;
+        if (!p.filling) t_lds[i * ncp + c] = (kvh == kv0) ? a : t_lds[i * ncp + c] + a;
       }
     }
 #pragma unroll
@@ -190,7 +272,11 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
     float a = red[x];
     for (int w = 1; w < nw; ++w) a += red[w * GE * D + x];
     const int ge = x / D;
-    ublk[((size_t)(kvh * G + ge % G) * C + ge / G) * D + (x - ge * D)] = a;
+    float* const ud = ublk + ((size_t)(kvh * G + ge % G) * C + ge / G) * D + (x - ge * D);
+    if (shared)
+      st_agent(ud, a);
+    else
+      *ud = a;
   }
   __syncthreads();  // the reduction area is free for the next KV head
   }  // KV heads
@@ -202,6 +288,37 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __builtin_amdgcn_s_waitcnt(0);  // the U sums are in memory before other waves read them
+  if (shared) {
+    // ---- hand over: this part's tentative-score rows and its heads' statistics (the U sums are there
+    //      already); whoever arrives last resolves the group for the unit
+    float* const tp = p.tpart + ((size_t)unit * P + part) * C * ncp;
+    for (int x = tid; x < C * ncp; x += nt) st_agent(tp + x, t_lds[x]);
+    float* const sp = p.stat + (size_t)unit * H * C * 2;
+    for (int x = tid; x < HP * G * C; x += nt) {
+      const int y = kv0 * G * C + x;  // (head, token) entries of this part's heads are contiguous
+      st_agent(sp + 2 * y, mst[y]);
+      st_agent(sp + 2 * y + 1, zst[y]);
+    }
+    const int prev = arrive(p.cnt_unit + unit, 1, flag_lds, tid);
+    if (prev + 1 != P) continue;  // (block-uniform) not the last: on to the next group, which starts with a wait
+    reset_counter(p.cnt_unit + unit, tid);
+    for (int x = tid; x < C * ncp; x += nt) {
+      float a = 0.f;
+      constexpr int PB = 8;  // parts whose loads are issued together
+      for (int q0 = 0; q0 < P; q0 += PB) {
+        float v[PB];
+#pragma unroll
+        for (int u = 0; u < PB; ++u) v[u] = (q0 + u < P) ? ld_agent(p.tpart + ((size_t)unit * P + q0 + u) * C * ncp + x) : 0.f;
+#pragma unroll
+        for (int u = 0; u < PB; ++u) a += v[u];  // (part order)
+      }
+      t_lds[x] = a;
+    }
+    for (int x = tid; x < H * C; x += nt) {
+      mst[x] = ld_agent(sp + 2 * x);
+      zst[x] = ld_agent(sp + 2 * x + 1);
+    }
+  }
   if (tid < C) pos[tid] = -1;
   __syncthreads();
   float* qs = e_lds;                                       // [H][D] the token's queries in fp32
@@ -220,8 +337,10 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
         const T* row = (cand < k) ? reinterpret_cast<const T*>(p.K) + ((size_t)(pair0 + h) * k + cand) * D
                                   : reinterpret_cast<const T*>(p.k_new) + tok_kv + (size_t)(cand - k) * p.kv_stride +
                                         (size_t)(pair0 + h) * D;
+        // (with parts a cached row may have been stored by another workgroup of this launch)
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) kx[hb][e] = (lane + 64 * e < D) ? elem_f32<T>(row, lane + 64 * e) : 0.f;
+        for (int e = 0; e < EPL; ++e)
+          kx[hb][e] = (lane + 64 * e < D) ? ((shared && cand < k) ? elem_f32_agent<T>(row, lane + 64 * e) : elem_f32<T>(row, lane + 64 * e)) : 0.f;
       }
 #pragma unroll
       for (int hb = 0; hb < HB; ++hb) {
@@ -246,16 +365,17 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
 
   if (p.filling) {
     // nothing is removed: out = U / Z, the tokens take the next free slots
-    for (int x = tid; x < C * H * D; x += nt) {
-      const int i = x / (H * D), y = x - i * (H * D), hq = y / D;
+    const int HO = HP * G;  // query heads of this workgroup's KV heads (all of them without parts)
+    for (int x = tid; x < C * HO * D; x += nt) {
+      const int i = x / (HO * D), y = kv0 * G * D + (x - i * (HO * D)), hq = y / D;
       T* outi = reinterpret_cast<T*>(p.out) + tok_q + (size_t)i * p.q_stride + (size_t)unit * H * D;
       E::store(outi + y, ublk[((size_t)hq * C + i) * D + (y - hq * D)] / zst[hq * C + i]);
     }
     if (tid < C) {
       pos[tid] = n + tid;
-      if (evp) evp[(size_t)tid * p.units + unit] = -1;
+      if (evp && part == 0) evp[(size_t)tid * p.units + unit] = -1;
     }
-    if (tid == 0) p.occupancy[unit] = n + C;
+    if (tid == 0 && part == 0) p.occupancy[unit] = n + C;
     __syncthreads();
   }
   for (int i = 0; i < C && !p.filling; ++i) {
@@ -313,13 +433,15 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
         const int n_own = i + 1, ncx = k + n_own;
         const bool own_here = (wave == nw - 1);
         float mx[G], Zx[G];
-        logit_pass<T, D, G>(
+        // (cached rows are read past the caches on this route: with parts another workgroup of the launch
+        // may have stored them, and an earlier trip down this route may have left old copies nearby)
+        logit_pass<T, D, G, 2, true>(
             Kb, k, n_own, own_here, [&](int g) { return qh + g * D; },
             [&](int r) { return knew0 + (size_t)r * p.kv_stride; },
             [&](int, int r) { return r < i && pos[r] < 0; },  // an earlier token of the group that holds no slot any more
             scale2, lane, wave, nw, e_lds, mx);
         V16 vX[Gx::UV];
-        pv_first_tile<T, D, G>(vX, Vb, k, lane, wave);
+        pv_first_tile<T, D, G, true>(vX, Vb, k, lane, wave);
         __syncthreads();  // the logits are in LDS
         if (tid < i && vict[tid] < k) {  // cached rows that earlier tokens of the group removed
 #pragma unroll
@@ -356,8 +478,8 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
           }
         }
         float accx[G][Gx::VEC];
-        pv_pass<T, D, G>(Vb, k, n_own, own_here, [&](int r) { return vnew0 + (size_t)r * p.kv_stride; }, e_lds, G, 0,
-                         lane, wave, nw, vX, accx);
+        pv_pass<T, D, G, true>(Vb, k, n_own, own_here, [&](int r) { return vnew0 + (size_t)r * p.kv_stride; }, e_lds, G, 0,
+                               lane, wave, nw, vX, accx);
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
@@ -467,13 +589,14 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
     T* outi = reinterpret_cast<T*>(p.out) + tok_q + (size_t)i * p.q_stride + (size_t)unit * H * D;
     for (int x = tid; x < H * D && !from_scratch; x += nt) {
       const int hq = x / D, dd = x - hq * D;
-      float a = ublk[((size_t)hq * C + i) * D + dd];
+      const float* up = ublk + ((size_t)hq * C + i) * D + dd;
+      float a = shared ? ld_agent(up) : *up;
       for (int e = 0; e < i; ++e) {
         const int cand = vict[e];
         const T* vrow = (cand < k) ? reinterpret_cast<const T*>(p.V) + ((size_t)(pair0 + hq / G) * k + cand) * D
                                    : reinterpret_cast<const T*>(p.v_new) + tok_kv + (size_t)(cand - k) * p.kv_stride +
                                          (size_t)(pair0 + hq / G) * D;
-        a = fmaf(-wev[e * H + hq], elem_f32<T>(vrow, dd), a);
+        a = fmaf(-wev[e * H + hq], (shared && cand < k) ? elem_f32_agent<T>(vrow, dd) : elem_f32<T>(vrow, dd), a);
       }
       E::store(outi + x, a / zcs[hq]);
     }
@@ -481,25 +604,39 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
   }
 
   // ================= commit: the tokens that still hold a slot =================
+  if (shared) {
+    // the resolving part only says where the tokens ended up; every part stores the rows of its own KV
+    // heads when it comes back to the unit (top of the loop)
+    if (tid < C) st_agent_i(p.gpos + (size_t)unit * 8 + tid, pos[tid]);
+    if (tid == 0) {
+      for (int i = 0; i < C; ++i)
+        if (pos[i] >= 0) st_agent_i(p.slot_token + (size_t)unit * k + pos[i], p.t + ch * C + i);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);  // (the counter's reset, the slots and the map have landed ...)
+    __syncthreads();
+    if (tid == 0) st_agent_u64(p.pstate + unit, (unsigned long long)(uint32_t)(ch + 1));  // ... before the group counts as done
+    continue;
+  }
   for (int i = 0; i < C; ++i) {
     const int ps = pos[i];
     if (ps < 0) continue;  // block-uniform
-    const T* kn = reinterpret_cast<const T*>(p.k_new) + tok_kv + (size_t)i * p.kv_stride + (size_t)pair0 * D;
-    const T* vn = reinterpret_cast<const T*>(p.v_new) + tok_kv + (size_t)i * p.kv_stride + (size_t)pair0 * D;
-    T* Ku = reinterpret_cast<T*>(p.K) + ((size_t)pair0 * k + ps) * D;
-    T* Vu = reinterpret_cast<T*>(p.V) + ((size_t)pair0 * k + ps) * D;
-    for (int x = tid; x < p.H_kv * ROW16; x += nt) {
+    const T* kn = reinterpret_cast<const T*>(p.k_new) + tok_kv + (size_t)i * p.kv_stride + (size_t)(pair0 + kv0) * D;
+    const T* vn = reinterpret_cast<const T*>(p.v_new) + tok_kv + (size_t)i * p.kv_stride + (size_t)(pair0 + kv0) * D;
+    T* Ku = reinterpret_cast<T*>(p.K) + ((size_t)(pair0 + kv0) * k + ps) * D;
+    T* Vu = reinterpret_cast<T*>(p.V) + ((size_t)(pair0 + kv0) * k + ps) * D;
+    for (int x = tid; x < HP * ROW16; x += nt) {  // (this workgroup's KV heads: all of them without parts)
       const int h = x / ROW16, c16 = x - h * ROW16;
       reinterpret_cast<V16*>(Ku + (size_t)h * k * D)[c16] = reinterpret_cast<const V16*>(kn)[x];
       reinterpret_cast<V16*>(Vu + (size_t)h * k * D)[c16] = reinterpret_cast<const V16*>(vn)[x];
     }
-    if (tid == 0) p.slot_token[(size_t)unit * k + ps] = p.t + ch * C + i;
+    if (tid == 0 && part == 0) p.slot_token[(size_t)unit * k + ps] = p.t + ch * C + i;
   }
   // the rows must have landed before other waves of this block read them in the unit's next group
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
-  }  // units
+  }  // units (items)
   }  // groups
 }
 
@@ -523,6 +660,34 @@ hipError_t launch_gc(int G, int C, const PrefillParams& p, const LaunchPlan& lp,
   return hipErrorInvalidValue;
 }
 
+template <typename T, int D>
+int resident_gc(int G, int C, int block, int lds) {
+  int per_cu = -1;
+#define TOVA_PREFILL_CASE(g, c)                                                                                   \
+  if (G == g && C == c) {                                                                                         \
+    if (ensure_dynamic_lds<&tova_prefill_kernel<T, D, g, c>>(lds) != hipSuccess) return 0;                        \
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tova_prefill_kernel<T, D, g, c>, block, (size_t)lds) != hipSuccess) \
+      return 0;                                                                                                   \
+  }
+  TOVA_PREFILL_CASE(1, 4)
+  TOVA_PREFILL_CASE(1, 8)
+  TOVA_PREFILL_CASE(2, 2)
+  TOVA_PREFILL_CASE(2, 4)
+  TOVA_PREFILL_CASE(4, 2)
+#undef TOVA_PREFILL_CASE
+  if (per_cu < 0) return 0;
+  return per_cu * device_cus();
+}
+template <typename T>
+int resident_dgc(int D, int G, int C, int block, int lds) {
+  switch (D) {
+    case 32: return resident_gc<T, 32>(G, C, block, lds);
+    case 64: return resident_gc<T, 64>(G, C, block, lds);
+    case 128: return resident_gc<T, 128>(G, C, block, lds);
+    default: return 0;
+  }
+}
+
 template <typename T>
 hipError_t launch_dgc(int D, int G, int C, const PrefillParams& p, const LaunchPlan& lp, hipStream_t s) {
   switch (D) {
@@ -534,6 +699,10 @@ hipError_t launch_dgc(int D, int G, int C, const PrefillParams& p, const LaunchP
 }
 
 }  // namespace
+
+int prefill_resident_blocks(int dtype_is_bf16, int D, int G, int C, int block, int lds_bytes) {
+  return dtype_is_bf16 ? resident_dgc<bf16_t>(D, G, C, block, lds_bytes) : resident_dgc<float>(D, G, C, block, lds_bytes);
+}
 
 hipError_t launch_prefill(int dtype_is_bf16, int D, int G, int C, const PrefillParams& p, const LaunchPlan& lp,
                           hipStream_t stream) {

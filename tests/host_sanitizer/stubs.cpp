@@ -40,7 +40,10 @@ hipError_t launch_step(int, int D, int G, const StepParams& p, const LaunchPlan&
   return hipSuccess;
 }
 hipError_t launch_prefill(int, int, int G, int C, const PrefillParams& p, const LaunchPlan& lp, hipStream_t) {
-  require(C >= 2 && G * C <= 8 && p.n_chunks >= 1 && lp.grid >= 1 && lp.grid <= p.units, "prompt groups");
+  require(C >= 2 && G * C <= 8 && p.n_chunks >= 1 && lp.grid >= 1, "prompt groups");
+  require(p.parts >= 1 && p.H_kv % p.parts == 0, "parts divide the KV heads");
+  require(p.parts == 1 ? lp.grid <= p.units : lp.grid == p.units * p.parts, "grid of the prompt kernel");
+  require(p.parts == 1 || (p.tpart && p.stat && p.gpos && p.cnt_unit && p.pstate && p.error_flag), "hand-over areas");
   require(lp.lds_bytes <= 160 * 1024 && p.uscr != nullptr, "prompt LDS / scratch");
   ++g_launches;
   return hipSuccess;
@@ -51,6 +54,7 @@ hipError_t launch_repos(int, int, int, const ReposParams& p, const LaunchPlan& l
   return hipSuccess;
 }
 int repos_resident_blocks(int, int, int, int, int) { return 512; }
+int prefill_resident_blocks(int, int, int, int, int, int) { return 768; }
 hipError_t launch_policy(const PolicyParams& p, hipStream_t) {
   require(p.units >= 1 && p.w && p.row_bytes % 16 == 0, "policy step");
   ++g_launches;

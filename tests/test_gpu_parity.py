@@ -489,7 +489,8 @@ def test_prefill_groups_from_scratch_route(dtype, d, H, H_kv, k, T, L, B, call, 
         assert all(s["mismatches"] == 0 for s in stats)
 
 
-def test_prefill_guard_when_a_removed_row_held_a_heads_weight():
+@pytest.mark.parametrize("with_parts", [False, True])
+def test_prefill_guard_when_a_removed_row_held_a_heads_weight(with_parts):
     """The case the corrections cannot handle, constructed: a cached row c* is the lowest on the head
     mean for the first token of a group (every head of that query points away from its key), so it is
     removed inside the group -- and for a later token of the same group one head points straight at
@@ -516,12 +517,12 @@ def test_prefill_guard_when_a_removed_row_held_a_heads_weight():
     assert cache.layout.unit_workgroups == 0             # (few units: force the form that groups prompt tokens)
     cache.destroy()
     import os
-    os.environ["TOVA_UNIT_MODE"] = "1"
-    try:
+    os.environ["TOVA_PREFILL_PARTS" if with_parts else "TOVA_UNIT_MODE"] = "16" if with_parts else "1"
+    try:       # with parts: 2 units, the 4 KV heads of each dealt to 4 workgroups; else a workgroup per unit
         cache = TovaCache(L, B, k, H, H_kv, d, dtype="f32", n_splits=1)
     finally:
-        del os.environ["TOVA_UNIT_MODE"]
-    assert cache.layout.prefill_group == 8
+        os.environ.pop("TOVA_UNIT_MODE", None); os.environ.pop("TOVA_PREFILL_PARTS", None)
+    assert cache.layout.prefill_group == 8 and cache.layout.unit_workgroups == (0 if with_parts else 1)
     qd, kd, vd = q.cuda(), kk.cuda(), vv.cuda()
     out = torch.empty_like(qd)
     ev = torch.empty(T, L, B, dtype=torch.int32, device="cuda:0")
@@ -539,6 +540,107 @@ def test_prefill_guard_when_a_removed_row_held_a_heads_weight():
             assert err <= 1e-5, f"token {t} sequence {b}: output rel err {err:.2e}"
             worst = max(worst, err)
     print(f"[parity] prompt guard: max rel err {worst:.2e}", flush=True)
+    cache.destroy()
+
+
+PARTS_SWEEP = [
+    # dtype, d, H, H_kv, k, T, L, B, tokens per call, expected group, most parts allowed (None: the default)
+    ("f32", 32, 4, 4, 70, 190, 1, 2, 190, 8, None),
+    ("f32", 64, 8, 4, 100, 260, 1, 2, 37, 4, None),          # calls that are no multiple of the group
+    ("f32", 128, 8, 2, 64, 200, 1, 2, 64, 2, None),          # 4 heads per KV head, 2 parts
+    ("bf16", 128, 32, 8, 300, 520, 1, 3, 128, 2, None),
+    ("bf16", 128, 32, 32, 512, 700, 2, 1, 94, 8, None),      # the paper's scoring shape per layer (k = 512), 16 parts of 2 KV heads
+    ("bf16", 128, 8, 8, 1025, 1300, 1, 2, 256, 8, 4),
+    ("bf16", 64, 8, 4, 130, 300, 2, 2, 33, 4, 2),
+    ("bf16", 32, 8, 2, 77, 200, 1, 5, 200, 2, None),
+]
+
+
+@pytest.mark.parametrize("dtype,d,H,H_kv,k,T,L,B,call,group,max_parts", PARTS_SWEEP)
+@pytest.mark.parametrize("exact", ["0", "1"])
+def test_prefill_few_units_parts(dtype, d, H, H_kv, k, T, L, B, call, group, max_parts, exact, monkeypatch):
+    """Prompts on few units (the paper scores one text at a time: its 32 layers are 32 units): the KV heads
+    of a unit are dealt to several workgroups, which hand their partial score rows, statistics and PV
+    sums to the one that resolves the group.  Same bars against the oracle's sequential steps; with
+    exact=1 every grouped token takes the from-scratch route (cached rows read past the caches)."""
+    from paper_2401_06104_amd import TovaCache
+    # (given explicitly, the limit also lifts the size condition: parts are meant for steps that stream
+    # hundreds of MB; here they run on small shapes)
+    monkeypatch.setenv("TOVA_PREFILL_PARTS", str(16 if max_parts is None else max_parts))
+    monkeypatch.setenv("TOVA_PREFILL_EXACT", exact)
+    if exact == "1" and k > 600:
+        pytest.skip("the forced from-scratch route is covered by the smaller shapes")
+    spec = StreamSpec(f"parts_{dtype}_d{d}_h{H}_{H_kv}_k{k}", L=L, B=B, H=H, H_kv=H_kv, d=d, dtype=dtype,
+                      k=k, T=T, sink="first", n_sinks=2)
+    units = [(l, b) for l in range(L) for b in range(B)][:4]
+    res = parity.run_gpu(spec, 1700 + k, units, chunk_steps=call, use_prefill=True)
+    assert res["unit_workgroups"] == 0 and res["prefill_group"] == group
+    parity.check_global_invariants(spec, res)
+    stats = parity.check_units(spec, 1700 + k, units, res, workers=4)
+    for s_ in stats:
+        print(f"[parity]   {s_}", flush=True)
+    if dtype == "f32":
+        assert all(s_["mismatches"] == 0 for s_ in stats)
+
+
+def test_prefill_few_units_random_shapes_match_decode_steps(monkeypatch):
+    """Sixty random small shapes with few units, the prompt cut into calls at random places: the prompt
+    kernel with the KV heads of a unit dealt to parts must give tova_decode_steps' victims and final
+    state, outputs within the tolerance (GPU against GPU: a regression net, no parity credit)."""
+    import random
+    from paper_2401_06104_amd import TovaCache
+    monkeypatch.setenv("TOVA_PREFILL_PARTS", "16")
+    rng = random.Random(15)
+    grouped = 0
+    for case in range(60):
+        d = rng.choice([32, 64, 128]); G = rng.choice([1, 2, 4]); H_kv = rng.choice([2, 3, 4, 6, 8]); H = G * H_kv
+        k = rng.choice([16, 21, 33, 40, 64, 77, 130]); T = k + rng.randint(5, 90)
+        L = rng.choice([1, 2]); B = rng.choice([1, 2, 3]); dtype = rng.choice(["f32", "bf16"])
+        pinned = rng.choice([0, 0, 0, 1, 2])
+        dt = torch.float32 if dtype == "f32" else torch.bfloat16
+        g = torch.Generator().manual_seed(case * 7 + 2)
+        q = torch.randn(T, L, B, H, d, generator=g).to(dt).cuda()
+        kk = torch.randn(T, L, B, H_kv, d, generator=g).to(dt).cuda()
+        vv = torch.randn(T, L, B, H_kv, d, generator=g).to(dt).cuda()
+        runs = []
+        for how in ("steps", "prefill"):
+            cache = TovaCache(L, B, k, H, H_kv, d, dtype=dtype, n_pinned=pinned)
+            out = torch.empty_like(q)
+            ev = torch.empty(T, L, B, dtype=torch.int32, device="cuda")
+            if how == "steps":
+                cache.decode_steps(q, kk, vv, out, ev)
+            else:
+                cuts = sorted(set([0, T] + [rng.randint(1, T - 1) for _ in range(rng.randint(0, 3))]))
+                for a, b in zip(cuts[:-1], cuts[1:]):
+                    cache.prefill(q[a:b], kk[a:b], vv[a:b], out[a:b], ev[a:b])
+                grouped += int(cache.layout.prefill_group > 1)
+            torch.cuda.synchronize()
+            assert int(cache.error_flag.item()) == 0
+            runs.append((out.float().cpu(), ev.cpu(), cache.slot_token.cpu().clone(), cache.K.cpu().clone(), cache.V.cpu().clone()))
+            cache.destroy()
+        what = f"case {case}: d={d} G={G} H_kv={H_kv} k={k} T={T} L={L} B={B} {dtype} pinned={pinned}"
+        assert torch.equal(runs[0][1], runs[1][1]), "victims differ, " + what
+        assert torch.equal(runs[0][2], runs[1][2]) and torch.equal(runs[0][3], runs[1][3]) and torch.equal(runs[0][4], runs[1][4]), \
+            "final state differs, " + what
+        err = ((runs[0][0] - runs[1][0]).abs().amax(dim=-1) / runs[0][0].abs().amax(dim=-1).clamp_min(1e-30)).max().item()
+        assert err <= 2 * parity.OUT_TOL[dtype], f"outputs differ by {err:.2e}, " + what
+    assert grouped >= 30
+
+
+def test_prefill_few_units_wait_runs_out_cleanly(monkeypatch):
+    """Failure handling, forced from the host: no polls allowed, so the parts of a unit cannot get the
+    previous group's result; all leave, the kernel ends, the error flag is set."""
+    from paper_2401_06104_amd import TovaCache
+    from workloads import Stream
+    monkeypatch.setenv("TOVA_MULTI_STEP_SPIN", "0")
+    monkeypatch.setenv("TOVA_PREFILL_PARTS", "16")
+    spec = StreamSpec("parts_timeout", L=2, B=2, H=8, H_kv=4, d=64, dtype="bf16", k=64, T=64 + 48)
+    cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype)
+    assert cache.layout.prefill_group == 4 and cache.layout.unit_workgroups == 0
+    c = Stream(spec, 14, device="cuda:0").chunk(0, spec.T)
+    out = torch.empty_like(c["q"])
+    cache.prefill(c["q"], c["k"], c["v"], out, None)
+    assert cache.status() == 1
     cache.destroy()
 
 

@@ -117,11 +117,14 @@ def test_launch_plan(c, expect_S):
     (cfg(L=32, B=64, k=1024, H=32, Hkv=8, d=128, dt=TOVA_BF16), 1, 2),    # 4 heads per KV head: 2 tokens = 8 combinations
     (cfg(L=8, B=64, k=1024, H=32, Hkv=32, d=128, dt=TOVA_BF16), 1, 8),
     (cfg(L=32, B=16, k=4096, H=32, Hkv=4, d=128, dt=TOVA_BF16), 1, 0),    # 8 heads per KV head: no room for a second token
-    (cfg(B=64, k=1024, H=32, Hkv=8, d=128, dt=TOVA_BF16), 0, 0),          # 64 units: the hand-off form, token by token
+    (cfg(B=64, k=1024, H=32, Hkv=8, d=128, dt=TOVA_BF16), 0, 0),          # 64 units, 268 MB per step: token by token
+    (cfg(B=64, k=1024, H=8, Hkv=1, d=128, dt=TOVA_BF16), 0, 0),           # 8 heads per KV head: no room for a second token
     (cfg(L=32, B=4, k=512, H=32, Hkv=32, d=128, dt=TOVA_BF16), 0, 8),     # 128 units, no grouping of heads: prompts are grouped all the same
     (cfg(L=32, B=2, k=1024, H=32, Hkv=32, d=128, dt=TOVA_BF16), 0, 8),    # 64 units at k >= 1024 likewise
-    (cfg(L=32, B=1, k=512, H=32, Hkv=32, d=128, dt=TOVA_BF16), 0, 0),     # the paper's batch-1 scoring (32 units): token by token
-    (cfg(L=2, B=100, k=1024, H=32, Hkv=8, d=128, dt=TOVA_BF16), 0, 0),    # grouped heads below 256 units: token by token
+    (cfg(L=32, B=1, k=512, H=32, Hkv=32, d=128, dt=TOVA_BF16), 0, 0),     # the paper's batch-1 scoring (32 units) at k = 512: token by token
+    (cfg(L=32, B=1, k=2048, H=32, Hkv=32, d=128, dt=TOVA_BF16), 0, 8),    # ... at k = 2048: grouped, the KV heads of a unit dealt to several workgroups
+    (cfg(L=32, B=1, k=4096, H=32, Hkv=32, d=128, dt=TOVA_BF16), 0, 4),
+    (cfg(L=2, B=100, k=1024, H=32, Hkv=8, d=128, dt=TOVA_BF16), 0, 2),    # grouped heads, 200 units (840 MB per step): groups of 2 with parts
 ])
 def test_prompt_groups_in_the_plan(c, unit, group):
     lay = tova_cache_layout(c)
