@@ -293,7 +293,8 @@ def test_unit_workgroups_wide_groups_large_capacity(monkeypatch):
 def test_unit_workgroups_random_shapes_match_the_hand_off_form(monkeypatch):
     """Sixty random small shapes through both forms (automatic split count in the hand-off form):
     the victims and the final state must be identical and the outputs equal to rounding -- bit for
-    bit when the hand-off form also runs one chunk per KV head (same arithmetic, same head order)."""
+    bit when the hand-off form also runs one chunk per KV head with fewer than 8 query heads per KV head
+    (same arithmetic, same head order, same row order in the PV sums)."""
     import random
     from paper_2401_06104_amd import TovaCache
     rng = random.Random(9)
@@ -325,7 +326,7 @@ def test_unit_workgroups_random_shapes_match_the_hand_off_form(monkeypatch):
         what = f"case {case}: d={d} G={G} H_kv={H_kv} k={k} T={T} L={L} B={B} {dtype} splits={splits} pinned={pinned}"
         assert torch.equal(runs[0][1], runs[1][1]), "victims differ, " + what
         assert torch.equal(runs[0][2], runs[1][2]) and torch.equal(runs[0][3], runs[1][3]), "final state differs, " + what
-        if runs[1][4]:
+        if runs[1][4] and G < 8:     # (with 8 heads per KV head the hand-off form's V tiles are deeper: another summation order)
             assert torch.equal(runs[0][0], runs[1][0]), "outputs differ, " + what
         else:
             a, b = runs[0][0].float(), runs[1][0].float()
