@@ -621,6 +621,82 @@ __device__ __forceinline__ void pv_pass(const T* Vb, int nrows, int n_own, bool 
   }
 }
 
+// PV pass on the matrix cores (bf16, d = 128, 8 heads per KV head).  With V stored row by row the
+// contraction index (the slot) is not contiguous in memory, but it can be made contiguous in a
+// lane's registers without any cross-lane traffic: lane l takes the SAME 16-byte column chunk
+// (l % 16) of eight DIFFERENT rows (tile row (l / 16) * 8 + i for load i), so a wave-level load
+// still covers four whole contiguous rows and the eight loads of a tile cover 32 adjacent rows.
+// Column c of the chunk, taken from the eight loaded registers with four byte permutes, is then
+// the B operand (column l % 16, contraction elements (l / 16) * 8 + i) of
+// v_mfma_f32_16x16x32_bf16 number c of the tile.  The A operand holds the weights: row m < 8 the
+// upper 16 bits of head m's exp value as a bf16, row m + 8 the bf16 of what that leaves (the
+// remainder is exact in fp32), so the two halves of the result add up to a product with a 16-bit
+// weight mantissa -- the rows that would be zero padding with 8 heads carry the correction instead.
+// Result register r of acc[c] in lane l: head (l / 16) * 4 + r (lanes >= 32: its correction), column
+// 8 * (l % 16) + c.  The vector version of this pass needs 8 * NH multiply-adds per 16 bytes and
+// lane and is bound by them; this one needs four permutes and one matrix instruction.
+template <typename T, int D, int NH>
+struct PvMfma {
+  static constexpr bool OK = Geo<T, D, NH>::MFMA_K && D == 128 && NH == 8;
+  static constexpr int ROWS = 32;  // rows of a wave's tile
+};
+template <typename T, int D, bool COH = false>
+__device__ __forceinline__ void pv_mfma_load(V16 (&vt)[8], const T* Vb, int base, int nrows, int lane) {
+  const int n16 = lane & 15, kg = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int j = base + kg * 8 + i;
+    vt[i] = V16{{0u, 0u, 0u, 0u}};
+    if (j < nrows) vt[i] = ld_v16<COH>(Vb + (size_t)j * D + n16 * 8);
+  }
+}
+template <typename T, int D, int NH, bool COH = false>
+__device__ __forceinline__ void pv_pass_mfma(const T* Vb, int nrows, const float* e_lds, int NHT, int col0,
+                                             int lane, int wave, int nw, V16 (&vA)[8], f32x4_t (&acc)[8]) {
+  static_assert(PvMfma<T, D, NH>::OK, "shape");
+  const int kg = lane >> 4, h = lane & 7;
+  const bool corr = (lane & 8) != 0;  // this lane's A row is a correction row
+  constexpr int TILE = PvMfma<T, D, NH>::ROWS;
+  const int stride = nw * TILE;
+  auto compute = [&](const V16(&vt)[8], int base) {
+    uint32_t w[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int j = base + kg * 8 + i;
+      const float e = (j < nrows) ? e_lds[j * NHT + col0 + h] : 0.f;
+      const uint32_t hi = __float_as_uint(e) & 0xffff0000u;
+      w[i] = corr ? __float_as_uint(e - __uint_as_float(hi)) : hi;
+    }
+    V16 a;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) a.w[r] = (w[2 * r] >> 16) | (w[2 * r + 1] & 0xffff0000u);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      V16 b;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const uint32_t x = vt[2 * r].w[c >> 1], y = vt[2 * r + 1].w[c >> 1];
+        b.w[r] = (c & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
+      }
+      acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), acc[c], 0, 0, 0);
+    }
+  };
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  V16 vB[8];
+  int base = wave * TILE;
+  while (base < nrows) {
+    pv_mfma_load<T, D, COH>(vB, Vb, base + stride, nrows, lane);
+    compute(vA, base);
+    base += stride;
+    if (base >= nrows) break;
+    pv_mfma_load<T, D, COH>(vA, Vb, base + stride, nrows, lane);
+    compute(vB, base);
+    base += stride;
+  }
+}
+
 }  // namespace
 }  // namespace tova
 #endif  // TOVA_DEVICE_H
