@@ -697,6 +697,51 @@ __device__ __forceinline__ void pv_pass_mfma(const T* Vb, int nrows, const float
   }
 }
 
+// Completes pv_pass_mfma (called by all threads of the block: it contains the barrier after which the
+// reduction area may reuse the memory of the exp values).  Lanes l and l ^ 32 hold the two halves of the
+// same sums: one row swap between the registers of columns c and c + 4 and one addition complete both,
+// columns 0 .. 3 in the lower 32 lanes and 4 .. 7 in the upper ones.  The own candidates' rows are added
+// on the vector ALUs, in fp32, by the wave that has them; then the wave's sums go to
+// red[(wave * 8 + head) * D + column].
+template <typename T, int D, int NH, typename OwnPtr>
+__device__ __forceinline__ void pv_mfma_finish(f32x4_t (&pacc)[8], int nrows, int n_own, bool own_here, OwnPtr&& ownp,
+                                               const float* e_lds, int NHT, int col0, int lane, int wave, float* red) {
+  static_assert(PvMfma<T, D, NH>::OK, "shape");
+  // (the row swaps are inline assembly: the compiler does not see that they read the results of matrix
+  // instructions, so the wait states between the two are spelled out here, once, on all accumulators)
+  asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3"
+               : "+v"(pacc[0]), "+v"(pacc[1]), "+v"(pacc[2]), "+v"(pacc[3]), "+v"(pacc[4]), "+v"(pacc[5]),
+                 "+v"(pacc[6]), "+v"(pacc[7]));
+  float tot[4][4];  // [c % 4][r]: head ((lane >> 4) & 1) * 4 + r, column 8 * (lane & 15) + (lane >> 5) * 4 + c % 4
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float xf = pacc[c][r], yf = pacc[c + 4][r];  // (copies: a bit cast straight from a vector element reads element 0)
+      unsigned x = __float_as_uint(xf), y = __float_as_uint(yf);
+      swap_rows32(x, y);
+      tot[c][r] = __uint_as_float(x) + __uint_as_float(y);
+    }
+  const int hb = ((lane >> 4) & 1) * 4, cb = (lane & 15) * 8 + (lane >> 5) * 4;
+  if (own_here) {
+    for (int o = 0; o < n_own; ++o) {
+      const uint2 vn = *reinterpret_cast<const uint2*>(ownp(o) + cb);
+      const float vf[4] = {__uint_as_float(vn.x << 16), __uint_as_float(vn.x & 0xffff0000u),
+                           __uint_as_float(vn.y << 16), __uint_as_float(vn.y & 0xffff0000u)};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float w = e_lds[(nrows + o) * NHT + col0 + hb + r];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) tot[c][r] = fmaf(w, vf[c], tot[c][r]);
+      }
+    }
+  }
+  __syncthreads();  // everyone is done reading e_lds; the reduction area may reuse it
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+    *reinterpret_cast<float4*>(red + (wave * NH + hb + r) * D + cb) = float4{tot[0][r], tot[1][r], tot[2][r], tot[3][r]};
+}
+
 }  // namespace
 }  // namespace tova
 #endif  // TOVA_DEVICE_H

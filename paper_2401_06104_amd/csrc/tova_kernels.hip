@@ -277,46 +277,10 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : 4) voi
   // ---------------- phase 3: PV ----------------
   float* red = big + p.red_off;  // [nw][G*D]; behind the exp values when they are still needed (S > 1)
   if constexpr (PVM) {
-    // Matrix cores (see pv_pass_mfma).  Lanes l and l ^ 32 hold the two halves of the same sums: one row
-    // swap between the registers of columns c and c + 4 and one addition complete both, columns 0 .. 3 in
-    // the lower 32 lanes and 4 .. 7 in the upper ones.  The incoming token's row is added on the vector
-    // ALUs, in fp32, by the wave that has it.
+    // Matrix cores (see pv_pass_mfma; the incoming token's row is added on the vector ALUs).
     f32x4_t pacc[8];
     pv_pass_mfma<T, D, G>(Vb, ncached, e_lds, G, 0, lane, wave, nw, vA, pacc);
-    // (the row swaps are inline assembly: the compiler does not see that they read the results of matrix
-    // instructions, so the wait states between the two are spelled out here, once, on all accumulators)
-    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3"
-                 : "+v"(pacc[0]), "+v"(pacc[1]), "+v"(pacc[2]), "+v"(pacc[3]), "+v"(pacc[4]), "+v"(pacc[5]),
-                   "+v"(pacc[6]), "+v"(pacc[7]));
-    float tot[4][4];  // [c % 4][r]: head ((lane >> 4) & 1) * 4 + r, column 8 * (lane & 15) + (lane >> 5) * 4 + c % 4
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float xf = pacc[c][r], yf = pacc[c + 4][r];  // (copies: a bit cast straight from a vector element reads element 0)
-        unsigned x = __float_as_uint(xf), y = __float_as_uint(yf);
-        swap_rows32(x, y);
-        tot[c][r] = __builtin_bit_cast(float, x) + __builtin_bit_cast(float, y);
-      }
-    const int hb = ((lane >> 4) & 1) * 4, cb = (lane & 15) * 8 + (lane >> 5) * 4;
-    if (new_here) {
-      float vf[4];
-      const uint2 vn = *reinterpret_cast<const uint2*>(vnew + cb);
-      vf[0] = __uint_as_float(vn.x << 16);
-      vf[1] = __uint_as_float(vn.x & 0xffff0000u);
-      vf[2] = __uint_as_float(vn.y << 16);
-      vf[3] = __uint_as_float(vn.y & 0xffff0000u);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float w = e_lds[ncached * G + hb + r];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) tot[c][r] = fmaf(w, vf[c], tot[c][r]);
-      }
-    }
-    __syncthreads();  // everyone is done reading e_lds; the reduction area reuses it
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-      *reinterpret_cast<float4*>(red + (wave * G + hb + r) * D + cb) = float4{tot[0][r], tot[1][r], tot[2][r], tot[3][r]};
+    pv_mfma_finish<T, D, G>(pacc, ncached, 1, new_here, [&](int) { return vnew; }, e_lds, G, 0, lane, wave, red);
   } else {
   float acc[G][VEC];
   pv_pass<T, D, G>(Vb, ncached, 1, new_here, [&](int) { return vnew; }, e_lds, G, 0, lane, wave, nw, vA, acc);

@@ -210,8 +210,12 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
   // the first V tile is requested before the softmax barriers
   const int lv = lane % LV;
   const int rv = lane / LV;
-  V16 vA[UV];
-  pv_first_tile<T, D, GE>(vA, Vb, n, lane, wave);
+  constexpr bool PVM = PvMfma<T, D, GE>::OK;  // bf16, d = 128, 8 combinations: PV on the matrix cores
+  V16 vA[PVM ? 8 : UV];
+  if constexpr (PVM)
+    pv_mfma_load<T, D>(vA, Vb, wave * PvMfma<T, D, GE>::ROWS, n, lane);
+  else
+    pv_first_tile<T, D, GE>(vA, Vb, n, lane, wave);
 
   // ---- maxima, exp values, sums over all causally allowed candidates
   block_reduce<GE, true>(m, small, lane, wave, nw);
@@ -252,20 +256,27 @@ __global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel
   }
 
   // ---- unmasked PV sums: U_(i,g) = sum over allowed candidates of w V
-  float acc[GE][VEC];
-  pv_pass<T, D, GE>(Vb, n, C, own_here, [&](int r) { return vnew0 + (size_t)r * p.kv_stride; }, e_lds, GE, 0, lane,
-                    wave, nw, vA, acc);
   float* red = big;  // [nw][GE * D]
-#pragma unroll
-  for (int ge = 0; ge < GE; ++ge)
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) acc[ge][v] = column_sum<LV>(acc[ge][v]);
-  __syncthreads();  // everyone is done reading the exp values; the reduction area reuses them
-  if (rv == 0) {
+  if constexpr (PVM) {
+    f32x4_t pacc[8];
+    pv_pass_mfma<T, D, GE>(Vb, n, e_lds, GE, 0, lane, wave, nw, vA, pacc);
+    pv_mfma_finish<T, D, GE>(pacc, n, C, own_here, [&](int r) { return vnew0 + (size_t)r * p.kv_stride; }, e_lds, GE,
+                             0, lane, wave, red);
+  } else {
+    float acc[GE][VEC];
+    pv_pass<T, D, GE>(Vb, n, C, own_here, [&](int r) { return vnew0 + (size_t)r * p.kv_stride; }, e_lds, GE, 0, lane,
+                      wave, nw, vA, acc);
 #pragma unroll
     for (int ge = 0; ge < GE; ++ge)
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) red[(wave * GE + ge) * D + lv * VEC + v] = acc[ge][v];
+      for (int v = 0; v < VEC; ++v) acc[ge][v] = column_sum<LV>(acc[ge][v]);
+    __syncthreads();  // everyone is done reading the exp values; the reduction area reuses them
+    if (rv == 0) {
+#pragma unroll
+      for (int ge = 0; ge < GE; ++ge)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) red[(wave * GE + ge) * D + lv * VEC + v] = acc[ge][v];
+    }
   }
   __syncthreads();
   for (int x = tid; x < GE * D; x += nt) {

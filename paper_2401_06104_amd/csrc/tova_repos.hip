@@ -471,8 +471,12 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
 
   // The first PV tile is requested now, so that the V stream is in flight during the softmax barriers.
   const int lv = lane % LV, rv = lane / LV;
-  V16 vA[UV];
-  pv_first_tile<T, D, G>(vA, Vb, n, lane, wave);
+  constexpr bool PVM = PvMfma<T, D, G>::OK;  // bf16, d = 128, 8 heads per KV head: PV on the matrix cores
+  V16 vA[PVM ? 8 : UV];
+  if constexpr (PVM)
+    pv_mfma_load<T, D>(vA, Vb, wave * PvMfma<T, D, G>::ROWS, n, lane);
+  else
+    pv_first_tile<T, D, G>(vA, Vb, n, lane, wave);
 
   // ---------------- phase 2: softmax statistics, head-summed scores ----------------
   block_reduce<G, true>(m, small, lane, wave, nw);  // (its barrier also makes the logits visible)
@@ -502,19 +506,25 @@ __global__ __launch_bounds__(512, 2) void tova_repos_kernel(const ReposParams p)
   if (P > 1 && kvh == kv0 + HP - 1) victim_and_state();  // (block-uniform; the exp values and the first V tile stay as they are)
 
   // ---------------- phase 3: PV (values carry no positions) ----------------
-  float acc[G][VEC];
-  pv_pass<T, D, G>(Vb, n, 1, new_here, [&](int) { return vnew; }, e_lds, G, 0, lane, wave, nw, vA, acc);
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) acc[g][v] = column_sum<LV>(acc[g][v]);
   float* red = big;  // [nw][G * D]
-  __syncthreads();   // everyone is done reading the exp values; the reduction area reuses them
-  if (rv == 0) {
+  if constexpr (PVM) {
+    f32x4_t pacc[8];
+    pv_pass_mfma<T, D, G>(Vb, n, e_lds, G, 0, lane, wave, nw, vA, pacc);
+    pv_mfma_finish<T, D, G>(pacc, n, 1, new_here, [&](int) { return vnew; }, e_lds, G, 0, lane, wave, red);
+  } else {
+    float acc[G][VEC];
+    pv_pass<T, D, G>(Vb, n, 1, new_here, [&](int) { return vnew; }, e_lds, G, 0, lane, wave, nw, vA, acc);
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) red[(wave * G + g) * D + lv * VEC + v] = acc[g][v];
+      for (int v = 0; v < VEC; ++v) acc[g][v] = column_sum<LV>(acc[g][v]);
+    __syncthreads();   // everyone is done reading the exp values; the reduction area reuses them
+    if (rv == 0) {
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) red[(wave * G + g) * D + lv * VEC + v] = acc[g][v];
+    }
   }
   __syncthreads();
   T* outb = reinterpret_cast<T*>(p.out) + (size_t)it * p.q_stride + ((size_t)unit * p.H + (size_t)kvh * G) * D;
