@@ -635,9 +635,14 @@ __device__ __forceinline__ void pv_pass(const T* Vb, int nrows, int n_own, bool 
 // Result register r of acc[c] in lane l: head (l / 16) * 4 + r (lanes >= 32: its correction), column
 // 8 * (l % 16) + c.  The vector version of this pass needs 8 * NH multiply-adds per 16 bytes and
 // lane and is bound by them; this one needs four permutes and one matrix instruction.
+// (-DTOVA_PV_VECTOR builds the library with this pass on the vector ALUs everywhere: the A/B of the profiles)
 template <typename T, int D, int NH>
 struct PvMfma {
+#ifdef TOVA_PV_VECTOR
+  static constexpr bool OK = false;
+#else
   static constexpr bool OK = Geo<T, D, NH>::MFMA_K && D == 128 && NH == 8;
+#endif
   static constexpr int ROWS = 32;  // rows of a wave's tile
 };
 template <typename T, int D, bool COH = false>
