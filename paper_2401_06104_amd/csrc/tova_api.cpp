@@ -90,6 +90,9 @@ int resolve(const tova_config_t* c, Resolved* r) {
   r->scale = c->softmax_scale > 0.f ? c->softmax_scale : (float)(1.0 / std::sqrt((double)r->D));
 
   const int k = r->k;
+  // groups whose passes run on the matrix cores (8 heads per KV head; 4 at bf16, d = 128): ~160 VGPRs, three
+  // waves per SIMD, so workgroups of 256 threads, up to three to a CU
+  const bool wide = G >= 8 || (r->bf16 && r->D == 128 && G == 4);
   int nt_env = 0;
   if (const char* e = std::getenv("TOVA_BLOCK_THREADS")) {  // tuning aid: 64..512, multiple of 64
     int v = std::atoi(e);
@@ -112,7 +115,7 @@ int resolve(const tova_config_t* c, Resolved* r) {
     if (want && (c->n_splits <= 1 || r->policy != TOVA_POLICY_TOVA)) {
       const long long e_fl = ((long long)(k + 1) * G + 3) / 4 * 4;
       const long long s_fl = ((long long)k + 1 + 3) / 4 * 4;
-      int nt = nt_env ? nt_env : ((k >= 512 && G < 8) ? 512 : 256);
+      int nt = nt_env ? nt_env : ((k >= 512 && !wide) ? 512 : 256);
       long long red_fl = (long long)(nt / 64) * G * r->D;
       long long st = e_fl > red_fl ? e_fl : red_fl;
       if ((kSmallFloats + st + s_fl) * 4 > kMaxLdsBytes && !nt_env) {  // alone on its CU: all the threads a block may have
@@ -222,7 +225,7 @@ int resolve(const tova_config_t* c, Resolved* r) {
     bool ok = false;
     // wide groups need ~150 VGPRs: three waves per SIMD, i.e. three 256-thread blocks per CU but only
     // one 512-thread block
-    const int cand[2] = {nt_env ? nt_env : ((R >= 512 && G < 8) ? 512 : 256), 256};
+    const int cand[2] = {nt_env ? nt_env : ((R >= 512 && !wide) ? 512 : 256), 256};
     for (int ci = 0; ci < 2 && !ok; ++ci) {
       NT = cand[ci];
       const long long red_fl = (long long)(NT / 64) * G * r->D;

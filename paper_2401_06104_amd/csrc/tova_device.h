@@ -330,8 +330,12 @@ struct Geo {
                                                // fewer for wide groups, whose q fragments fill the registers
   // Wide bf16 groups run the logit pass on the matrix cores (see the kernel): q.K^T for 16 rows x
   // up to 16 heads per v_mfma_f32_16x16x32_bf16, which takes the register file and the VALU out
-  // of the picture (8 heads of q fragments alone are 64 VGPRs on the vector path).
-  static constexpr bool MFMA_K = (sizeof(T) == 2) && (G >= 8) && (G <= 16) && (D % 32 == 0);
+  // of the picture (8 heads of q fragments alone are 64 VGPRs on the vector path).  Groups of 4 heads
+  // at d = 128 take it as well: three quarters of the instruction's columns are padding then, but the
+  // instruction is cheap against the ~25 vector instructions per KB that it replaces (bench workload:
+  // 38.3 -> 36.7 us per step together with the PV pass below).
+  static constexpr bool MFMA_K =
+      (sizeof(T) == 2) && (D % 32 == 0) && ((G >= 8 && G <= 16) || (G == 4 && D == 128));
   static constexpr int LV = CH;
   static constexpr int RV = 64 / LV;  // rows per wave pass, PV pass
   static constexpr int UV = (G >= 8) ? 2 : 4;
@@ -641,7 +645,7 @@ struct PvMfma {
 #ifdef TOVA_PV_VECTOR
   static constexpr bool OK = false;
 #else
-  static constexpr bool OK = Geo<T, D, NH>::MFMA_K && D == 128 && NH == 8;
+  static constexpr bool OK = Geo<T, D, NH>::MFMA_K && D == 128 && (NH == 8 || NH == 4);
 #endif
   static constexpr int ROWS = 32;  // rows of a wave's tile
 };
@@ -668,7 +672,7 @@ __device__ __forceinline__ void pv_pass_mfma(const T* Vb, int nrows, const float
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int j = base + kg * 8 + i;
-      const float e = (j < nrows) ? e_lds[j * NHT + col0 + h] : 0.f;
+      const float e = (j < nrows && h < NH) ? e_lds[j * NHT + col0 + h] : 0.f;  // (NH = 4: half the rows stay zero)
       const uint32_t hi = __float_as_uint(e) & 0xffff0000u;
       w[i] = corr ? __float_as_uint(e - __uint_as_float(hi)) : hi;
     }
@@ -728,7 +732,8 @@ __device__ __forceinline__ void pv_mfma_finish(f32x4_t (&pacc)[8], int nrows, in
       tot[c][r] = __uint_as_float(x) + __uint_as_float(y);
     }
   const int hb = ((lane >> 4) & 1) * 4, cb = (lane & 15) * 8 + (lane >> 5) * 4;
-  if (own_here) {
+  const bool has_rows = hb < NH;  // (NH = 4: lanes 16 .. 31 and 48 .. 63 hold padding)
+  if (own_here && has_rows) {
     for (int o = 0; o < n_own; ++o) {
       const uint2 vn = *reinterpret_cast<const uint2*>(ownp(o) + cb);
       const float vf[4] = {__uint_as_float(vn.x << 16), __uint_as_float(vn.x & 0xffff0000u),
@@ -742,9 +747,11 @@ __device__ __forceinline__ void pv_mfma_finish(f32x4_t (&pacc)[8], int nrows, in
     }
   }
   __syncthreads();  // everyone is done reading e_lds; the reduction area may reuse it
+  if (has_rows) {
 #pragma unroll
-  for (int r = 0; r < 4; ++r)
-    *reinterpret_cast<float4*>(red + (wave * NH + hb + r) * D + cb) = float4{tot[0][r], tot[1][r], tot[2][r], tot[3][r]};
+    for (int r = 0; r < 4; ++r)
+      *reinterpret_cast<float4*>(red + (wave * NH + hb + r) * D + cb) = float4{tot[0][r], tot[1][r], tot[2][r], tot[3][r]};
+  }
 }
 
 }  // namespace

@@ -45,7 +45,7 @@ namespace {
 
 
 template <typename T, int D, int G, bool MULTI, bool UNIT = false>
-__global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : 4) void tova_step_kernel(const StepParams p) {
+__global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfma<T, D, G>::OK ? 3 : 4)) void tova_step_kernel(const StepParams p) {
   static_assert(MULTI || !UNIT, "the one-block-per-unit form is built on the multi-step loop");
   using E = Elem<T>;
   using Ge = Geo<T, D, G>;

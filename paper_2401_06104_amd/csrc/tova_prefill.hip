@@ -95,7 +95,7 @@ constexpr float kBoundSlack = 1e-4f;  // rounding of the streamed sums against t
 constexpr float kMinKept = 0.125f;
 
 template <typename T, int D, int G, int C>
-__global__ __launch_bounds__(512, (G * C >= 8) ? 3 : 4) void tova_prefill_kernel(const PrefillParams p) {
+__global__ __launch_bounds__(512, (G * C >= 8 || PvMfma<T, D, G * C>::OK) ? 3 : 4) void tova_prefill_kernel(const PrefillParams p) {
   using E = Elem<T>;
   constexpr int GE = G * C;  // (token, query head) combinations served by one streamed row
   using Ge = Geo<T, D, GE>;
