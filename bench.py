@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # Bytes that left L2 per decode step of the step kernel on this workload, from rocprofv3 --pmc FETCH_SIZE
 # and WRITE_SIZE runs of this script (256 steps per launch), each scaled by what the same counter reads
 # for a 1 GiB copy kernel (summary: profiles/tova_step_kernel_c3_mistral_gqa.txt).  Not measured live.
-PROFILED_TRAFFIC_BYTES_PER_STEP = 274.4e6
+PROFILED_TRAFFIC_BYTES_PER_STEP = 274.0e6
 # ... and of the 32-layer variant (workgroup-per-unit form), profiles/tova_step_kernel_unit_c3_mistral_gqa_x32.txt
 PROFILED_TRAFFIC_BYTES_PER_STEP_X32 = 8648.8e6
 
