@@ -35,7 +35,7 @@ struct Resolved {
   int n_pinned, per_head;
   int policy, h2o_recent;  // TOVA_POLICY_*; H2O: tokens of the recent window, the incoming one included
   size_t acc_off;          // in state_mem: H2O's aggregated weights [units][k] (0 bytes for the other policies)
-  int units, pairs, S, R, kp, NT, grid, lds, st_off, red_off, spin_limit, force_slow, persist_spin, multi_step, multi_grid, spin_env;
+  int units, pairs, S, R, kp, NT, grid, lds, st_off, red_off, spin_limit, force_slow, persist_spin, multi_step, multi_grid, spin_env, svc;
   int unit_mode;  // one workgroup per unit instead of one per (unit, KV head, chunk)
   int pf_C, pf_NT, pf_lds, pf_e_floats, pf_ncp;  // multi-token kernel: tokens per group (0 = not available) and its LDS plan
   int pf_grid;                                   // ... its workgroups (decided in tova_cache_init)
@@ -261,6 +261,16 @@ int resolve(const tova_config_t* c, Resolved* r) {
   // multi-step launches (decided for good in tova_cache_init, which can ask the device)
   r->multi_step = 1;
   if (const char* e = std::getenv("TOVA_MULTI_STEP")) r->multi_step = r->multi_step && (std::atoi(e) != 0);
+  // Service wave (multi-step launches of the hand-off form; see the step kernel): the last wave of a workgroup
+  // serves the hand-off -- score rows, arrival, and for the unit's last arrival the scan and the victim -- beside
+  // the PV pass instead of behind it.  Measured on MI355X (us per step, without -> with): it pays for one chunk
+  // per KV head with the 256-thread workgroups of the matrix-core passes while the unit's score rows are small
+  // enough for one wave to scan (GQA 32/8: k = 512 20.8 -> 19.7, k = 1024 36.9 -> 35.6, k = 2048 91.0 -> 91.0;
+  // 16/4 x 128 sequences 36.6 -> 36.3), and costs where a wave is a larger share of the PV pass's loads in
+  // flight or the rows are many (32 heads MHA x 32 layers, k = 512: 42.3 -> 45.6; one layer: 13.0 -> 16.3;
+  // GQA 32/16 90.5 -> 92.5; split cache, config 5: 44.6 -> 51.0; 8 heads per KV head x 128 units, k = 1024: 36.8 -> 37.8).
+  r->svc = (!r->unit_mode && r->S == 1 && wide && G == 4 && (long long)r->H_kv * (k + 1) <= 12 * 1024) ? 1 : 0;
+  if (const char* e = std::getenv("TOVA_SERVICE_WAVE")) r->svc = (std::atoi(e) != 0);  // tuning aid / test hook
   r->persist_spin = 1 << 22;  // polls of ~0.2 us or more each: seconds, i.e. "something is broken"
   if (const char* e = std::getenv("TOVA_MULTI_STEP_SPIN")) {  // test hook: make the wait run out
     int v = std::atoi(e);
@@ -279,9 +289,9 @@ int resolve(const tova_config_t* c, Resolved* r) {
   r->state_bytes = r->acc_off + (r->policy == TOVA_POLICY_H2O ? round_up((size_t)r->units * k * 4, kAlign) : 0);
 
   size_t off = 0;
-  r->cnt_pair_off = off; off += round_up((size_t)r->pairs * 4, kAlign);
+  r->cnt_pair_off = off; off += round_up((size_t)r->pairs * 2 * 4, kAlign);  // (two copies, by token parity)
   r->cnt_unit_off = off; off += round_up((size_t)r->units * 4, kAlign);
-  r->cnt_pub_off = off; off += round_up((size_t)r->pairs * 4, kAlign);
+  r->cnt_pub_off = off; off += round_up((size_t)r->pairs * 2 * 4, kAlign);
   r->slow_off = off; off += round_up((size_t)r->pairs * S * 4, kAlign);
   r->pstate_off = off; off += round_up((size_t)r->units * 8, kAlign);
   r->cnt_bytes = off;
@@ -416,7 +426,7 @@ int tova_cache_init(tova_cache_t** out, const tova_config_t* cfg, void* kv_mem, 
   // other's results): its grid is capped at what the device can hold, and each block then walks
   // several (unit, KV head) pairs per step.
   c->r.multi_grid = 0;
-  const int cap = tova::resident_blocks(r.bf16, r.D, r.G, r.NT, r.lds, r.unit_mode) / 8 * 8;
+  const int cap = tova::resident_blocks(r.bf16, r.D, r.G, r.NT, r.lds, r.unit_mode ? 1 : (r.svc && r.NT >= 128 ? 2 : 0)) / 8 * 8;
   if (!r.spin_env && r.grid > cap) c->r.spin_limit = 0;
   if (r.unit_mode) {
     // every launch walks the units with a grid that just fills the device (nothing waits for
@@ -609,6 +619,7 @@ int decode_steps_on(tova_cache* c, char* scratch, int32_t n_steps, const void* q
     p.n_iter = m;
     p.persistent = (m > 1);
     p.unit_mode = r.unit_mode;
+    p.svc = (m > 1 && !r.unit_mode && r.svc && r.NT >= 128) ? 1 : 0;
     hipError_t e = hipSuccess;
     if (m > 1 && !r.unit_mode)  // the units' state words start from "no step finished"
       e = tova::launch_fill_i32(reinterpret_cast<int32_t*>(p.pstate), 0, (size_t)r.units * 2, s);

@@ -172,9 +172,9 @@ __device__ __forceinline__ void block_reduce(float (&v)[G], float* red, int lane
 // Block-wide argmin of (value, index) pairs, the lowest index winning ties: every wave reduces its
 // lanes by butterfly shuffles, lane 0 posts the wave's pair, and after one barrier every thread
 // combines the posted pairs in wave order.  `red` holds 2 * kMaxWaves words and must not be in use.
-template <typename V>  // float scores, or int token indices
-__device__ __forceinline__ void block_argmin(V& best, int& bj, float* red, int lane, int wave, int nw) {
-  static_assert(sizeof(V) == 4, "one word per posted value");
+// (the wave's part: afterwards every lane holds the wave's lowest value and its lowest index)
+template <typename V>
+__device__ __forceinline__ void wave_argmin(V& best, int& bj) {
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) {
     const V ob = __shfl_xor(best, o);
@@ -184,6 +184,11 @@ __device__ __forceinline__ void block_argmin(V& best, int& bj, float* red, int l
       bj = oj;
     }
   }
+}
+template <typename V>  // float scores, or int token indices
+__device__ __forceinline__ void block_argmin(V& best, int& bj, float* red, int lane, int wave, int nw) {
+  static_assert(sizeof(V) == 4, "one word per posted value");
+  wave_argmin(best, bj);
   V* bv = reinterpret_cast<V*>(red);
   int* bi = reinterpret_cast<int*>(red + kMaxWaves);
   if (lane == 0) {
@@ -706,22 +711,23 @@ __device__ __forceinline__ void pv_pass_mfma(const T* Vb, int nrows, const float
   }
 }
 
-// Completes pv_pass_mfma (called by all threads of the block: it contains the barrier after which the
-// reduction area may reuse the memory of the exp values).  Lanes l and l ^ 32 hold the two halves of the
-// same sums: one row swap between the registers of columns c and c + 4 and one addition complete both,
-// columns 0 .. 3 in the lower 32 lanes and 4 .. 7 in the upper ones.  The own candidates' rows are added
-// on the vector ALUs, in fp32, by the wave that has them; then the wave's sums go to
-// red[(wave * 8 + head) * D + column].
+// Completes pv_pass_mfma.  Lanes l and l ^ 32 hold the two halves of the same sums: one row swap between
+// the registers of columns c and c + 4 and one addition complete both, columns 0 .. 3 in the lower 32
+// lanes and 4 .. 7 in the upper ones (pv_mfma_fold).  The own candidates' rows are added on the vector
+// ALUs, in fp32, by the wave that has them.  pv_mfma_store then puts the wave's sums at
+// red[(wave * NH + head) * D + column]; between the two the caller places the barrier after which the
+// reduction area may reuse the memory of the exp values.  pv_mfma_finish is the three in a row, for
+// callers all of whose waves take part.
 template <typename T, int D, int NH, typename OwnPtr>
-__device__ __forceinline__ void pv_mfma_finish(f32x4_t (&pacc)[8], int nrows, int n_own, bool own_here, OwnPtr&& ownp,
-                                               const float* e_lds, int NHT, int col0, int lane, int wave, float* red) {
+__device__ __forceinline__ void pv_mfma_fold(f32x4_t (&pacc)[8], float (&tot)[4][4], int nrows, int n_own, bool own_here,
+                                             OwnPtr&& ownp, const float* e_lds, int NHT, int col0, int lane) {
   static_assert(PvMfma<T, D, NH>::OK, "shape");
   // (the row swaps are inline assembly: the compiler does not see that they read the results of matrix
   // instructions, so the wait states between the two are spelled out here, once, on all accumulators)
   asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3"
                : "+v"(pacc[0]), "+v"(pacc[1]), "+v"(pacc[2]), "+v"(pacc[3]), "+v"(pacc[4]), "+v"(pacc[5]),
                  "+v"(pacc[6]), "+v"(pacc[7]));
-  float tot[4][4];  // [c % 4][r]: head ((lane >> 4) & 1) * 4 + r, column 8 * (lane & 15) + (lane >> 5) * 4 + c % 4
+  // tot[c % 4][r]: head ((lane >> 4) & 1) * 4 + r, column 8 * (lane & 15) + (lane >> 5) * 4 + c % 4
 #pragma unroll
   for (int c = 0; c < 4; ++c)
 #pragma unroll
@@ -732,8 +738,7 @@ __device__ __forceinline__ void pv_mfma_finish(f32x4_t (&pacc)[8], int nrows, in
       tot[c][r] = __uint_as_float(x) + __uint_as_float(y);
     }
   const int hb = ((lane >> 4) & 1) * 4, cb = (lane & 15) * 8 + (lane >> 5) * 4;
-  const bool has_rows = hb < NH;  // (NH = 4: lanes 16 .. 31 and 48 .. 63 hold padding)
-  if (own_here && has_rows) {
+  if (own_here && hb < NH) {  // (NH = 4: lanes 16 .. 31 and 48 .. 63 hold padding)
     for (int o = 0; o < n_own; ++o) {
       const uint2 vn = *reinterpret_cast<const uint2*>(ownp(o) + cb);
       const float vf[4] = {__uint_as_float(vn.x << 16), __uint_as_float(vn.x & 0xffff0000u),
@@ -746,12 +751,23 @@ __device__ __forceinline__ void pv_mfma_finish(f32x4_t (&pacc)[8], int nrows, in
       }
     }
   }
-  __syncthreads();  // everyone is done reading e_lds; the reduction area may reuse it
-  if (has_rows) {
+}
+template <typename T, int D, int NH>
+__device__ __forceinline__ void pv_mfma_store(const float (&tot)[4][4], int lane, int wave, float* red) {
+  const int hb = ((lane >> 4) & 1) * 4, cb = (lane & 15) * 8 + (lane >> 5) * 4;
+  if (hb < NH) {
 #pragma unroll
     for (int r = 0; r < 4; ++r)
       *reinterpret_cast<float4*>(red + (wave * NH + hb + r) * D + cb) = float4{tot[0][r], tot[1][r], tot[2][r], tot[3][r]};
   }
+}
+template <typename T, int D, int NH, typename OwnPtr>
+__device__ __forceinline__ void pv_mfma_finish(f32x4_t (&pacc)[8], int nrows, int n_own, bool own_here, OwnPtr&& ownp,
+                                               const float* e_lds, int NHT, int col0, int lane, int wave, float* red) {
+  float tot[4][4];
+  pv_mfma_fold<T, D, NH>(pacc, tot, nrows, n_own, own_here, ownp, e_lds, NHT, col0, lane);
+  __syncthreads();  // everyone is done reading e_lds; the reduction area may reuse it
+  pv_mfma_store<T, D, NH>(tot, lane, wave, red);
 }
 
 }  // namespace

@@ -30,9 +30,9 @@ struct StepParams {
   float* stats;        // [pairs][S][G][2]   chunk-local (max, sum)   (S > 1 only)
   float* accp;         // [2][pairs][S][G][d] chunk-local PV partials, by token parity (S > 1 only)
   int64_t accp_half;   // floats per parity copy
-  int32_t* cnt_pair;   // [pairs] arrival counters, zero between launches
+  int32_t* cnt_pair;   // [2][pairs] arrival counters (by token parity), zero between launches
   int32_t* cnt_unit;   // [units]
-  int32_t* cnt_pub;    // [pairs] chunks that have published their softmax statistics (S > 1 only)
+  int32_t* cnt_pub;    // [2][pairs] chunks that have published their softmax statistics (S > 1 only)
   int32_t* slow_flag;  // [pairs][S] chunk left its exp values in escr for the finisher (S > 1 only)
   int32_t st_off;      // float offset, inside the big LDS area, of the chunk-statistics area (S > 1)
   int32_t red_off;     // float offset of the cross-wave PV reduction area: 0 (it reuses the logit area), or
@@ -59,6 +59,7 @@ struct StepParams {
   int32_t kp;          // k + 1 rounded up to 64: stride of sg / escr
   int32_t t;           // index of the incoming token
   const int32_t* t_dev;  // non-null: read the index from there instead (a step recorded into a graph)
+  int32_t svc;         // multi-step launch, hand-off form: the block's last wave serves the hand-off instead of streaming V
   float scale;
 };
 

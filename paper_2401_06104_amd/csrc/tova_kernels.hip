@@ -44,9 +44,10 @@ namespace tova {
 namespace {
 
 
-template <typename T, int D, int G, bool MULTI, bool UNIT = false>
-__global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfma<T, D, G>::OK ? 3 : 4)) void tova_step_kernel(const StepParams p) {
+template <typename T, int D, int G, bool MULTI, bool UNIT = false, bool SVC = false>
+__global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfma<T, D, G>::OK ? (SVC ? 2 : 3) : ((SVC && G >= 2) ? 3 : 4))) void tova_step_kernel(const StepParams p) {
   static_assert(MULTI || !UNIT, "the one-block-per-unit form is built on the multi-step loop");
+  static_assert(!SVC || (MULTI && !UNIT), "the service wave belongs to multi-step launches of the hand-off form");
   using E = Elem<T>;
   using Ge = Geo<T, D, G>;
   constexpr int VEC = Ge::VEC, LV = Ge::LV;
@@ -65,6 +66,13 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
 
   const int nt = blockDim.x;
   const int nw = nt >> 6;
+  // Service wave (SVC: multi-step launches of the hand-off form, when the host asks for it): the block's last wave
+  // takes no part in the PV pass.  While the others stream V it does everything that stands between the
+  // softmax and the unit's victim -- the chunk's statistics and score rows, the arrival at the unit's counter
+  // and, for the last arrival of the unit, the scan, the argmin and the publication -- so that chain runs
+  // beside the V stream instead of behind it.
+  constexpr bool svc = SVC;
+  const int nws = SVC ? nw - 1 : nw;  // waves of the PV pass
 
   // Per-step launch (MULTI == false): blockIdx -> (pair = (unit, KV head), chunk); one pass.
   // Consecutive block ids go to consecutive XCDs, so the S chunks of one pair are placed on the
@@ -186,7 +194,14 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
   // (vector ALUs, or the matrix cores for wide bf16 groups: see logit_pass; the incoming token is
   // candidate `ncached` -- App. B: the last column -- and is taken by the block's last wave)
   float m[G], Z[G];  // chunk-local softmax statistics (log2 domain)
-  const bool new_here = has_new && (wave == nw - 1);  // wave-uniform
+  const bool new_here = has_new && (wave == nw - 1);    // wave-uniform: the incoming token's logits
+  const bool new_here_v = has_new && (wave == nws - 1);  // ... and its value row in the PV pass
+  // the pair's counters alternate with the token's parity (a block of the unit's next step may already count
+  // on one copy while this step's last block still resets the other)
+  int32_t* const cnt_pair_p = p.cnt_pair + (size_t)(tok & 1) * p.pairs + pair;
+  int32_t* const cnt_pub_p = p.cnt_pub + (size_t)(tok & 1) * p.pairs + pair;
+  const int rst_tid = svc ? (nw - 1) * 64 : 0;  // who resets counters: with a service wave its first lane, whose
+                                                // own wait for its stores precedes the unit's next arrival
   logit_pass<T, D, G>(
       Kb, ncached, 1, new_here, [&](int g) { return qb + g * D; }, [&](int) { return knew; },
       [](int, int) { return false; }, scale2, lane, wave, nw, e_lds, m);
@@ -196,10 +211,12 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
   const int lv = lane % LV;
   const int rv = lane / LV;
   V16 vA[PVM ? 8 : UV];
-  if constexpr (PVM)
-    pv_mfma_load<T, D>(vA, Vb, wave * PvMfma<T, D, G>::ROWS, ncached, lane);
-  else
-    pv_first_tile<T, D, G>(vA, Vb, ncached, lane, wave);
+  if (!SVC || wave < nws) {
+    if constexpr (PVM)
+      pv_mfma_load<T, D>(vA, Vb, wave * PvMfma<T, D, G>::ROWS, ncached, lane);
+    else
+      pv_first_tile<T, D, G>(vA, Vb, ncached, lane, wave);
+  }
 
   // ---------------- phase 2: chunk-local softmax ----------------
   // The barrier inside this reduction is also the one that makes the logits visible.
@@ -240,17 +257,20 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
 #pragma unroll
       for (int g = 0; g < G; ++g) rz[g] = 1.0f / Z[g];
       float* sg = p.sg + (size_t)pair * p.kp;
-      for (int i = tid; i < nloc; i += nt) {
-        float a = 0.f;
+      // (a service wave writes the rows itself, see below: its arrival then only waits for its own stores)
+      if (!svc) {
+        for (int i = tid; i < nloc; i += nt) {
+          float a = 0.f;
 #pragma unroll
-        for (int g = 0; g < G; ++g) a = fmaf(e_lds[i * G + g], rz[g], a);
-        if (UNIT)
-          s_lds[i] = (kv_i == 0) ? a : s_lds[i] + a;  // (entry i is always this thread's; heads in order)
-        else
-          st_agent(sg + i, a);
+          for (int g = 0; g < G; ++g) a = fmaf(e_lds[i * G + g], rz[g], a);
+          if (UNIT)
+            s_lds[i] = (kv_i == 0) ? a : s_lds[i] + a;  // (entry i is always this thread's; heads in order)
+          else
+            st_agent(sg + i, a);
+        }
       }
     }
-  } else {
+  } else if (!svc) {
     if (wave == 0) {  // wave-uniform: the stores and the counter update are this wave's alone
       if (lane < G) {
         float mg = m[0], zg = Z[0];
@@ -269,67 +289,197 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
         // they have long arrived.
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_s_waitcnt(0);
-        if (lane == 0) __hip_atomic_fetch_add(p.cnt_pub + pair, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (lane == 0) __hip_atomic_fetch_add(cnt_pub_p, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
   }
 
+  // The unit's finish by ONE wave (the service wave whose arrival completes the unit's count): head-mean score
+  // over the k+1 candidates (as a sum: the factor 1/H does not move the argmin), KV-head partials added in
+  // head order, lowest index on ties; then the log entries and the unit's state word.
+  auto finish_unit_wave = [&]() {
+    if (lane == 0) st_agent_i(p.cnt_unit + unit, 0);
+    const float* sgu = p.sg + (size_t)unit * p.H_kv * p.kp;
+    float best = INFINITY;
+    int bj = 0x7fffffff;
+    if (p.H_kv <= 2)
+      scan_scores<8, 2>(sgu, p.H_kv, p.kp, k, p.n_pinned, lane, 64, best, bj);
+    else if (p.H_kv <= 4)
+      scan_scores<8, 4>(sgu, p.H_kv, p.kp, k, p.n_pinned, lane, 64, best, bj);
+    else
+      scan_scores<4, 8>(sgu, p.H_kv, p.kp, k, p.n_pinned, lane, 64, best, bj);
+    wave_argmin(best, bj);
+    if (bj > k) bj = k;  // only reachable with non-finite scores
+    if (lane == 0) {
+      if (evp) st_agent_i(evp + unit, bj);
+      if (bj < k) st_agent_i(p.slot_token + (size_t)unit * k + bj, tok);
+      st_agent_i(p.occupancy + unit, k);
+      __builtin_amdgcn_s_waitcnt(0);  // (the counter's reset has landed before anyone can arrive again)
+      st_agent_u64(p.pstate + unit, ((unsigned long long)(uint32_t)bj << 32) | (uint32_t)(tok + 1));
+    }
+  };
+
+  // What the service wave does while the other waves are in the PV pass (called in the other branch of
+  // that pass, so that the registers of the V tiles are not live here).
+  auto service_wave_work = [&]() {
+    int ok = full ? 1 : 0;  // (the cache is full in every multi-step launch)
+    if (S == 1) {
+      if (ok) {
+        float rz[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) rz[g] = 1.0f / Z[g];
+        float* sg = p.sg + (size_t)pair * p.kp;
+        for (int i = lane; i < nloc; i += 64) {
+          float a = 0.f;
+#pragma unroll
+          for (int g = 0; g < G; ++g) a = fmaf(e_lds[i * G + g], rz[g], a);
+          st_agent(sg + i, a);
+        }
+      }
+    } else {
+      // the chunk's statistics, as wave 0 publishes them without a service wave
+      if (lane < G) {
+        float mg = m[0], zg = Z[0];
+#pragma unroll
+        for (int g = 1; g < G; ++g) {
+          mg = (lane == g) ? m[g] : mg;
+          zg = (lane == g) ? Z[g] : zg;
+        }
+        float* st = p.stats + (((size_t)pair * S + chunk) * G + lane) * 2;
+        st_agent(st, mg);
+        st_agent(st + 1, zg);
+      }
+      if (ok) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);
+        if (lane == 0) __hip_atomic_fetch_add(cnt_pub_p, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    if (ok && S > 1) {
+      // the siblings' statistics (they run at the same time on neighbouring CUs): a bounded look, else the
+      // block takes the route behind its PV pass as it does without a service wave
+      int seen = 0;
+      if (lane == 0) {
+        seen = ld_agent_i(cnt_pub_p);
+        for (int sp = 0; sp < p.spin_limit && seen != nact; ++sp) {
+          __builtin_amdgcn_s_sleep(16);
+          seen = ld_agent_i(cnt_pub_p);
+        }
+      }
+      seen = __builtin_amdgcn_readfirstlane(seen);
+      ok = (seen == nact && !p.force_slow) ? 1 : 0;
+      if (ok) {
+        for (int x = lane; x < nact * G * 2; x += 64) sl[x] = ld_agent(stp + x);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();  // (one wave: its LDS accesses are performed in order)
+        float f[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float mg = -INFINITY;
+          for (int c = 0; c < nact; ++c) mg = fmaxf(mg, sl[(c * G + g) * 2]);
+          float zg = 0.f;
+          for (int c = 0; c < nact; ++c)
+            zg += sl[(c * G + g) * 2 + 1] * __builtin_amdgcn_exp2f(sl[(c * G + g) * 2] - mg);
+          f[g] = __builtin_amdgcn_exp2f(sl[(chunk * G + g) * 2] - mg) / zg;
+        }
+        float* sg = p.sg + (size_t)pair * p.kp + r0;
+        for (int i = lane; i < nloc; i += 64) {
+          float a = 0.f;
+#pragma unroll
+          for (int g = 0; g < G; ++g) a = fmaf(e_lds[i * G + g], f[g], a);
+          st_agent(sg + i, a);
+        }
+      }
+    }
+    if (ok) {
+      // arrival at the unit's counter, once this wave's score rows have completed
+      const int expected = p.H_kv * nact;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __builtin_amdgcn_s_waitcnt(0);
+      int prev = 0;
+      if (expected > 1 && lane == 0)
+        prev = __hip_atomic_fetch_add(p.cnt_unit + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      prev = __builtin_amdgcn_readfirstlane(prev);
+      if (prev + 1 == expected) finish_unit_wave();
+    }
+    if (lane == 0) flag_lds[4] = ok;
+  };
+
   // ---------------- phase 3: PV ----------------
   float* red = big + p.red_off;  // [nw][G*D]; behind the exp values when they are still needed (S > 1)
+  // (the waves of the pass compute, all waves meet at the barrier after which the reduction area may reuse the
+  // memory of the exp values -- a service wave gets there when its own work is done --, then the waves of the
+  // pass write their sums)
+  const bool pv_wave = !SVC || wave < nws;  // wave-uniform
   if constexpr (PVM) {
     // Matrix cores (see pv_pass_mfma; the incoming token's row is added on the vector ALUs).
-    f32x4_t pacc[8];
-    pv_pass_mfma<T, D, G>(Vb, ncached, e_lds, G, 0, lane, wave, nw, vA, pacc);
-    pv_mfma_finish<T, D, G>(pacc, ncached, 1, new_here, [&](int) { return vnew; }, e_lds, G, 0, lane, wave, red);
+    float tot[4][4];
+    if (pv_wave) {
+      f32x4_t pacc[8];
+      pv_pass_mfma<T, D, G>(Vb, ncached, e_lds, G, 0, lane, wave, nws, vA, pacc);
+      pv_mfma_fold<T, D, G>(pacc, tot, ncached, 1, new_here_v, [&](int) { return vnew; }, e_lds, G, 0, lane);
+    } else {
+      service_wave_work();
+    }
+    __syncthreads();
+    if (pv_wave) pv_mfma_store<T, D, G>(tot, lane, wave, red);
   } else {
-  float acc[G][VEC];
-  pv_pass<T, D, G>(Vb, ncached, 1, new_here, [&](int) { return vnew; }, e_lds, G, 0, lane, wave, nw, vA, acc);
-  // combine the RV row groups of the wave, then the waves (in wave order)
-  if constexpr (LV == 16 && (G * VEC) % 4 == 0) {
-    // Four row groups of 16 lanes.  Transposing reduction: swapping rows between the registers of
-    // two different values and adding halves the number of live registers at each of the two
-    // stages (odd/even rows, then upper/lower half), and leaves the total of value 4 j + r in row
-    // r of register j -- so all 64 lanes, not 16, write the wave's result to LDS.
+    // combine the RV row groups of the wave, then the waves (in wave order)
+    constexpr bool TR = (LV == 16 && (G * VEC) % 4 == 0);
     constexpr int NV = G * VEC;
-    float b[NV / 2];
+    float acc[G][VEC];
+    float cr[TR ? NV / 4 : 1];
+    if (pv_wave) {
+      pv_pass<T, D, G>(Vb, ncached, 1, new_here_v, [&](int) { return vnew; }, e_lds, G, 0, lane, wave, nws, vA, acc);
+      if constexpr (TR) {
+        // Four row groups of 16 lanes.  Transposing reduction: swapping rows between the registers of
+        // two different values and adding halves the number of live registers at each of the two
+        // stages (odd/even rows, then upper/lower half), and leaves the total of value 4 j + r in row
+        // r of register j -- so all 64 lanes, not 16, write the wave's result to LDS.
+        float b[NV / 2];
 #pragma unroll
-    for (int j = 0; j < NV / 2; ++j) {
-      unsigned x = __builtin_bit_cast(unsigned, acc[(2 * j) / VEC][(2 * j) % VEC]);
-      unsigned y = __builtin_bit_cast(unsigned, acc[(2 * j + 1) / VEC][(2 * j + 1) % VEC]);
-      swap_rows16(x, y);  // x: rows 0,2 keep value 2j, rows 1,3 get value 2j+1 of the row below/above
-      b[j] = __builtin_bit_cast(float, x) + __builtin_bit_cast(float, y);
-    }
-    float c[NV / 4];
+        for (int j = 0; j < NV / 2; ++j) {
+          unsigned x = __builtin_bit_cast(unsigned, acc[(2 * j) / VEC][(2 * j) % VEC]);
+          unsigned y = __builtin_bit_cast(unsigned, acc[(2 * j + 1) / VEC][(2 * j + 1) % VEC]);
+          swap_rows16(x, y);  // x: rows 0,2 keep value 2j, rows 1,3 get value 2j+1 of the row below/above
+          b[j] = __builtin_bit_cast(float, x) + __builtin_bit_cast(float, y);
+        }
 #pragma unroll
-    for (int j = 0; j < NV / 4; ++j) {
-      unsigned x = __builtin_bit_cast(unsigned, b[2 * j]);
-      unsigned y = __builtin_bit_cast(unsigned, b[2 * j + 1]);
-      swap_rows32(x, y);
-      c[j] = __builtin_bit_cast(float, x) + __builtin_bit_cast(float, y);
-    }
-    __syncthreads();  // everyone is done reading e_lds; the reduction area reuses it
+        for (int j = 0; j < NV / 4; ++j) {
+          unsigned x = __builtin_bit_cast(unsigned, b[2 * j]);
+          unsigned y = __builtin_bit_cast(unsigned, b[2 * j + 1]);
+          swap_rows32(x, y);
+          cr[j] = __builtin_bit_cast(float, x) + __builtin_bit_cast(float, y);
+        }
+      } else {
 #pragma unroll
-    for (int j = 0; j < NV / 4; ++j) {
-      const int idx = 4 * j + rv;  // value index g * VEC + v held by this lane's row
-      red[(wave * G + idx / VEC) * D + lv * VEC + idx % VEC] = c[j];
-    }
-  } else {
+        for (int g = 0; g < G; ++g)
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) {
-        acc[g][v] = column_sum<LV>(acc[g][v]);
+          for (int v = 0; v < VEC; ++v) acc[g][v] = column_sum<LV>(acc[g][v]);
       }
-    __syncthreads();  // everyone is done reading e_lds; the reduction area reuses it
-    if (rv == 0) {
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) red[(wave * G + g) * D + lv * VEC + v] = acc[g][v];
+    } else {
+      service_wave_work();
     }
-  }
+    __syncthreads();  // everyone is done reading e_lds; the reduction area reuses it
+    if (pv_wave) {
+      if constexpr (TR) {
+#pragma unroll
+        for (int j = 0; j < NV / 4; ++j) {
+          const int idx = 4 * j + rv;  // value index g * VEC + v held by this lane's row
+          red[(wave * G + idx / VEC) * D + lv * VEC + idx % VEC] = cr[j];
+        }
+      } else if (rv == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) red[(wave * G + g) * D + lv * VEC + v] = acc[g][v];
+      }
+    }
   }
   __syncthreads();
+  // (with a service wave: its score rows are written and it has arrived at the unit's counter, unless it did
+  // not see the siblings' statistics in time)
+  const bool early = svc && flag_lds[4] != 0;  // block-uniform
 
   T* outb = reinterpret_cast<T*>(p.out) + (size_t)it * p.q_stride + ((size_t)unit * p.H + (size_t)kvh * G) * D;
   bool pair_last = true;  // this block completes its (unit, KV head)
@@ -341,7 +491,7 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
   auto store_out_single = [&]() {
     for (int x = tid; x < G * D; x += nt) {
       float a = red[x];
-      for (int w = 1; w < nw; ++w) a += red[w * G * D + x];
+      for (int w = 1; w < nws; ++w) a += red[w * G * D + x];
       // Z of head x / D; G is a compile-time constant so this is a select chain
       float zg = Z[0];
 #pragma unroll
@@ -362,16 +512,17 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
     float* ap = p.accp + (size_t)(tok & 1) * p.accp_half + ((size_t)pair * S + chunk) * (G * D);
     for (int x = tid; x < G * D; x += nt) {
       float a = red[x];
-      for (int w = 1; w < nw; ++w) a += red[w * G * D + x];
+      for (int w = 1; w < nws; ++w) a += red[w * G * D + x];
       st_agent(ap + x, a);
     }
-    if (full) {
+    if (early) have_stats = true;  // (sl was filled by the service wave)
+    if (full && !early) {
       // the siblings' statistics, and with them this chunk's score rows (see phase 2)
       if (tid == 0) {
-        int seen = ld_agent_i(p.cnt_pub + pair);
+        int seen = ld_agent_i(cnt_pub_p);
         for (int sp = 0; sp < p.spin_limit && seen != nact; ++sp) {  // bounded: then the slow route
           __builtin_amdgcn_s_sleep(16);
-          seen = ld_agent_i(p.cnt_pub + pair);
+          seen = ld_agent_i(cnt_pub_p);
         }
         flag_lds[0] = (seen == nact && !p.force_slow) ? 1 : 0;
       }
@@ -410,17 +561,19 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
     int n_slow = slow;
     if (nact > 1) {
       // arrivals in the low half of the counter, chunks that need the finisher's help in the high half
-      const int prev = arrive(p.cnt_pair + pair, 1 + (slow << 16), flag_lds, tid);
+      const int prev = arrive(cnt_pair_p, 1 + (slow << 16), flag_lds, tid);
       pair_last = ((prev & 0xffff) == nact - 1);
       n_slow += prev >> 16;
     } else {
       __syncthreads();
     }
-    unit_add = slow ? 0 : 1;
+    unit_add = (slow || early) ? 0 : 1;
     if (pair_last) {
       // ---- pair finisher: global normalisers (log2 domain) m_g = max_c m_c, Z_g = sum_c Z_c 2^(m_c - m_g)
-      reset_counter(p.cnt_pair + pair, tid);
-      reset_counter(p.cnt_pub + pair, tid);
+      if (tid == rst_tid) {
+        st_agent_i(cnt_pair_p, 0);
+        st_agent_i(cnt_pub_p, 0);
+      }
       if (!have_stats) {  // (below capacity, or a sibling had not published when this chunk looked)
         for (int x = tid; x < nact * G * 2; x += nt) sl[x] = ld_agent(stp + x);  // all in flight at once
         __syncthreads();
@@ -491,12 +644,15 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
     // knows that every score row is written and that nobody reads the unit's K/V any more.
     const int expected = p.H_kv * nact;
     bool unit_last = false;
-    if (expected == 1) {
+    if (S == 1 && early) unit_add = 0;
+    if (unit_add == 0) {
+      // (the service wave has arrived for this block, or the pair's last block will)
+    } else if (expected == 1) {
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       __builtin_amdgcn_s_waitcnt(0);
       __syncthreads();
       unit_last = true;
-    } else if (unit_add > 0) {
+    } else {
       const int prev = arrive(p.cnt_unit + unit, unit_add, flag_lds, tid);
       unit_last = (prev + unit_add == expected);
       if (unit_last) reset_counter(p.cnt_unit + unit, tid);
@@ -662,11 +818,12 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
 
 // Blocks of the step kernel that can be resident on the device at once.
 template <typename T, int D, int G>
-int resident_blocks_one(int block, int lds, int unit_mode) {
+int resident_blocks_one(int block, int lds, int form) {  // form: 0 hand-off, 1 workgroup per unit, 2 hand-off with a service wave
   int per_cu = 0, dev = 0, cus = 0;
   const hipError_t e =
-      unit_mode ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tova_step_kernel<T, D, G, true, true>, block, (size_t)lds)
-                : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tova_step_kernel<T, D, G, true, false>, block, (size_t)lds);
+      form == 1   ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tova_step_kernel<T, D, G, true, true>, block, (size_t)lds)
+      : form == 2 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tova_step_kernel<T, D, G, true, false, true>, block, (size_t)lds)
+                  : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tova_step_kernel<T, D, G, true, false>, block, (size_t)lds);
   if (e != hipSuccess)
     return 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
@@ -707,6 +864,8 @@ hipError_t launch_one(const StepParams& p, const LaunchPlan& lp, hipStream_t str
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((tova_step_kernel<T, D, G, true, true>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes, stream, p);
   }
+  else if (p.persistent && p.svc)
+    hipLaunchKernelGGL((tova_step_kernel<T, D, G, true, false, true>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes, stream, p);
   else if (p.persistent)
     hipLaunchKernelGGL((tova_step_kernel<T, D, G, true>), dim3(lp.grid), dim3(lp.block), lp.lds_bytes, stream, p);
   else
