@@ -30,9 +30,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # Bytes that left L2 per decode step of the step kernel on this workload, from rocprofv3 --pmc FETCH_SIZE
 # and WRITE_SIZE runs of this script (256 steps per launch), each scaled by what the same counter reads
 # for a 1 GiB copy kernel (summary: profiles/tova_step_kernel_c3_mistral_gqa.txt).  Not measured live.
-PROFILED_TRAFFIC_BYTES_PER_STEP = 274.0e6
+PROFILED_TRAFFIC_BYTES_PER_STEP = 274.2e6
 # ... and of the 32-layer variant (workgroup-per-unit form), profiles/tova_step_kernel_unit_c3_mistral_gqa_x32.txt
-PROFILED_TRAFFIC_BYTES_PER_STEP_X32 = 8648.8e6
+PROFILED_TRAFFIC_BYTES_PER_STEP_X32 = 8648.6e6
 
 
 def algorithmic_bytes_per_step(spec) -> int:
@@ -284,7 +284,8 @@ def main():
                                        "scaled by a 1 GiB copy); multiplied by steps_per_launch here",
                      "kernel": "tova_step_kernel<bf16, d=128, G=4, " +
                                ("workgroup per unit, " if g["plan"]["unit_workgroups"] else "") +
-                               ("multi-step>" if steps_per_launch > 1 else "per-step>"),
+                               ("multi-step, service wave>" if steps_per_launch > 1 and not g["plan"]["unit_workgroups"]
+                                else "multi-step>" if steps_per_launch > 1 else "per-step>"),
                      "steps_per_launch": steps_per_launch, "algorithmic_bytes_per_step": abytes,
                      "algorithmic_bytes_per_launch": abytes * steps_per_launch,
                      "avg_launch_us": ms_per_step * 1e3 * steps_per_launch,

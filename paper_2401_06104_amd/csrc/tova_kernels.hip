@@ -14,10 +14,10 @@
 // load covers whole, contiguous rows, and the G = H / H_kv query heads that share a KV head are
 // all served from the same streamed row (grouped-query attention reads K/V once, not G times).
 //
-//   phase 1  logits   l[i][g] = scale * q_g . K[i]      -> LDS   (vector ALU; matrix cores for
-//                                                                 bf16 groups of 8 heads and more)
+//   phase 1  logits   l[i][g] = scale * q_g . K[i]      -> LDS   (vector ALU; matrix cores for bf16
+//                                                                 groups of 8 heads, of 4 at d = 128)
 //   phase 2  softmax  m_g, e[i][g] = exp(l - m_g), Z_g  (chunk-local), score contributions
-//   phase 3  PV       acc_g = sum_i e[i][g] * V[i]
+//   phase 3  PV       acc_g = sum_i e[i][g] * V[i]               (likewise; see pv_pass_mfma)
 //   phase 4  combine  (a) per (unit, KV head): merge the chunks' (m, Z, acc) -> out
 //                     (b) per unit: sum the score partials over KV heads in fixed order, argmin
 //                         with lowest-index tie break, put the new row into the victim's slot,
@@ -30,6 +30,8 @@
 // softmax statistics (and leaves its score rows to the finisher if they are not there), and in a
 // multi-step launch a workgroup waits, with a limit and an error flag, for the victim of its own
 // unit's previous step.  Every wave reaches its exit whatever the scheduling order.
+// In multi-step launches the host may give a workgroup a service wave, which does the hand-off work
+// of phases 2 and 4(b) while the other waves are in phase 3 (see SVC in the kernel).
 //
 // The path is bound by HBM bandwidth (2*k*d*sizeof(elem) bytes per KV head and step against
 // 4*G*k*d flops).
