@@ -138,7 +138,7 @@ def gpu_leg(spec, seed, steps, warmup, device, chunk=256, prefill=False, also_pr
     multi = cache.multi_step_blocks
     plan = dict(multi_step_blocks=multi, n_splits=lay.n_splits, rows_per_split=lay.rows_per_split, block_threads=lay.block_threads,
                 grid_blocks=lay.grid_blocks, lds_bytes=lay.lds_bytes, unit_workgroups=int(lay.unit_workgroups),
-                prefill_group=int(lay.prefill_group))
+                prefill_group=int(lay.prefill_group), service_wave=int(lay.service_wave))
     prompt_ms = None
     if also_prompt:
         # the same tokens once more, handed over as a prompt (tova_prefill: groups of tokens share one
@@ -284,7 +284,7 @@ def main():
                                        "scaled by a 1 GiB copy); multiplied by steps_per_launch here",
                      "kernel": "tova_step_kernel<bf16, d=128, G=4, " +
                                ("workgroup per unit, " if g["plan"]["unit_workgroups"] else "") +
-                               ("multi-step, service wave>" if steps_per_launch > 1 and not g["plan"]["unit_workgroups"]
+                               ("multi-step, service wave>" if steps_per_launch > 1 and g["plan"]["service_wave"]
                                 else "multi-step>" if steps_per_launch > 1 else "per-step>"),
                      "steps_per_launch": steps_per_launch, "algorithmic_bytes_per_step": abytes,
                      "algorithmic_bytes_per_launch": abytes * steps_per_launch,

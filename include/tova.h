@@ -117,6 +117,9 @@ typedef struct {
   size_t h2o_acc_offset;    /* state_mem: float [L][B][k] (H2O only; with per_head [L][B][H_kv][k]): per slot,
                                the attention weights summed over the query heads and over all steps
                                since the slot's token came in (divide by H for the head average)   */
+  int32_t service_wave;     /* nonzero: in multi-step launches the last wave of a workgroup serves the hand-off
+                               between workgroups instead of streaming V (hand-off form only; a tuning
+                               decision of the library, reported for the record)                     */
 } tova_layout_t;
 
 /* Sizes of the three caller-owned DEVICE buffers.  kv_bytes is exactly

@@ -37,7 +37,8 @@ class TovaLayout(ctypes.Structure):
     _fields_ = [("k_offset", c_size_t), ("v_offset", c_size_t), ("occupancy_offset", c_size_t),
                 ("slot_token_offset", c_size_t), ("error_flag_offset", c_size_t), ("n_splits", c_int32), ("rows_per_split", c_int32),
                 ("block_threads", c_int32), ("grid_blocks", c_int32), ("lds_bytes", c_int32),
-                ("unit_workgroups", c_int32), ("prefill_group", c_int32), ("tokens_seen_offset", c_size_t), ("h2o_acc_offset", c_size_t)]
+                ("unit_workgroups", c_int32), ("prefill_group", c_int32), ("tokens_seen_offset", c_size_t), ("h2o_acc_offset", c_size_t),
+                ("service_wave", c_int32)]
 
 
 def library_path() -> str:

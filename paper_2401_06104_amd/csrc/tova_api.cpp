@@ -370,6 +370,7 @@ int tova_cache_layout(const tova_config_t* cfg, tova_layout_t* layout) {
   layout->grid_blocks = r.grid;
   layout->lds_bytes = r.lds;
   layout->unit_workgroups = r.unit_mode;
+  layout->service_wave = (!r.unit_mode && r.svc && r.NT >= 128) ? 1 : 0;
   layout->prefill_group = r.pf_C;
   layout->h2o_acc_offset = r.acc_off;
   layout->tokens_seen_offset = r.tok_off;
