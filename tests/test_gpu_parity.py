@@ -69,6 +69,12 @@ SWEEP = [
     ("bf16", 32, 8, 2, 77, 200, 1, 5, 0),
     ("bf16", 128, 2, 1, 640, 900, 1, 9, 2),     # more units than one XCD round
     ("bf16", 64, 8, 8, 48, 120, 8, 40, 1),      # 320 units: a workgroup per unit (see the tests further down)
+    # the matrix-core PV pass (bf16, d = 128, 8 or 4 heads per KV head): capacities below one 32-row tile,
+    # one row past a tile, tiles split over chunks
+    ("bf16", 128, 16, 2, 31, 200, 1, 2, 0),
+    ("bf16", 128, 8, 2, 33, 200, 2, 2, 2),
+    ("bf16", 128, 16, 2, 97, 300, 1, 2, 3),
+    ("bf16", 128, 12, 3, 5, 80, 1, 2, 0),
 ]
 
 
@@ -229,6 +235,31 @@ def test_split_finisher_handles_every_chunk(dtype, d, H, H_kv, k, T, L, B, split
         assert all(s["mismatches"] == 0 for s in stats)
 
 
+@pytest.mark.parametrize("dtype,d,H,H_kv,k,T,L,B,splits,slow", [
+    ("f32", 64, 8, 4, 100, 300, 1, 2, 1, 0),       # vector passes, one chunk per KV head
+    ("f32", 32, 4, 4, 37, 150, 2, 3, 3, 0),        # split cache: the service wave fetches the siblings' statistics
+    ("bf16", 128, 32, 8, 300, 520, 1, 3, 1, 0),    # matrix-core passes (the shape class the host turns it on for)
+    ("bf16", 128, 32, 4, 513, 700, 2, 1, 5, 0),    # 8 heads per KV head, split cache
+    ("bf16", 128, 16, 4, 130, 330, 1, 2, 4, 1),    # ... and the service wave told that the statistics are not there
+    ("bf16", 64, 8, 8, 1, 40, 1, 2, 1, 0),         # capacity 1
+])
+def test_service_wave_shape_sweep(dtype, d, H, H_kv, k, T, L, B, splits, slow, monkeypatch):
+    """Multi-step launches of the hand-off form with a service wave (TOVA_SERVICE_WAVE=1 turns it on whatever
+    the shape), against the oracle: the last wave of a workgroup writes the score rows, arrives for the
+    workgroup and finishes the unit beside the PV pass of the others."""
+    monkeypatch.setenv("TOVA_SERVICE_WAVE", "1")
+    monkeypatch.setenv("TOVA_UNIT_MODE", "0")
+    if slow:
+        monkeypatch.setenv("TOVA_FORCE_SLOW_MERGE", "1")
+    spec = StreamSpec(f"service_{dtype}_d{d}_h{H}_{H_kv}_k{k}", L=L, B=B, H=H, H_kv=H_kv, d=d, dtype=dtype,
+                      k=k, T=T, sink="first", n_sinks=2)
+    units = [(l, b) for l in range(L) for b in range(B)][:3]
+    stats, res = _run(spec, seed=700 + k, units=units, n_splits=splits, workers=3)
+    assert res["layout"][0] == splits and res["unit_workgroups"] == 0
+    if dtype == "f32":
+        assert all(s["mismatches"] == 0 for s in stats)
+
+
 # ---- a workgroup per unit --------------------------------------------------------------------
 UNIT_SWEEP = [
     # dtype, d, H, H_kv, k, T, L, B
@@ -239,6 +270,8 @@ UNIT_SWEEP = [
     ("bf16", 128, 8, 8, 1025, 1300, 1, 2),
     ("bf16", 64, 16, 2, 130, 300, 2, 2),        # wide bf16 groups: matrix-core logit pass
     ("bf16", 32, 8, 2, 77, 200, 1, 5),
+    ("bf16", 128, 16, 2, 70, 250, 1, 3),        # 8 heads per KV head: logit and PV passes on the matrix cores
+    ("bf16", 128, 8, 2, 5, 60, 1, 2),           # 4 heads per KV head, capacity below a tile
 ]
 
 
