@@ -159,7 +159,8 @@ int tova_decode_step(tova_cache_t* cache, const void* q, const void* k_new, cons
 /* n_steps consecutive decode steps (Sec. 3.2 + Sec. 4, App. B Alg. 1 once per step: the loop an
  * autoregressive decoder runs over its bounded multi-state) with inputs resident in device memory:
  * the arrays of tova_decode_step with a leading [n_steps] dimension
- * (evicted: [n_steps][L][B], may be NULL).  Same results as n_steps calls.
+ * (evicted: [n_steps][L][B], may be NULL).  Same victims and cache contents as n_steps calls; `out`
+ * agrees to the rounding of fp32 sums (the rows may be added in another order).
  * Once the cache is full the remaining steps of a call run in ONE launch.
  *  - With L * B >= 256 units and one chunk per KV head (layout: unit_workgroups != 0) a workgroup
  *    owns whole units: it goes through a unit's KV heads in turn, keeps the head-summed scores in
@@ -175,7 +176,8 @@ int tova_decode_step(tova_cache_t* cache, const void* q, const void* k_new, cons
  *    tova_cache_status reports the condition, tova_cache_recover takes the cache back into
  *    service from a snapshot the caller restores (see there).
  * The environment variable TOVA_MULTI_STEP=0 keeps one launch per step; TOVA_UNIT_MODE=0 / 1
- * (read by tova_cache_init / tova_cache_layout) overrides the choice between the two forms. */
+ * (read by tova_cache_init / tova_cache_layout) overrides the choice between the two forms,
+ * TOVA_SERVICE_WAVE=0 / 1 the use of a service wave (layout: service_wave). */
 int tova_decode_steps(tova_cache_t* cache, int32_t n_steps, const void* q, const void* k_new,
                       const void* v_new, void* out, int32_t* evicted, void* hip_stream);
 
