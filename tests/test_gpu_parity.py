@@ -869,6 +869,62 @@ def test_multi_step_wait_runs_out_and_the_cache_recovers(monkeypatch):
     cache.destroy()
 
 
+def test_split_cache_statistics_survive_a_broken_token_sequence(monkeypatch):
+    """The chunks of a split cache leave their softmax statistics in scratch memory in two copies that
+    alternate with the token's parity, and a step zeroes what the next one will look at.  When the step
+    kernel does not see consecutive tokens -- the caller rolls back to a snapshot, or sets the token count
+    two steps on, so that a step meets the copy an abandoned step filled -- the library has to start the
+    area from zero.  A stream is stepped with such breaks (rolled back twice, at an even and an odd
+    distance, onto a restored snapshot) and must give exactly what an unbroken twin gives; two sequences
+    are followed by the oracle."""
+    from paper_2401_06104_amd import TovaCache
+    from workloads import Stream
+    monkeypatch.setenv("TOVA_UNIT_MODE", "0")
+    spec = StreamSpec("broken_sequence", L=2, B=2, H=16, H_kv=2, d=128, dtype="bf16", k=96, T=96 + 90, sink="first",
+                      n_sinks=2)
+    c = Stream(spec, 21, device="cuda:0").chunk(0, spec.T)
+    runs = []
+    for broken in (False, True):
+        cache = TovaCache(spec.L, spec.B, spec.k, spec.H, spec.H_kv, spec.d, dtype=spec.dtype, n_splits=3)
+        assert cache.layout.n_splits == 3
+        out = torch.empty_like(c["q"])
+        ev = torch.full((spec.T, spec.L, spec.B), -7, dtype=torch.int32, device="cuda:0")
+
+        def steps(a, b, o=out, e=ev):
+            cache.decode_steps(c["q"][a:b], c["k"][a:b], c["v"][a:b], o[a:b], e[a:b])
+
+        if not broken:
+            steps(0, spec.T)
+        else:
+            scrap_o, scrap_e = torch.empty_like(out), torch.empty_like(ev)
+            a = spec.k + 20
+            steps(0, a)
+            for ahead in (7, 4):                     # abandoned futures of odd and of even length
+                snap_kv, snap_state = cache.kv_mem.clone(), cache.state_mem.clone()
+                steps(a, a + ahead, scrap_o, scrap_e)
+                cache.kv_mem.copy_(snap_kv); cache.state_mem.copy_(snap_state)
+                cache.set_tokens_seen(a)
+                steps(a, a + 11)                     # multi-step launch
+                a += 11
+                steps(a, a + 1)                      # one launch per step
+                a += 1
+            steps(a, spec.T)
+        torch.cuda.synchronize()
+        assert cache.status() == 0 and cache.tokens_seen == spec.T
+        runs.append((out.cpu(), ev.cpu(), cache.slot_token.cpu().clone(), cache.K.cpu().clone(), cache.V.cpu().clone()))
+        if broken:
+            units = [(0, 1), (1, 0)]
+            ul, ub = [u[0] for u in units], [u[1] for u in units]
+            res = {"out": out[:, ul, ub].float().cpu().numpy(), "evicted": ev.cpu().numpy(),
+                   "slot_token": cache.slot_token.cpu().numpy(), "K": cache.K[ul, ub].float().cpu().numpy(),
+                   "V": cache.V[ul, ub].float().cpu().numpy()}
+            for s_ in parity.check_units(spec, 21, units, res, workers=2):
+                print(f"[parity]   {s_}", flush=True)
+        cache.destroy()
+    for x, y in zip(*runs):
+        assert torch.equal(x, y)
+
+
 # ---- one recorded step, replayed for token after token ------------------------------------------
 @pytest.mark.parametrize("unit_mode,splits", [("0", 1), ("0", 3), ("1", 1)])
 def test_decode_step_graph_replays(unit_mode, splits, monkeypatch):
