@@ -630,7 +630,8 @@ __device__ __forceinline__ void pv_pass(const T* Vb, int nrows, int n_own, bool 
   }
 }
 
-// PV pass on the matrix cores (bf16, d = 128, 8 heads per KV head).  With V stored row by row the
+// PV pass on the matrix cores (bf16, d = 128, NH = 8 or 4 columns per streamed row; with 4, rows 4 .. 7
+// and 12 .. 15 of the weight operand stay zero).  With V stored row by row the
 // contraction index (the slot) is not contiguous in memory, but it can be made contiguous in a
 // lane's registers without any cross-lane traffic: lane l takes the SAME 16-byte column chunk
 // (l % 16) of eight DIFFERENT rows (tile row (l / 16) * 8 + i for load i), so a wave-level load
