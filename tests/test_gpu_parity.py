@@ -242,6 +242,8 @@ def test_split_finisher_handles_every_chunk(dtype, d, H, H_kv, k, T, L, B, split
     ("bf16", 128, 32, 4, 513, 700, 2, 1, 5, 0),    # 8 heads per KV head, split cache
     ("bf16", 128, 16, 4, 130, 330, 1, 2, 4, 1),    # ... and the service wave told that the statistics are not there
     ("bf16", 64, 8, 8, 1, 40, 1, 2, 1, 0),         # capacity 1
+    ("f32", 128, 8, 1, 257, 420, 1, 2, 1, 0),      # one KV head, one chunk: the workgroup is its unit's only arrival
+    ("bf16", 128, 4, 1, 200, 380, 2, 1, 3, 0),     # one KV head, three chunks
 ])
 def test_service_wave_shape_sweep(dtype, d, H, H_kv, k, T, L, B, splits, slow, monkeypatch):
     """Multi-step launches of the hand-off form with a service wave (TOVA_SERVICE_WAVE=1 turns it on whatever
