@@ -290,7 +290,7 @@ int resolve(const tova_config_t* c, Resolved* r) {
 
   size_t off = 0;
   r->cnt_pair_off = off; off += round_up((size_t)r->pairs * 2 * 4, kAlign);  // (two copies, by token parity)
-  r->cnt_unit_off = off; off += round_up((size_t)r->units * 4, kAlign);
+  r->cnt_unit_off = off; off += round_up((size_t)r->units * 2 * 4, kAlign);  // (two copies in the step kernel; the others use the first)
   r->cnt_pub_off = off; off += round_up((size_t)r->pairs * 2 * 4, kAlign);
   r->slow_off = off; off += round_up((size_t)r->pairs * S * 4, kAlign);
   r->pstate_off = off; off += round_up((size_t)r->units * 8, kAlign);

@@ -31,7 +31,7 @@ struct StepParams {
   float* accp;         // [2][pairs][S][G][d] chunk-local PV partials, by token parity (S > 1 only)
   int64_t accp_half;   // floats per parity copy
   int32_t* cnt_pair;   // [2][pairs] arrival counters (by token parity), zero between launches
-  int32_t* cnt_unit;   // [units]
+  int32_t* cnt_unit;   // [2][units] (by token parity)
   int32_t* cnt_pub;    // [2][pairs] chunks that have published their softmax statistics (S > 1 only)
   int32_t* slow_flag;  // [pairs][S] chunk left its exp values in escr for the finisher (S > 1 only)
   int32_t st_off;      // float offset, inside the big LDS area, of the chunk-statistics area (S > 1)

@@ -159,6 +159,14 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
     __syncthreads();
     if (flag_lds[2] == 0) return;  // block-uniform
     const int vic = flag_lds[3];
+    // The log entries of that step are written here, by the workgroup that has the unit's first KV head and
+    // first chunk: always the same thread, so entries of one slot in successive steps stay in order, and the
+    // unit's finisher can publish the victim without waiting for any store of its own.
+    if (tid == 0 && chunk == 0 && pair == unit * p.H_kv) {
+      if (p.evicted) p.evicted[(size_t)(it - 1) * (p.pairs / p.H_kv) + unit] = vic;
+      if (vic < k) p.slot_token[(size_t)unit * k + vic] = tok - 1;
+      p.occupancy[unit] = k;
+    }
     if (vic >= r0 && vic < r1 && tid < ROW16) {  // (vic == k: the incoming token was dropped) the chunk that owns the slot
       const T* kprev = reinterpret_cast<const T*>(p.k_new) + (size_t)(it - 1) * p.kv_stride + (size_t)pair * D;
       const T* vprev = reinterpret_cast<const T*>(p.v_new) + (size_t)(it - 1) * p.kv_stride + (size_t)pair * D;
@@ -201,6 +209,7 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
   // the pair's counters alternate with the token's parity (a block of the unit's next step may already count
   // on one copy while this step's last block still resets the other)
   int32_t* const cnt_pair_p = p.cnt_pair + (size_t)(tok & 1) * p.pairs + pair;
+  int32_t* const cnt_unit_p = p.cnt_unit + (size_t)(tok & 1) * (p.pairs / p.H_kv) + unit;  // (likewise the unit's)
   int32_t* const cnt_pub_p = p.cnt_pub + (size_t)(tok & 1) * p.pairs + pair;
   const int rst_tid = svc ? (nw - 1) * 64 : 0;  // who resets counters: with a service wave its first lane, whose
                                                 // own wait for its stores precedes the unit's next arrival
@@ -300,7 +309,9 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
   // over the k+1 candidates (as a sum: the factor 1/H does not move the argmin), KV-head partials added in
   // head order, lowest index on ties; then the log entries and the unit's state word.
   auto finish_unit_wave = [&]() {
-    if (lane == 0) st_agent_i(p.cnt_unit + unit, 0);
+    // (the reset lands before anyone counts on this copy again, two steps on: this wave waits for its stores
+    // before it arrives in the unit's next step)
+    if (lane == 0) st_agent_i(cnt_unit_p, 0);
     const float* sgu = p.sg + (size_t)unit * p.H_kv * p.kp;
     float best = INFINITY;
     int bj = 0x7fffffff;
@@ -312,13 +323,8 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
       scan_scores<4, 8>(sgu, p.H_kv, p.kp, k, p.n_pinned, lane, 64, best, bj);
     wave_argmin(best, bj);
     if (bj > k) bj = k;  // only reachable with non-finite scores
-    if (lane == 0) {
-      if (evp) st_agent_i(evp + unit, bj);
-      if (bj < k) st_agent_i(p.slot_token + (size_t)unit * k + bj, tok);
-      st_agent_i(p.occupancy + unit, k);
-      __builtin_amdgcn_s_waitcnt(0);  // (the counter's reset has landed before anyone can arrive again)
-      st_agent_u64(p.pstate + unit, ((unsigned long long)(uint32_t)bj << 32) | (uint32_t)(tok + 1));
-    }
+    // (the log entries are written by the unit's first workgroup when it reads this word)
+    if (lane == 0) st_agent_u64(p.pstate + unit, ((unsigned long long)(uint32_t)bj << 32) | (uint32_t)(tok + 1));
   };
 
   // What the service wave does while the other waves are in the PV pass (called in the other branch of
@@ -400,7 +406,7 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
       __builtin_amdgcn_s_waitcnt(0);
       int prev = 0;
       if (expected > 1 && lane == 0)
-        prev = __hip_atomic_fetch_add(p.cnt_unit + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        prev = __hip_atomic_fetch_add(cnt_unit_p, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       prev = __builtin_amdgcn_readfirstlane(prev);
       if (prev + 1 == expected) finish_unit_wave();
     }
@@ -655,9 +661,11 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
       __syncthreads();
       unit_last = true;
     } else {
-      const int prev = arrive(p.cnt_unit + unit, unit_add, flag_lds, tid);
+      const int prev = arrive(cnt_unit_p, unit_add, flag_lds, tid);
       unit_last = (prev + unit_add == expected);
-      if (unit_last) reset_counter(p.cnt_unit + unit, tid);
+      // (lands before anyone counts on this copy again, two steps on: every wave of this block waits for its
+      // stores at the top of the unit's next step, before the block can arrive there)
+      if (unit_last) reset_counter(cnt_unit_p, tid);
     }
     if (S == 1) store_out_single();
     if (unit_last) {
@@ -698,17 +706,14 @@ __global__ __launch_bounds__(512, (G >= 8) ? ((MULTI && !UNIT) ? 2 : 3) : (PvMfm
         }
       }
       if (tid == 0) {
-        // (written through: in a multi-step launch the finishers of successive steps sit on
-        // different XCDs, and a slot's entry may be rewritten a few steps later)
-        if (evp) st_agent_i(evp + unit, bj);
-        if (bj < k) st_agent_i(p.slot_token + (size_t)unit * k + bj, tok);
-        st_agent_i(p.occupancy + unit, k);
         if (MULTI) {
-          // Multi-step launch: publish the victim; every block stores the row of its own KV head
-          // when it comes back to the pair.  The arrival counter's reset must have landed before
-          // anyone can arrive again.
-          __builtin_amdgcn_s_waitcnt(0);
+          // Multi-step launch: publish the victim, at once; every block stores the row of its own KV head
+          // when it comes back to the pair, and the unit's first block writes the log entries then.
           st_agent_u64(p.pstate + unit, ((unsigned long long)(uint32_t)bj << 32) | (uint32_t)(tok + 1));
+        } else {
+          if (evp) evp[unit] = bj;
+          if (bj < k) p.slot_token[(size_t)unit * k + bj] = tok;
+          p.occupancy[unit] = k;
         }
       }
     }
