@@ -262,6 +262,42 @@ def test_service_wave_shape_sweep(dtype, d, H, H_kv, k, T, L, B, splits, slow, m
         assert all(s["mismatches"] == 0 for s in stats)
 
 
+def test_random_shapes_and_launch_knobs_against_the_oracle(monkeypatch, say):
+    """Thirty seeded random cases: head dimension, heads per KV head, KV heads, capacities around the tile sizes,
+    dtype, forced split counts, calls of 7 / 50 / 256 steps, and the library's launch choices overridden at
+    random (service wave, workgroup per unit, one launch per step, the route through scratch memory) -- every
+    one followed by the oracle on up to three units."""
+    import random
+    rng = random.Random(5)
+    knobs = ("TOVA_SERVICE_WAVE", "TOVA_UNIT_MODE", "TOVA_MULTI_STEP", "TOVA_FORCE_SLOW_MERGE")
+    for case in range(30):
+        d = rng.choice([32, 64, 128, 128]); G = rng.choice([1, 2, 4, 4, 8, 8]); H_kv = rng.choice([1, 2, 3, 4, 8])
+        k = rng.choice([1, 2, 5, 16, 31, 32, 33, 64, 65, 100, 129, 257, 300]); T = k + rng.randint(10, 120)
+        L = rng.choice([1, 2]); B = rng.choice([1, 2, 3]); dtype = rng.choice(["f32", "bf16", "bf16"])
+        splits = rng.choice([0, 1, 1, 2, 3, 5])
+        env = dict(zip(knobs, (rng.choice(["0", "1", None]), rng.choice(["0", "0", "1", None]),
+                               rng.choice(["1", "1", "0"]), rng.choice([None, None, "1"]))))
+        if env["TOVA_UNIT_MODE"] == "1":
+            splits = 1
+        for name, v in env.items():
+            if v is None:
+                monkeypatch.delenv(name, raising=False)
+            else:
+                monkeypatch.setenv(name, v)
+        chunk = rng.choice([7, 50, 256])
+        spec = StreamSpec(f"random_{case}", L=L, B=B, H=G * H_kv, H_kv=H_kv, d=d, dtype=dtype, k=k, T=T, sink="first",
+                          n_sinks=min(2, k))
+        units = [(l, b) for l in range(L) for b in range(B)][:3]
+        what = (f"case {case}: d={d} G={G} H_kv={H_kv} k={k} T={T} L={L} B={B} {dtype} splits={splits} "
+                f"steps per call {chunk} {env}")
+        res = parity.run_gpu(spec, 2000 + case, units, n_splits=splits, chunk_steps=chunk)
+        parity.check_global_invariants(spec, res)
+        stats = parity.check_units(spec, 2000 + case, units, res, workers=3)
+        if dtype == "f32":
+            assert all(s_["mismatches"] == 0 for s_ in stats), what
+        say(f"[parity] {what}: plan {res['layout']}, max rel err {max(s_['max_rel_err'] for s_ in stats):.2e}")
+
+
 # ---- a workgroup per unit --------------------------------------------------------------------
 UNIT_SWEEP = [
     # dtype, d, H, H_kv, k, T, L, B
