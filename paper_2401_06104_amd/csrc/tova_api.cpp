@@ -268,8 +268,11 @@ int resolve(const tova_config_t* c, Resolved* r) {
   // enough for one wave to scan (GQA 32/8: k = 512 20.8 -> 19.7, k = 1024 36.9 -> 35.6, k = 2048 91.0 -> 91.0;
   // 16/4 x 128 sequences 36.6 -> 36.3), and costs where a wave is a larger share of the PV pass's loads in
   // flight or the rows are many (32 heads MHA x 32 layers, k = 512: 42.3 -> 45.6; one layer: 13.0 -> 16.3;
-  // GQA 32/16 90.5 -> 92.5; split cache, config 5: 44.6 -> 51.0; 8 heads per KV head x 128 units, k = 1024: 36.8 -> 37.8).
-  r->svc = (!r->unit_mode && r->S == 1 && wide && G == 4 && (long long)r->H_kv * (k + 1) <= 12 * 1024) ? 1 : 0;
+  // GQA 32/16 90.5 -> 92.5; split cache, config 5: 44.6 -> 51.0).  8 heads per KV head: 32/4 x 128 units at
+  // k = 256 / 512 / 768 / 1024 17.4 -> 16.6 / 21.7 -> 20.3 / 29.3 -> 26.9 / 36.8 -> 37.3, x 192 units at k = 1024
+  // 70.2 -> 63.5, 64/8 x 64 units at k = 512 / 1024 22.2 -> 20.4 / 37.5 -> 36.5: on.
+  r->svc = (!r->unit_mode && r->S == 1 && r->bf16 && r->D == 128 && (G == 4 || G == 8) &&
+            (long long)r->H_kv * (k + 1) <= 12 * 1024) ? 1 : 0;
   if (const char* e = std::getenv("TOVA_SERVICE_WAVE")) r->svc = (std::atoi(e) != 0);  // tuning aid / test hook
   r->persist_spin = 1 << 22;  // polls of ~0.2 us or more each: seconds, i.e. "something is broken"
   if (const char* e = std::getenv("TOVA_MULTI_STEP_SPIN")) {  // test hook: make the wait run out

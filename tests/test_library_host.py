@@ -103,9 +103,9 @@ def test_launch_plan(c, expect_S):
         assert lay.unit_workgroups == 0 and lay.grid_blocks == (pairs + 7) // 8 * 8 * S
     assert lay.block_threads in (256, 512)
     G = c.n_q_heads // c.n_kv_heads
-    # the service wave: hand-off form, one chunk per KV head, four heads per KV head at bf16 / d = 128, rows
-    # that one wave can scan
-    want_service = (not lay.unit_workgroups and S == 1 and G == 4 and c.dtype == TOVA_BF16 and c.head_dim == 128
+    # the service wave: hand-off form, one chunk per KV head, four or eight heads per KV head at bf16 / d = 128,
+    # rows that one wave can scan
+    want_service = (not lay.unit_workgroups and S == 1 and G in (4, 8) and c.dtype == TOVA_BF16 and c.head_dim == 128
                     and c.n_kv_heads * (k + 1) <= 12 * 1024)
     assert bool(lay.service_wave) == want_service
     if want_service:
