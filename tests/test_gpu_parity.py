@@ -263,14 +263,14 @@ def test_service_wave_shape_sweep(dtype, d, H, H_kv, k, T, L, B, splits, slow, m
 
 
 def test_random_shapes_and_launch_knobs_against_the_oracle(monkeypatch, say):
-    """Thirty seeded random cases: head dimension, heads per KV head, KV heads, capacities around the tile sizes,
+    """Twenty seeded random cases: head dimension, heads per KV head, KV heads, capacities around the tile sizes,
     dtype, forced split counts, calls of 7 / 50 / 256 steps, and the library's launch choices overridden at
     random (service wave, workgroup per unit, one launch per step, the route through scratch memory) -- every
     one followed by the oracle on up to three units."""
     import random
     rng = random.Random(5)
     knobs = ("TOVA_SERVICE_WAVE", "TOVA_UNIT_MODE", "TOVA_MULTI_STEP", "TOVA_FORCE_SLOW_MERGE")
-    for case in range(30):
+    for case in range(20):
         d = rng.choice([32, 64, 128, 128]); G = rng.choice([1, 2, 4, 4, 8, 8]); H_kv = rng.choice([1, 2, 3, 4, 8])
         k = rng.choice([1, 2, 5, 16, 31, 32, 33, 64, 65, 100, 129, 257, 300]); T = k + rng.randint(10, 120)
         L = rng.choice([1, 2]); B = rng.choice([1, 2, 3]); dtype = rng.choice(["f32", "bf16", "bf16"])
